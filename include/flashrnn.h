@@ -1,0 +1,125 @@
+/*
+ * flashrnn.h -- C ABI of the MI355X (gfx950) FlashRNN time-step loop.
+ *
+ * One library, two compute entry points: flashrnn_fwd runs the strictly sequential, head-wise
+ * block-diagonal recurrence for all T steps in one persistent kernel, flashrnn_bwd runs
+ * back-propagation through time and the weight-gradient reduction.
+ *
+ * Conventions for every function below
+ *   - All tensor pointers are DEVICE pointers owned by the caller; the library never allocates or
+ *     frees device memory and keeps no state between calls.
+ *   - Calls are asynchronous on the HIP stream passed as `hip_stream` (a hipStream_t cast to void*,
+ *     NULL = the default stream).  Buffers must stay valid until the stream has drained.
+ *   - All tensors are dense, row major, in the layouts written next to each argument.
+ *   - Return value: FLASHRNN_OK (0) or a negative flashrnn_status_t.  Nothing is thrown.
+ *   - Calls that share a workspace must not overlap in time.
+ *
+ * Index names:  T time steps, B batch, NH heads, D units per head, G gates, S states.
+ *   Gate order on the G axis:  LSTM, sLSTM: i, f, z, o     GRU: r, z, n
+ *   State order on the S axis: LSTM: h, c     GRU: h     sLSTM: h, c, n, m   (paper App. A)
+ */
+#ifndef FLASHRNN_H
+#define FLASHRNN_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { FLASHRNN_LSTM = 0, FLASHRNN_GRU = 1, FLASHRNN_SLSTM = 2 } flashrnn_cell_t;
+typedef enum { FLASHRNN_F32 = 0, FLASHRNN_BF16 = 1 } flashrnn_dtype_t;
+
+typedef enum {
+    FLASHRNN_OK = 0,
+    FLASHRNN_ERR_NULL = -1,        /* a required pointer is NULL                                   */
+    FLASHRNN_ERR_SHAPE = -2,       /* T < 0, or B, NH, D <= 0, or unknown cell / dtype             */
+    FLASHRNN_ERR_UNSUPPORTED = -3, /* D not a multiple of 16, or the head does not fit the chip    */
+    FLASHRNN_ERR_WORKSPACE = -4,   /* workspace missing or misaligned (needs 256-byte alignment)   */
+    FLASHRNN_ERR_LAUNCH = -5,      /* a HIP call failed                                            */
+    FLASHRNN_ERR_TIMEOUT = -6      /* a cross-CU wait gave up (reported by flashrnn_check)         */
+} flashrnn_status_t;
+
+/*
+ * Problem description.  io_dtype is the type of Wx, R, b, dH and dWx (bf16 or f32).  States, dR, db
+ * and dstates0 are always f32.  With bf16 I/O the recurrent product runs on the bf16 matrix cores
+ * with f32 accumulation and h (forward) / the gate gradients (backward) are rounded to bf16 as
+ * its operand; with f32 I/O it runs on the f32 matrix cores.
+ */
+typedef struct {
+    int cell;     /* flashrnn_cell_t  */
+    int T, B, NH, D;
+    int io_dtype; /* flashrnn_dtype_t */
+} flashrnn_desc_t;
+
+/* Number of states / gates of a cell (paper App. A): LSTM 2 / 4, GRU 1 / 3, sLSTM 4 / 4; -1 if unknown. */
+int flashrnn_num_states(int cell);
+int flashrnn_num_gates(int cell);
+
+/*
+ * Size in bytes of the opaque buffer the forward pass fills for the backward pass (the "gates
+ * written out for the backward pass" of Alg. 1), and of the scratch workspace both passes need
+ * (cross-CU exchange buffers and flags, GRU recurrent-side gate gradients, split-K partial sums).
+ * Both return 0 for an invalid descriptor.  The workspace content need not be preserved between
+ * calls; it must be 256-byte aligned.
+ */
+size_t flashrnn_gate_cache_bytes(const flashrnn_desc_t* desc);
+size_t flashrnn_workspace_bytes(const flashrnn_desc_t* desc);
+
+/*
+ * Forward pass (paper Sec. 3 eq. (1)-(2), Alg. 1):
+ *     g_t = Wx_t + R s0_{t-1} + b ;   s_t = P(s_{t-1}, g_t)      for t = 1..T, every head and batch row.
+ *   Wx       [T,B,G,NH,D] io_dtype  input pre-activations (the input projection W x is the caller's)
+ *   R        [NH,D,G,D]   io_dtype  recurrent weights; first D = previous-state index (contracted),
+ *                                   last D = unit the gate belongs to
+ *   b        [NH,G,D]     io_dtype  bias
+ *   states0  [S,B,NH,D]   f32       initial states, or NULL for zeros
+ *   states   [T+1,S,B,NH,D] f32     OUT: slot 0 = initial states, slot t = states after step t
+ *   gate_cache  flashrnn_gate_cache_bytes() bytes, OUT, or NULL for a forward-only call
+ *   workspace   flashrnn_workspace_bytes() bytes (may be NULL when that size is 0)
+ */
+int flashrnn_fwd(const flashrnn_desc_t* desc, const void* Wx, const void* R, const void* b, const void* states0,
+                 void* states, void* gate_cache, void* workspace, void* hip_stream);
+
+/*
+ * Backward pass, BPTT (paper Sec. 4 eq. (3)-(7)), with L depending on h_1..h_T through dH and on the
+ * final states through dstates_last:
+ *     dg_t = dP/dg ds_t ;  ds_{t-1} = dP/ds ds_t (+ R^T dg_t on the hidden state) ;
+ *     dWx_t = dg_t ;  db = sum_t dg_t ;  dR = sum_t s0_{t-1} (x) dg_t
+ *   R, b        as in the forward call
+ *   states      [T+1,S,B,NH,D] f32  the forward call's output
+ *   gate_cache  the forward call's output
+ *   dH          [T,B,NH,D] io_dtype gradient w.r.t. h_1..h_T (slot t-1 belongs to h_t)
+ *   dstates_last [S,B,NH,D] f32     gradient w.r.t. the final states, or NULL for zeros
+ *                                   (the sLSTM stabilizer slot is ignored: m carries no gradient)
+ *   dWx         [T,B,G,NH,D] io_dtype OUT
+ *   dR          [NH,D,G,D] f32      OUT
+ *   db          [NH,G,D]   f32      OUT
+ *   dstates0    [S,B,NH,D] f32      OUT (sLSTM stabilizer slot = 0)
+ * For the GRU, gate n's input-side gradient (dWx) and recurrent-side gradient (used for dR, db and
+ * dh_{t-1}) differ by the factor sig(r); the library keeps the latter in the workspace.
+ */
+int flashrnn_bwd(const flashrnn_desc_t* desc, const void* R, const void* b, const void* states,
+                 const void* gate_cache, const void* dH, const void* dstates_last, void* dWx, void* dR, void* db,
+                 void* dstates0, void* workspace, void* hip_stream);
+
+/*
+ * Reads the error word the kernels of the last call on this workspace left behind (synchronizes
+ * the stream).  Returns FLASHRNN_OK, FLASHRNN_ERR_TIMEOUT if a cross-CU wait ran into its spin
+ * limit (results are then invalid), or FLASHRNN_ERR_LAUNCH.  workspace may be NULL (returns OK).
+ */
+int flashrnn_check(const flashrnn_desc_t* desc, const void* workspace, void* hip_stream);
+
+/*
+ * Launch plan the library would use for `desc`, for reporting: number of workgroups (= CUs kept
+ * busy) of the forward / backward persistent kernel, workgroups that share one head, waves per
+ * workgroup.  Any out pointer may be NULL.  Returns a status.
+ */
+int flashrnn_plan(const flashrnn_desc_t* desc, int backward, int* workgroups, int* cus_per_head, int* waves_per_wg);
+
+const char* flashrnn_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLASHRNN_H */

@@ -1,0 +1,345 @@
+// C ABI of the library (see include/flashrnn.h): argument checks, launch planning, workspace carving
+// and the launches.  No device memory is allocated here.
+#include "flashrnn.h"
+
+#include <stdlib.h>
+#include <string.h>
+
+#include <mutex>
+#include <set>
+
+#include "flashrnn_common.h"
+#include "flashrnn_host.h"
+
+using namespace flashrnn;
+
+namespace {
+
+constexpr int kXcds = 8;            // accelerator dies a workgroup index cycles through
+constexpr size_t kAlign = 256;
+
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+inline int num_states(int cell) { return cell == FLASHRNN_LSTM ? 2 : cell == FLASHRNN_GRU ? 1 : cell == FLASHRNN_SLSTM ? 4 : -1; }
+inline int num_gates(int cell) { return cell == FLASHRNN_LSTM ? 4 : cell == FLASHRNN_GRU ? 3 : cell == FLASHRNN_SLSTM ? 4 : -1; }
+inline int num_cached(int cell) { return cell == FLASHRNN_SLSTM ? 5 : 4; }
+inline size_t io_size(int dt) { return dt == FLASHRNN_BF16 ? 2 : 4; }
+
+int env_int(const char* name, int dflt) {
+    const char* v = getenv(name);
+    return (v && *v) ? atoi(v) : dflt;
+}
+
+int device_cus() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) cus = n;
+        else cus = 256;  // MI355X
+    }
+    return cus;
+}
+
+KernelTable table_for(int cell, int dt) {
+    const bool bf = dt == FLASHRNN_BF16;
+    switch (cell) {
+        case FLASHRNN_LSTM: return bf ? table_lstm_bf16() : table_lstm_f32();
+        case FLASHRNN_GRU: return bf ? table_gru_bf16() : table_gru_f32();
+        default: return bf ? table_slstm_bf16() : table_slstm_f32();
+    }
+}
+
+struct Plan {
+    const KernelEntry* e = nullptr;
+    int NWU = 0, P = 0, NG = 0, GPAR = 0, grid = 0, block = 0, DK = 0;
+    size_t smem = 0, exch_bytes = 0, rpack_bytes = 0;
+};
+
+int validate(const flashrnn_desc_t* d) {
+    if (!d) return FLASHRNN_ERR_NULL;
+    if (num_states(d->cell) < 0 || (d->io_dtype != FLASHRNN_F32 && d->io_dtype != FLASHRNN_BF16)) return FLASHRNN_ERR_SHAPE;
+    if (d->T < 0 || d->B <= 0 || d->NH <= 0 || d->D <= 0) return FLASHRNN_ERR_SHAPE;
+    if (d->D % 16 != 0) return FLASHRNN_ERR_UNSUPPORTED;
+    return FLASHRNN_OK;
+}
+
+// Launch plan.  One workgroup per group whenever the head's R fits one CU's registers with 16 units
+// per wave (no cross-CU traffic at all); then small batch tiles spread the point-wise work over more
+// CUs.  Otherwise a group is split over P workgroups of one XCD that exchange h / dg every step.
+int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
+    const int G = num_gates(d->cell);
+    const bool bf = d->io_dtype == FLASHRNN_BF16;
+    const int kstep = bf ? 32 : 4;
+    const int kdim = bwd ? G * d->D : d->D;
+    const int units16 = d->D / 16;
+    const KernelTable tab = table_for(d->cell, d->io_dtype);
+    const int cus = device_cus();
+    const int force_multi = env_int("FLASHRNN_MULTI", -1);   // 1: always split groups, 0: never
+    const int force_bt = env_int("FLASHRNN_BT", 0);
+    const int force_nwu = env_int("FLASHRNN_NWU", 0);
+    const int force_ks = env_int("FLASHRNN_KS", 0);
+    Plan pl;
+
+    if (force_multi != 1) {
+        int bt_pref[3] = {16, 8, 4};
+        int nbt = 1;
+        if (bf) {
+            // smallest batch tile whose groups still fit the chip once
+            if (d->NH * ((d->B + 3) / 4) <= cus) { bt_pref[0] = 4; bt_pref[1] = 8; bt_pref[2] = 16; }
+            else if (d->NH * ((d->B + 7) / 8) <= cus) { bt_pref[0] = 8; bt_pref[1] = 16; bt_pref[2] = 4; }
+            nbt = 3;
+        }
+        if (force_bt) { bt_pref[0] = force_bt; nbt = 1; }
+        for (int b = 0; b < nbt && !pl.e; ++b) {
+            const KernelEntry* best = nullptr;
+            for (int i = 0; i < tab.count; ++i) {
+                const KernelEntry& e = tab.entries[i];
+                if (e.bwd != bwd || e.multi || e.KS != 1 || e.BT != bt_pref[b]) continue;
+                if (e.KT * kstep < kdim || e.maxw < units16) continue;
+                if (!best || e.KT < best->KT) best = &e;
+            }
+            if (best) {
+                pl.e = best;
+                pl.NWU = units16;
+                pl.P = 1;
+                pl.NG = d->NH * ((d->B + best->BT - 1) / best->BT);
+                pl.GPAR = pl.NG;
+                pl.grid = pl.NG;
+                pl.block = 64 * pl.NWU;
+                pl.DK = best->KT * kstep;
+                const int hp = pl.DK + (bf ? 8 : 4);
+                pl.smem = (size_t)2 * best->BT * hp * (bf ? 2 : 4);
+                pl.exch_bytes = 0;
+            }
+        }
+    }
+    if (!pl.e && force_multi != 0) {
+        const int cap = cus / kXcds - 2;                 // workgroups of one launch per XCD, with a margin
+        const int NG = d->NH * ((d->B + 15) / 16);
+        const int want_ks = force_ks ? force_ks : (d->D >= 512 ? 4 : 1);
+        const KernelEntry* best = nullptr;
+        for (int pass = 0; pass < 2 && !best; ++pass) {
+            for (int i = 0; i < tab.count; ++i) {
+                const KernelEntry& e = tab.entries[i];
+                if (e.bwd != bwd || !e.multi || e.KT * e.KS * kstep != kdim) continue;
+                if (pass == 0 && e.KS != want_ks) continue;
+                if (!best || e.maxw > best->maxw) best = &e;
+            }
+        }
+        if (best) {
+            const int nwu_max = best->maxw / best->KS;
+            // most workgroups per group (shortest MFMA and point-wise phase per step) that still lets
+            // every group run at once; fall back to looping over groups
+            const int slots = (NG + kXcds - 1) / kXcds;       // groups per XCD if all run at once
+            int chosen = 0;
+            for (int nwu = 1; nwu <= nwu_max; ++nwu) {
+                if (units16 % nwu) continue;
+                const int P = units16 / nwu;
+                if (force_nwu ? nwu == force_nwu : P * slots <= cap) { chosen = nwu; break; }
+            }
+            int gpar = NG;
+            if (!chosen) {
+                // even the fewest workgroups per group do not fit all groups: loop over groups
+                for (int nwu = nwu_max; nwu >= 1 && !chosen; --nwu)
+                    if (units16 % nwu == 0 && units16 / nwu <= cap) chosen = nwu;
+                if (chosen) gpar = kXcds * (cap / (units16 / chosen));
+                if (gpar > NG) gpar = NG;
+            }
+            if (chosen) {
+                pl.e = best;
+                pl.NWU = chosen;
+                pl.P = units16 / chosen;
+                pl.NG = NG;
+                pl.GPAR = gpar;
+                pl.grid = (gpar + kXcds - 1) / kXcds * pl.P * kXcds;
+                pl.block = 64 * chosen * best->KS;
+                pl.DK = best->KT * best->KS * kstep;
+                const int nt = bwd ? 1 : G;
+                pl.smem = best->KS > 1 ? (size_t)2 * (best->KS - 1) * chosen * nt * 4 * 64 * 4 : 16;
+                pl.exch_bytes = (size_t)2 * gpar * 16 * pl.DK * (bf ? 4 : 8);
+            }
+        }
+    }
+    if (!pl.e) return FLASHRNN_ERR_UNSUPPORTED;
+    pl.rpack_bytes = (bwd ? (size_t)d->NH * d->D * pl.DK : (size_t)d->NH * G * d->D * pl.DK) * io_size(d->io_dtype);
+    *out = pl;
+    return FLASHRNN_OK;
+}
+
+struct Workspace {
+    size_t err_off, exch_off, rpack_off, dgn_off, dbpart_off, drpart_off, total;
+};
+
+int carve(const flashrnn_desc_t* d, Workspace* w, Plan* pf, Plan* pb) {
+    int rc = make_plan(d, 0, pf);
+    if (rc != FLASHRNN_OK) return rc;
+    rc = make_plan(d, 1, pb);
+    if (rc != FLASHRNN_OK) return rc;
+    const int G = num_gates(d->cell);
+    size_t off = 0;
+    w->err_off = off; off += kAlign;
+    w->exch_off = off; off += align_up(pf->exch_bytes > pb->exch_bytes ? pf->exch_bytes : pb->exch_bytes);
+    w->rpack_off = off; off += align_up(pf->rpack_bytes > pb->rpack_bytes ? pf->rpack_bytes : pb->rpack_bytes);
+    w->dgn_off = off; off += align_up(d->cell == FLASHRNN_GRU ? (size_t)d->T * d->B * d->NH * d->D * io_size(d->io_dtype) : 0);
+    w->dbpart_off = off; off += align_up((size_t)d->B * d->NH * G * d->D * 4);
+    w->drpart_off = off;
+    const int sk = dr_split_k(d->T, d->B, d->NH, d->D, G);
+    off += align_up(sk > 1 ? (size_t)sk * d->NH * d->D * G * d->D * 4 : 0);
+    w->total = off;
+    return FLASHRNN_OK;
+}
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+int prepare_kernel(const Plan& pl) {
+    static std::mutex mu;
+    static std::set<const void*> done;
+    std::lock_guard<std::mutex> lock(mu);
+    if (done.count(pl.e->fn)) return FLASHRNN_OK;
+    if (hipFuncSetAttribute(pl.e->fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) {
+        (void)hipGetLastError();
+        if (pl.smem > 64 * 1024) return FLASHRNN_ERR_LAUNCH;
+    }
+    done.insert(pl.e->fn);
+    return FLASHRNN_OK;
+}
+
+int launch_persistent(const Plan& pl, KernelParams& kp, hipStream_t stream) {
+    if (prepare_kernel(pl) != FLASHRNN_OK) return FLASHRNN_ERR_LAUNCH;
+    kp.P = pl.P;
+    kp.NWU = pl.NWU;
+    kp.NG = pl.NG;
+    kp.GPAR = pl.GPAR;
+    kp.spin_limit = env_int("FLASHRNN_SPIN_LIMIT", 1 << 21);
+    void* args[] = {&kp};
+    if (hipLaunchKernel(pl.e->fn, dim3(pl.grid), dim3(pl.block), args, pl.smem, stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
+    return FLASHRNN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int flashrnn_num_states(int cell) { return num_states(cell); }
+int flashrnn_num_gates(int cell) { return num_gates(cell); }
+
+size_t flashrnn_gate_cache_bytes(const flashrnn_desc_t* d) {
+    if (validate(d) != FLASHRNN_OK) return 0;
+    return (size_t)d->T * d->B * d->NH * num_cached(d->cell) * d->D * io_size(d->io_dtype);
+}
+
+size_t flashrnn_workspace_bytes(const flashrnn_desc_t* d) {
+    if (validate(d) != FLASHRNN_OK) return 0;
+    Workspace w;
+    Plan pf, pb;
+    if (carve(d, &w, &pf, &pb) != FLASHRNN_OK) return 0;
+    return w.total;
+}
+
+int flashrnn_plan(const flashrnn_desc_t* d, int backward, int* workgroups, int* cus_per_head, int* waves_per_wg) {
+    int rc = validate(d);
+    if (rc != FLASHRNN_OK) return rc;
+    Plan pl;
+    rc = make_plan(d, backward ? 1 : 0, &pl);
+    if (rc != FLASHRNN_OK) return rc;
+    if (workgroups) *workgroups = (pl.GPAR < pl.NG ? pl.GPAR : pl.NG) * pl.P;
+    if (cus_per_head) *cus_per_head = pl.P * ((d->B + pl.e->BT - 1) / pl.e->BT);
+    if (waves_per_wg) *waves_per_wg = pl.block / 64;
+    return FLASHRNN_OK;
+}
+
+int flashrnn_fwd(const flashrnn_desc_t* d, const void* Wx, const void* R, const void* b, const void* states0, void* states,
+                 void* gate_cache, void* workspace, void* hip_stream) {
+    int rc = validate(d);
+    if (rc != FLASHRNN_OK) return rc;
+    if (!R || !b || !states || (d->T > 0 && !Wx)) return FLASHRNN_ERR_NULL;
+    if (!aligned16(Wx) || !aligned16(R) || !aligned16(b) || !aligned16(states0) || !aligned16(states) || !aligned16(gate_cache))
+        return FLASHRNN_ERR_UNSUPPORTED;
+    Workspace w;
+    Plan pf, pb;
+    rc = carve(d, &w, &pf, &pb);
+    if (rc != FLASHRNN_OK) return rc;
+    if (!workspace || ((uintptr_t)workspace & (kAlign - 1))) return FLASHRNN_ERR_WORKSPACE;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    char* ws = (char*)workspace;
+    const int G = num_gates(d->cell);
+    if (launch_fill_zero(ws + w.err_off, kAlign + align_up(pf.exch_bytes), stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
+    if (launch_pack_r(d->io_dtype == FLASHRNN_BF16, false, R, ws + w.rpack_off, d->NH, d->D, G, pf.DK, stream) != hipSuccess)
+        return FLASHRNN_ERR_LAUNCH;
+    KernelParams kp;
+    memset(&kp, 0, sizeof(kp));
+    kp.Wx = Wx; kp.R = ws + w.rpack_off; kp.bias = b; kp.states0 = (const float*)states0; kp.states = (float*)states;
+    kp.cache = gate_cache;
+    kp.exch = (uint32_t*)(ws + w.exch_off);
+    kp.err = (int*)(ws + w.err_off);
+    kp.T = d->T; kp.B = d->B; kp.NH = d->NH; kp.D = d->D;
+    return launch_persistent(pf, kp, stream);
+}
+
+int flashrnn_bwd(const flashrnn_desc_t* d, const void* R, const void* b, const void* states, const void* gate_cache,
+                 const void* dH, const void* dstates_last, void* dWx, void* dR, void* db, void* dstates0, void* workspace,
+                 void* hip_stream) {
+    int rc = validate(d);
+    if (rc != FLASHRNN_OK) return rc;
+    (void)b;
+    if (!R || !states || !dR || !db || !dstates0 || (d->T > 0 && (!gate_cache || !dH || !dWx))) return FLASHRNN_ERR_NULL;
+    if (!aligned16(R) || !aligned16(states) || !aligned16(gate_cache) || !aligned16(dH) || !aligned16(dstates_last) ||
+        !aligned16(dWx) || !aligned16(dR) || !aligned16(db) || !aligned16(dstates0))
+        return FLASHRNN_ERR_UNSUPPORTED;
+    Workspace w;
+    Plan pf, pb;
+    rc = carve(d, &w, &pf, &pb);
+    if (rc != FLASHRNN_OK) return rc;
+    if (!workspace || ((uintptr_t)workspace & (kAlign - 1))) return FLASHRNN_ERR_WORKSPACE;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    char* ws = (char*)workspace;
+    const int G = num_gates(d->cell), S = num_states(d->cell);
+    const bool bf = d->io_dtype == FLASHRNN_BF16;
+    if (launch_fill_zero(ws + w.err_off, kAlign + align_up(pb.exch_bytes), stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
+    if (launch_pack_r(bf, true, R, ws + w.rpack_off, d->NH, d->D, G, pb.DK, stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
+    KernelParams kp;
+    memset(&kp, 0, sizeof(kp));
+    kp.R = ws + w.rpack_off; kp.states = (float*)const_cast<void*>(states); kp.cache = const_cast<void*>(gate_cache);
+    kp.dH = dH; kp.dlast = (const float*)dstates_last; kp.dWx = dWx; kp.dgn = ws + w.dgn_off;
+    kp.dstates0 = (float*)dstates0; kp.db_part = (float*)(ws + w.dbpart_off);
+    kp.exch = (uint32_t*)(ws + w.exch_off);
+    kp.err = (int*)(ws + w.err_off);
+    kp.T = d->T; kp.B = d->B; kp.NH = d->NH; kp.D = d->D;
+    rc = launch_persistent(pb, kp, stream);
+    if (rc != FLASHRNN_OK) return rc;
+    // db: sum of the per-row partial sums in row order; dR: GEMM over (t, b)
+    const size_t nb = (size_t)d->NH * G * d->D;
+    if (launch_sum_slices((const float*)(ws + w.dbpart_off), (float*)db, nb, d->B, nb, stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
+    if (d->T == 0) {
+        if (launch_fill_zero(dR, (size_t)d->NH * d->D * G * d->D * 4, stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
+        return FLASHRNN_OK;
+    }
+    if (launch_dr_gemm(bf, (const float*)states, dWx, ws + w.dgn_off, (float*)(ws + w.drpart_off), (float*)dR, d->T, d->B, d->NH, d->D,
+                       G, S, d->cell == FLASHRNN_GRU, stream) != hipSuccess)
+        return FLASHRNN_ERR_LAUNCH;
+    return FLASHRNN_OK;
+}
+
+int flashrnn_check(const flashrnn_desc_t* d, const void* workspace, void* hip_stream) {
+    (void)d;
+    if (!workspace) return FLASHRNN_OK;
+    int flag = 0;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (hipMemcpyAsync(&flag, workspace, sizeof(int), hipMemcpyDeviceToHost, stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
+    if (hipStreamSynchronize(stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
+    return flag == 0 ? FLASHRNN_OK : FLASHRNN_ERR_TIMEOUT;
+}
+
+const char* flashrnn_status_string(int status) {
+    switch (status) {
+        case FLASHRNN_OK: return "ok";
+        case FLASHRNN_ERR_NULL: return "a required pointer is NULL";
+        case FLASHRNN_ERR_SHAPE: return "invalid shape, cell or dtype";
+        case FLASHRNN_ERR_UNSUPPORTED: return "unsupported head size, alignment or dtype combination";
+        case FLASHRNN_ERR_WORKSPACE: return "workspace missing or not 256-byte aligned";
+        case FLASHRNN_ERR_LAUNCH: return "a HIP call failed";
+        case FLASHRNN_ERR_TIMEOUT: return "a cross-CU wait ran into its spin limit";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,195 @@
+// Shared device-side definitions of the persistent forward / backward kernels (gfx950 only).
+//
+// Tiling vocabulary (paper App. B uses E/W/B/L per axis; ours, chosen for CDNA4):
+//   - a *group* is one (head, batch tile); a batch tile holds BT <= 16 rows;
+//   - a group is served by P workgroups ("members"), each owning U = 16*NWU consecutive units of
+//     the head and ALL gates of those units (the gate axis is never split, so the point-wise
+//     function stays in registers);
+//   - inside a workgroup a wave owns 16 units (one MFMA tile row block per gate) and, when KS > 1,
+//     one of KS slices of the contraction axis; partial sums of the KS slices meet in LDS;
+//   - one MFMA tile is [16 units] x [16 batch slots]: the recurrent weights are the A operand (kept
+//     in registers for all T steps, paper Sec. 5.2), h_{t-1} (or the gate gradients) is the B operand.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace flashrnn {
+
+enum : int { CELL_LSTM = 0, CELL_GRU = 1, CELL_SLSTM = 2 };
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4;
+typedef __attribute__((__vector_size__(2 * sizeof(int)))) int i32x2;
+
+template <int CELL> struct CellTraits;
+template <> struct CellTraits<CELL_LSTM> { static constexpr int G = 4, S = 2, NC = 4; };
+template <> struct CellTraits<CELL_GRU> { static constexpr int G = 3, S = 1, NC = 4; };
+template <> struct CellTraits<CELL_SLSTM> { static constexpr int G = 4, S = 4, NC = 5; };
+// NC = values per (t, batch row, unit) the forward pass saves for the backward pass:
+//   LSTM  sig(i), sig(f), tanh(z), sig(o)
+//   GRU   sig(r), sig(z), tanh(candidate), yn = R_n h + b_n
+//   sLSTM input weight exp(i - m_t), forget weight exp(log sig(f) + m_{t-1} - m_t), tanh(z), sig(o), sig(-f)
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// Cache policy bits of the raw buffer intrinsics on gfx942/gfx950.
+constexpr int kAuxAgent = 16;  // sc1: coherent at agent scope (misses the CU's vector L1)
+
+struct KernelParams {
+    const void* Wx;        // fwd: [T,B,G,NH,D] io
+    const void* R;         // [NH,D,G,D] io
+    const void* bias;      // [NH,G,D] io
+    const float* states0;  // fwd: [S,B,NH,D] or null
+    float* states;         // [T+1,S,B,NH,D]
+    void* cache;           // [T,B,NH,NC,D] io dtype, may be null in fwd
+    const void* dH;        // bwd: [T,B,NH,D] io
+    const float* dlast;    // bwd: [S,B,NH,D] or null
+    void* dWx;             // bwd: [T,B,G,NH,D] io
+    void* dgn;             // bwd, GRU: recurrent-side gradient of gate n, [T,B,NH,D] io
+    float* dstates0;       // bwd: [S,B,NH,D]
+    float* db_part;        // bwd: [B,NH,G,D] per-batch-row partial sums of db
+    uint32_t* exch;        // cross-CU exchange buffer (stamped words)
+    int* err;              // error word
+    int T, B, NH, D;
+    int P;                 // workgroups per group
+    int NWU;               // unit waves per workgroup (each 16 units)
+    int NG;                // groups in total: NH * batch tiles; group id = tile * NH + head
+    int GPAR;              // groups processed concurrently; a workgroup set loops over NG / GPAR of them
+    int spin_limit;
+};
+
+// ---------------------------------------------------------------------------------------------
+// small helpers
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t u16) { return __builtin_bit_cast(float, u16 << 16); }
+
+// round to nearest even; inputs are finite in every use below
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+    uint32_t u = __builtin_bit_cast(uint32_t, f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
+__device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+
+// Point-wise math in two flavours: FAST (bf16 I/O: hardware exp2/log2/rcp, ~1e-6 relative) and
+// accurate (f32 I/O: library functions, needed for 1e-5 agreement with the fp64 oracle).
+template <bool FAST> __device__ __forceinline__ float sigm(float x) {
+    if constexpr (FAST) return fast_rcp(1.0f + fast_exp2(-kLog2e * x));
+    else return 1.0f / (1.0f + expf(-x));
+}
+template <bool FAST> __device__ __forceinline__ float tanh_(float x) {
+    if constexpr (FAST) return 1.0f - 2.0f * fast_rcp(1.0f + fast_exp2((2.0f * kLog2e) * x));
+    else return tanhf(x);
+}
+template <bool FAST> __device__ __forceinline__ float exp_(float x) {
+    if constexpr (FAST) return fast_exp2(kLog2e * x);
+    else return expf(x);
+}
+
+// DPP row shift right by N lanes inside each row of 16 lanes, written only to the lanes of the
+// banks in BANKS (bank k = lanes 4k..4k+3 of every row); other lanes keep `old`.
+template <int N, int BANKS> __device__ __forceinline__ float dpp_row_shr(float old, float src) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, old), __builtin_bit_cast(int, src),
+                                                                 0x110 + N, 0xF, BANKS, false));
+}
+
+// MFMA output of one [16 units] x [16 batch slots] tile: lane (c = lane%16, q = lane/16) holds batch
+// slot c and units 4q..4q+3.  With fewer than 16 valid batch slots the idle lanes take over part of
+// the units of the busy ones, so that the point-wise work is spread over all 64 lanes:
+//   BT = 16: PP = 4 pairs per lane, unit offset 4q + i
+//   BT = 8 : lanes c >= 8 take units 4q+2, 4q+3 of batch slot c-8;       PP = 2, offset 4q + 2(c/8) + i
+//   BT = 4 : lanes c in [4k, 4k+4) take unit 4q+k of batch slot c%4;     PP = 1, offset 4q + c/4
+template <int BT> __device__ __forceinline__ void compact_tile(f32x4& a) {
+    if constexpr (BT == 8) {
+        a[0] = dpp_row_shr<8, 0xC>(a[0], a[2]);
+        a[1] = dpp_row_shr<8, 0xC>(a[1], a[3]);
+    } else if constexpr (BT == 4) {
+        a[0] = dpp_row_shr<4, 0x2>(a[0], a[1]);
+        a[0] = dpp_row_shr<8, 0x4>(a[0], a[2]);
+        a[0] = dpp_row_shr<12, 0x8>(a[0], a[3]);
+    }
+}
+
+// typed I/O of PP consecutive elements (io dtype bf16 or f32), PP in {1, 2, 4}
+template <bool BF16, int PP> __device__ __forceinline__ void load_io(const void* base, size_t idx, float (&out)[PP]) {
+    if constexpr (BF16) {
+        const uint16_t* p = (const uint16_t*)base + idx;
+        if constexpr (PP == 4) {
+            uint2 v = *(const uint2*)p;
+            out[0] = bf16_bits_to_f32(v.x & 0xFFFFu); out[1] = __builtin_bit_cast(float, v.x & 0xFFFF0000u);
+            out[2] = bf16_bits_to_f32(v.y & 0xFFFFu); out[3] = __builtin_bit_cast(float, v.y & 0xFFFF0000u);
+        } else if constexpr (PP == 2) {
+            uint32_t v = *(const uint32_t*)p;
+            out[0] = bf16_bits_to_f32(v & 0xFFFFu); out[1] = __builtin_bit_cast(float, v & 0xFFFF0000u);
+        } else {
+            out[0] = bf16_bits_to_f32(*p);
+        }
+    } else {
+        const float* p = (const float*)base + idx;
+        if constexpr (PP == 4) { float4 v = *(const float4*)p; out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w; }
+        else if constexpr (PP == 2) { float2 v = *(const float2*)p; out[0] = v.x; out[1] = v.y; }
+        else out[0] = *p;
+    }
+}
+
+template <bool BF16, int PP> __device__ __forceinline__ void store_io(void* base, size_t idx, const float (&v)[PP]) {
+    if constexpr (BF16) {
+        uint16_t* p = (uint16_t*)base + idx;
+        if constexpr (PP == 4) {
+            uint2 o;
+            o.x = f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16);
+            o.y = f32_to_bf16_bits(v[2]) | (f32_to_bf16_bits(v[3]) << 16);
+            *(uint2*)p = o;
+        } else if constexpr (PP == 2) {
+            *(uint32_t*)p = f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16);
+        } else {
+            *p = (uint16_t)f32_to_bf16_bits(v[0]);
+        }
+    } else {
+        float* p = (float*)base + idx;
+        if constexpr (PP == 4) *(float4*)p = make_float4(v[0], v[1], v[2], v[3]);
+        else if constexpr (PP == 2) *(float2*)p = make_float2(v[0], v[1]);
+        else *p = v[0];
+    }
+}
+
+template <int PP> __device__ __forceinline__ void load_f32(const float* base, size_t idx, float (&out)[PP]) {
+    load_io<false, PP>(base, idx, out);
+}
+template <int PP> __device__ __forceinline__ void store_f32(float* base, size_t idx, const float (&v)[PP]) {
+    store_io<false, PP>(base, idx, v);
+}
+
+// Operand type of one MFMA k-step: 8 bf16 (v_mfma_f32_16x16x32_bf16) or one float (v_mfma_f32_16x16x4_f32).
+template <bool BF16> struct Operand;
+template <> struct Operand<true> {
+    using type = bf16x8;
+    static constexpr int KPL = 8;   // contraction elements per lane per k-step
+    static constexpr int KSTEP = 32;
+    static __device__ __forceinline__ f32x4 mfma(bf16x8 a, bf16x8 b, f32x4 c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+    }
+};
+template <> struct Operand<false> {
+    using type = float;
+    static constexpr int KPL = 1;
+    static constexpr int KSTEP = 4;
+    static __device__ __forceinline__ f32x4 mfma(float a, float b, f32x4 c) {
+        return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+    }
+};
+
+// Contraction index held by (k-step kt, lane quad q, element j) of a wave whose slice starts at k0.
+// The assignment is free as long as both MFMA operands use the same one; this one makes the KPL*KT
+// elements of a lane... (bf16) 8 consecutive per k-step, (f32) KT consecutive per lane.
+template <bool BF16, int KT> __device__ __forceinline__ int k_index(int k0, int kt, int q, int j) {
+    if constexpr (BF16) return k0 + kt * 32 + q * 8 + j;
+    else return k0 + q * KT + kt;
+}
+
+}  // namespace flashrnn

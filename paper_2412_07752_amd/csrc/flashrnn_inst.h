@@ -1,0 +1,40 @@
+// Instantiation lists of the persistent kernels.  Included by one translation unit per
+// (cell, I/O dtype) with FRNN_CELL, FRNN_G and FRNN_BF16 defined.
+//
+// Shapes (KT = k-steps per wave, 32 contraction elements per bf16 step, 4 per f32 step):
+//   one workgroup per group:   units D <= 32 / 64 / 128 / 192 (bf16) or 16 / 32 / 64 / 128 (f32)
+//   several workgroups:        D up to 1024 (bf16) / 256 (f32), optionally 4 contraction slices
+#pragma once
+#include "flashrnn_host.h"
+#include "flashrnn_kernels.h"
+
+namespace flashrnn {
+
+#define FRNN_F(KT, KS, BT, MULTI, MAXW) \
+    {FRNN_CELL, FRNN_BF16, 0, KT, KS, BT, MULTI, MAXW, (const void*)&fwd_kernel<FRNN_CELL, (FRNN_BF16 != 0), KT, KS, BT, (MULTI != 0), MAXW>},
+#define FRNN_B(KT, KS, BT, MULTI, MAXW) \
+    {FRNN_CELL, FRNN_BF16, 1, (KT) * FRNN_G, KS, BT, MULTI, MAXW, (const void*)&bwd_kernel<FRNN_CELL, (FRNN_BF16 != 0), (KT) * FRNN_G, KS, BT, (MULTI != 0), MAXW>},
+// forward and backward share the shape list: the backward contraction axis is G times longer
+#define FRNN_FB(KT, KS, BT, MULTI, MAXW) FRNN_F(KT, KS, BT, MULTI, MAXW) FRNN_B(KT, KS, BT, MULTI, MAXW)
+
+static const KernelEntry kEntries[] = {
+#if FRNN_BF16
+    FRNN_FB(1, 1, 16, 0, 4) FRNN_FB(1, 1, 8, 0, 4) FRNN_FB(1, 1, 4, 0, 4)
+    FRNN_FB(2, 1, 16, 0, 4) FRNN_FB(2, 1, 8, 0, 4) FRNN_FB(2, 1, 4, 0, 4)
+    FRNN_FB(4, 1, 16, 0, 8) FRNN_FB(4, 1, 8, 0, 8) FRNN_FB(4, 1, 4, 0, 8)
+    FRNN_FB(6, 1, 16, 0, 12) FRNN_FB(6, 1, 8, 0, 12) FRNN_FB(6, 1, 4, 0, 12)
+    FRNN_FB(2, 1, 16, 1, 4) FRNN_FB(4, 1, 16, 1, 4) FRNN_FB(6, 1, 16, 1, 4) FRNN_FB(1, 4, 16, 1, 4)
+    FRNN_FB(8, 1, 16, 1, 8) FRNN_FB(12, 1, 16, 1, 8) FRNN_FB(16, 1, 16, 1, 4) FRNN_FB(24, 1, 16, 1, 4)
+    FRNN_FB(6, 4, 16, 1, 8) FRNN_FB(8, 4, 16, 1, 8)
+#else
+    FRNN_FB(4, 1, 16, 0, 4) FRNN_FB(8, 1, 16, 0, 4) FRNN_FB(16, 1, 16, 0, 4) FRNN_FB(32, 1, 16, 0, 8)
+    FRNN_FB(16, 1, 16, 1, 4) FRNN_FB(32, 1, 16, 1, 4) FRNN_FB(48, 1, 16, 1, 4) FRNN_FB(64, 1, 16, 1, 4)
+    FRNN_FB(8, 4, 16, 1, 4)
+#endif
+};
+
+#undef FRNN_F
+#undef FRNN_B
+#undef FRNN_FB
+
+}  // namespace flashrnn

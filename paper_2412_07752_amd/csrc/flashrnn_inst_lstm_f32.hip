@@ -1,0 +1,9 @@
+// Persistent-kernel instantiations: lstm, f32 I/O.
+#define FRNN_CELL flashrnn::CELL_LSTM
+#define FRNN_G 4
+#define FRNN_BF16 0
+#include "flashrnn_inst.h"
+
+namespace flashrnn {
+KernelTable table_lstm_f32() { return KernelTable{kEntries, (int)(sizeof(kEntries) / sizeof(kEntries[0]))}; }
+}  // namespace flashrnn

@@ -1,0 +1,637 @@
+// Persistent forward and backward kernels of the RNN time-step loop (gfx950, wave64, MFMA).
+//
+// Forward (paper Sec. 3 eq. (1)-(2), Alg. 1): per step  y = R^T h_{t-1}  on the matrix cores, then
+// g = Wx_t + y + b and the cell's point-wise function in registers; states and the values the
+// backward pass needs go to HBM; the new h goes to LDS (one CU per group) or to a stamped exchange
+// buffer in global memory (several CUs per group) and is the next step's MFMA operand.
+// Backward (paper Sec. 4 eq. (3)-(4)): per step the point-wise Jacobians give the gate gradients dg_t,
+// which are streamed out as dWx, handed to the other waves like h in the forward pass, and contracted
+// with the same resident R along its gate/unit axis to give dh_{t-1}.
+#pragma once
+#include "flashrnn_common.h"
+
+namespace flashrnn {
+
+// ---------------------------------------------------------------------------------------------
+// point-wise functions (paper App. A); gate order i,f,z,o (LSTM, sLSTM) and r,z,n (GRU)
+// ---------------------------------------------------------------------------------------------
+template <int CELL, bool FAST> struct Cell;
+
+template <bool FAST> struct Cell<CELL_LSTM, FAST> {
+    // st = {h, c}; wx = input pre-activations, yb = R^T h + b
+    static __device__ __forceinline__ void fwd(const float (&wx)[4], const float (&yb)[4], float (&st)[2], float (&cv)[4]) {
+        const float i = sigm<FAST>(wx[0] + yb[0]), f = sigm<FAST>(wx[1] + yb[1]);
+        const float z = tanh_<FAST>(wx[2] + yb[2]), o = sigm<FAST>(wx[3] + yb[3]);
+        const float c = f * st[1] + i * z;
+        st[1] = c;
+        st[0] = o * tanh_<FAST>(c);
+        cv[0] = i; cv[1] = f; cv[2] = z; cv[3] = o;
+    }
+    // sc = states after the step (h unused), sp = states before the step;
+    // ds = carried gradients {dh (total incl. external), dc}; on return ds = point-wise carries
+    // (ds[0] = direct h path, zero here); dwx = input-side, dg = recurrent-side gate gradients.
+    static __device__ __forceinline__ void bwd(const float (&cv)[4], const float (&sc)[2], const float (&sp)[2], float (&ds)[2],
+                                               float (&dwx)[4], float (&dg)[4]) {
+        const float i = cv[0], f = cv[1], z = cv[2], o = cv[3];
+        const float tc = tanh_<FAST>(sc[1]);
+        const float dh = ds[0];
+        const float dc = ds[1] + dh * o * (1.0f - tc * tc);
+        dg[0] = dc * z * i * (1.0f - i);
+        dg[1] = dc * sp[1] * f * (1.0f - f);
+        dg[2] = dc * i * (1.0f - z * z);
+        dg[3] = dh * tc * o * (1.0f - o);
+        dwx[0] = dg[0]; dwx[1] = dg[1]; dwx[2] = dg[2]; dwx[3] = dg[3];
+        ds[1] = dc * f;
+        ds[0] = 0.0f;
+    }
+};
+
+template <bool FAST> struct Cell<CELL_SLSTM, FAST> {
+    // st = {h, c, n, m}
+    static __device__ __forceinline__ void fwd(const float (&wx)[4], const float (&yb)[4], float (&st)[4], float (&cv)[5]) {
+        const float pi = wx[0] + yb[0], pf = wx[1] + yb[1];
+        float lf, sf;  // log sig(pf), sig(-pf)
+        if constexpr (FAST) {
+            const float t = fast_exp2(-kLog2e * fabsf(pf));
+            const float r = fast_rcp(1.0f + t);
+            const float tr = t * r;
+            const bool pos = pf >= 0.0f;
+            sf = pos ? tr : r;
+            lf = kLn2 * fast_log2(pos ? r : tr);
+        } else {
+            lf = pf >= 0.0f ? -log1pf(expf(-pf)) : pf - log1pf(expf(pf));
+            sf = 1.0f / (1.0f + expf(pf));
+        }
+        const float a = lf + st[3];
+        const float m = fmaxf(a, pi);
+        const float fg = exp_<FAST>(a - m), ig = exp_<FAST>(pi - m);
+        const float z = tanh_<FAST>(wx[2] + yb[2]), o = sigm<FAST>(wx[3] + yb[3]);
+        const float c = fg * st[1] + ig * z;
+        const float n = fg * st[2] + ig;
+        st[1] = c; st[2] = n; st[3] = m;
+        if constexpr (FAST) st[0] = o * c * fast_rcp(n);
+        else st[0] = o * c / n;
+        cv[0] = ig; cv[1] = fg; cv[2] = z; cv[3] = o; cv[4] = sf;
+    }
+    // ds = {dh, dc, dn, -}; the stabilizer carries no gradient
+    static __device__ __forceinline__ void bwd(const float (&cv)[5], const float (&sc)[4], const float (&sp)[4], float (&ds)[4],
+                                               float (&dwx)[4], float (&dg)[4]) {
+        const float ig = cv[0], fg = cv[1], z = cv[2], o = cv[3], sf = cv[4];
+        const float dh = ds[0];
+        float inv;
+        if constexpr (FAST) inv = fast_rcp(sc[2]);
+        else inv = 1.0f / sc[2];
+        const float ho = dh * o * inv;        // dh * o / n_t
+        const float q = sc[1] * inv;          // c_t / n_t
+        const float dc = ds[1] + ho;
+        const float dn = ds[2] - ho * q;
+        dg[0] = (dc * z + dn) * ig;
+        dg[1] = (dc * sp[1] + dn * sp[2]) * fg * sf;
+        dg[2] = dc * ig * (1.0f - z * z);
+        dg[3] = dh * q * o * (1.0f - o);
+        dwx[0] = dg[0]; dwx[1] = dg[1]; dwx[2] = dg[2]; dwx[3] = dg[3];
+        ds[1] = dc * fg; ds[2] = dn * fg; ds[3] = 0.0f;
+        ds[0] = 0.0f;
+    }
+};
+
+template <bool FAST> struct Cell<CELL_GRU, FAST> {
+    // st = {h}; gate n: yb[2] = R_n h + b_n is multiplied by sig(r) before it meets the input
+    static __device__ __forceinline__ void fwd(const float (&wx)[3], const float (&yb)[3], float (&st)[1], float (&cv)[4]) {
+        const float r = sigm<FAST>(wx[0] + yb[0]), z = sigm<FAST>(wx[1] + yb[1]);
+        const float yn = yb[2];
+        const float cand = tanh_<FAST>(wx[2] + r * yn);
+        st[0] = z * st[0] + (1.0f - z) * cand;
+        cv[0] = r; cv[1] = z; cv[2] = cand; cv[3] = yn;
+    }
+    static __device__ __forceinline__ void bwd(const float (&cv)[4], const float (&sc)[1], const float (&sp)[1], float (&ds)[1],
+                                               float (&dwx)[3], float (&dg)[3]) {
+        const float r = cv[0], z = cv[1], cand = cv[2], yn = cv[3];
+        const float dh = ds[0];
+        const float dpre = dh * (1.0f - z) * (1.0f - cand * cand);
+        const float dz = dh * (sp[0] - cand) * z * (1.0f - z);
+        const float dr = dpre * yn * r * (1.0f - r);
+        dwx[0] = dr; dwx[1] = dz; dwx[2] = dpre;
+        dg[0] = dr; dg[1] = dz; dg[2] = dpre * r;
+        ds[0] = dh * z;  // direct path h_{t-1} -> h_t
+        (void)sc;
+    }
+};
+
+// ---------------------------------------------------------------------------------------------
+// common per-lane geometry
+// ---------------------------------------------------------------------------------------------
+template <int BT> struct LaneMap {
+    static constexpr int PP = BT / 4;  // (unit, batch row) pairs per lane and tile
+    int c, quad, bslot, uoff;
+    __device__ __forceinline__ LaneMap(int lane) {
+        c = lane & 15;
+        quad = lane >> 4;
+        if constexpr (BT == 16) { bslot = c; uoff = 4 * quad; }
+        else if constexpr (BT == 8) { bslot = c & 7; uoff = 4 * quad + 2 * (c >> 3); }
+        else { bslot = c & 3; uoff = 4 * quad + (c >> 2); }
+    }
+};
+
+// group / member of a workgroup.  With several workgroups per group the members of a group get
+// block indices that are equal modulo 8: the hardware hands consecutive workgroups to the 8 XCDs in
+// turn, so a group's members share one XCD and its L2.
+struct BlockMap {
+    int member, gpar;
+    bool active;
+    __device__ __forceinline__ BlockMap(const KernelParams& p, bool multi) {
+        const int L = blockIdx.x;
+        if (multi) {
+            const int xcd = L & 7, slot = L >> 3;
+            member = slot % p.P;
+            gpar = (slot / p.P) * 8 + xcd;
+        } else {
+            member = 0;
+            gpar = L;
+        }
+        active = gpar < p.GPAR;
+    }
+};
+
+// ---------------------------------------------------------------------------------------------
+// operand hand-over between waves: LDS (one workgroup per group) or stamped words in global memory
+// ---------------------------------------------------------------------------------------------
+// Exchange word = 8 bytes {payload, stamp}: payload is two bf16 or one float.  A consumer polls the
+// words it needs until every stamp equals the one it expects; a word is written by one aligned
+// 8- or 16-byte store, so payload and stamp always arrive together and no fence is needed.  Stores and
+// loads carry the agent-scope cache policy.  Two buffers alternate; writing round r+1 requires having
+// read round r from every member, which implies every member has finished reading round r-1.
+// Polls KC k-steps of one operand row (first k-step kt0 of the wave's KT) and returns them in hB.
+// The loads are marked volatile: every round of the loop must go to memory again.
+template <bool BF16, int KT, int KC>
+__device__ __forceinline__ bool poll_operand(__amdgpu_buffer_rsrc_t rs, uint32_t row_off, int k0, int kt0, int quad, uint32_t stamp,
+                                             int spin_limit, int* err, typename Operand<BF16>::type* hB) {
+    constexpr int NL = BF16 ? 2 * KC : KC / 2;   // 16-byte loads per lane and round (two stamped words each)
+    static_assert(BF16 || (KC % 2 == 0 && KT % 2 == 0), "f32 operand rows are read two words at a time");
+    constexpr int kAuxPoll = (int)(0x80000000u | (unsigned)kAuxAgent);
+    const uint32_t base = BF16 ? row_off + (uint32_t)(k0 + kt0 * 32 + quad * 8) * 4u : row_off + (uint32_t)(k0 + quad * KT + kt0) * 8u;
+    constexpr uint32_t STEP = BF16 ? 128u : 16u;  // bytes between consecutive loads: next k-step (bf16) / next word pair (f32)
+    i32x4 raw[NL];
+    bool good = false;
+    int spins = 0;
+    while (true) {
+#pragma unroll
+        for (int j = 0; j < NL; ++j) {
+            const uint32_t off = BF16 ? base + (uint32_t)(j >> 1) * STEP + (uint32_t)(j & 1) * 16u : base + (uint32_t)j * STEP;
+            raw[j] = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, kAuxPoll);
+        }
+        bool ok = true;
+#pragma unroll
+        for (int j = 0; j < NL; ++j) ok = ok && ((uint32_t)raw[j][1] == stamp) && ((uint32_t)raw[j][3] == stamp);
+        if (__all((int)ok)) { good = true; break; }
+        if (++spins > spin_limit) {
+            __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            break;
+        }
+        if ((spins & 255) == 0 && __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) break;
+    }
+    if constexpr (BF16) {
+#pragma unroll
+        for (int j = 0; j < KC; ++j) hB[j] = __builtin_bit_cast(bf16x8, i32x4{raw[2 * j][0], raw[2 * j][2], raw[2 * j + 1][0], raw[2 * j + 1][2]});
+    } else {
+#pragma unroll
+        for (int j = 0; j < KC / 2; ++j) {
+            // (cast the whole vector, then index: a bit cast of a single vector element reads element 0
+            // with this compiler)
+            const f32x4 f = __builtin_bit_cast(f32x4, raw[j]);
+            hB[2 * j] = f[0];
+            hB[2 * j + 1] = f[2];
+        }
+    }
+    return good;
+}
+
+// write PP = 4 consecutive operand elements of one row as stamped words
+template <bool BF16>
+__device__ __forceinline__ void publish4(__amdgpu_buffer_rsrc_t rs, uint32_t row_off, int k, const float (&v)[4], uint32_t stamp) {
+    if constexpr (BF16) {
+        const i32x4 w = {(int)(f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16)), (int)stamp,
+                         (int)(f32_to_bf16_bits(v[2]) | (f32_to_bf16_bits(v[3]) << 16)), (int)stamp};
+        __builtin_amdgcn_raw_buffer_store_b128(w, rs, row_off + k * 4, 0, kAuxAgent);
+    } else {
+        const i32x4 w0 = {__builtin_bit_cast(int, v[0]), (int)stamp, __builtin_bit_cast(int, v[1]), (int)stamp};
+        const i32x4 w1 = {__builtin_bit_cast(int, v[2]), (int)stamp, __builtin_bit_cast(int, v[3]), (int)stamp};
+        __builtin_amdgcn_raw_buffer_store_b128(w0, rs, row_off + k * 8, 0, kAuxAgent);
+        __builtin_amdgcn_raw_buffer_store_b128(w1, rs, row_off + k * 8 + 16, 0, kAuxAgent);
+    }
+}
+
+// LDS operand row: element type bf16 (as uint16) or float
+template <bool BF16, int KT>
+__device__ __forceinline__ void read_operand_lds(const char* row, int k0, int quad, typename Operand<BF16>::type (&hB)[KT]) {
+    if constexpr (BF16) {
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt) hB[kt] = *(const bf16x8*)(row + (size_t)(k0 + kt * 32 + quad * 8) * 2);
+    } else {
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt) hB[kt] = *(const float*)(row + (size_t)(k0 + quad * KT + kt) * 4);
+    }
+}
+
+template <bool BF16, int PP> __device__ __forceinline__ void write_operand_lds(char* row, int k, const float (&v)[PP]) {
+    if constexpr (BF16) {
+        if constexpr (PP == 4) {
+            uint2 o;
+            o.x = f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16);
+            o.y = f32_to_bf16_bits(v[2]) | (f32_to_bf16_bits(v[3]) << 16);
+            *(uint2*)(row + k * 2) = o;
+        } else if constexpr (PP == 2) {
+            *(uint32_t*)(row + k * 2) = f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16);
+        } else {
+            *(uint16_t*)(row + k * 2) = (uint16_t)f32_to_bf16_bits(v[0]);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < PP; ++i) *(float*)(row + (k + i) * 4) = v[i];
+    }
+}
+
+// partial sums of the KS contraction slices meet in LDS: slices 1.. write, slice 0 adds
+template <int NT, int KS>
+__device__ __forceinline__ void reduce_slices(float* red, int parity, int ks, int wu, int NWU, int lane, f32x4 (&acc)[NT]) {
+    if constexpr (KS > 1) {
+        if (ks > 0) {
+#pragma unroll
+            for (int g = 0; g < NT; ++g)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    red[((((size_t)(parity * (KS - 1) + ks - 1) * NWU + wu) * NT + g) * 4 + i) * 64 + lane] = acc[g][i];
+        }
+        __syncthreads();
+        if (ks == 0) {
+#pragma unroll
+            for (int s = 1; s < KS; ++s)
+#pragma unroll
+                for (int g = 0; g < NT; ++g)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        acc[g][i] += red[((((size_t)(parity * (KS - 1) + s - 1) * NWU + wu) * NT + g) * 4 + i) * 64 + lane];
+        }
+    }
+}
+
+// =============================================================================================
+// forward
+// =============================================================================================
+// CELL, BF16 (I/O dtype), KT k-steps per wave, KS contraction slices, BT valid batch slots per tile,
+// MULTI several workgroups per group, MAXW launch bound in waves.
+// p.R is the packed forward copy of R: Rt[n][g][e][k], k < DK = KT*KS*KSTEP, zero beyond D.
+// The launch guarantees P * NWU * 16 == D, and with MULTI also DK == D.
+template <bool BF16> constexpr int poll_chunk(int KT) {
+    if (!BF16) return 8;
+    if (KT <= 6) return KT;
+    return KT % 6 == 0 ? 6 : KT % 4 == 0 ? 4 : KT % 3 == 0 ? 3 : KT % 2 == 0 ? 2 : 1;
+}
+
+template <int CELL, bool BF16, int KT, int KS, int BT, bool MULTI, int MAXW>
+__global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
+    using CT = CellTraits<CELL>;
+    using OP = Operand<BF16>;
+    using op_t = typename OP::type;
+    constexpr int G = CT::G, S = CT::S, NC = CT::NC;
+    constexpr int PP = BT / 4;
+    constexpr int ESZ = BF16 ? 2 : 4;               // operand element size in LDS
+    constexpr int DK = KT * KS * OP::KSTEP;         // padded contraction length
+    constexpr int HP = DK + (BF16 ? 8 : 4);         // LDS row pitch in elements
+    constexpr int KC = poll_chunk<BF16>(KT);
+    static_assert(!MULTI || BT == 16, "several workgroups per group exchange full 16-row tiles");
+    static_assert(KS == 1 || MULTI, "contraction slices are only used with several workgroups per group");
+    static_assert(!MULTI || KT % KC == 0, "poll chunks must tile the k-steps");
+
+    extern __shared__ __align__(16) char smem[];
+    const BlockMap bm(p, MULTI);
+    if (!bm.active) return;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int wu = w % p.NWU, ks = w / p.NWU;
+    const LaneMap<BT> lm(lane);
+    const int T = p.T, B = p.B, NH = p.NH, D = p.D;
+    const int e_wave = (bm.member * p.NWU + wu) * 16;  // first unit of this wave
+    const int e0 = e_wave + lm.uoff;                    // first unit of this lane's pairs
+    const int k0 = ks * KT * OP::KSTEP;
+
+    char* hbuf = smem;                                          // !MULTI: [2][BT][HP] operand rows
+    float* red = (float*)smem;                                  // MULTI, KS > 1: partial sums
+    __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(p.exch, 0, 0x7FFFFFFF, 0x00020000);
+    constexpr uint32_t XROW = DK * (BF16 ? 4 : 8);             // bytes per exchange row
+    const uint32_t xgroup = (uint32_t)bm.gpar * 16u * XROW;    // this group's rows inside one buffer
+    const uint32_t xbuf = (uint32_t)p.GPAR * 16u * XROW;       // bytes per buffer
+    bool failed = false;
+
+    int iter = 0;
+    for (int gid = bm.gpar; gid < p.NG; gid += p.GPAR, ++iter) {
+        const int n = gid % NH, q = gid / NH;
+        // ---- load once per group: R fragments (A operand: row = unit e_wave + c) and bias; they stay
+        // in registers for all T steps
+        op_t Rf[G][KT];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const size_t rrow = (((size_t)n * G + g) * D + e_wave + lm.c) * DK;
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt) {
+                if constexpr (BF16) Rf[g][kt] = *(const bf16x8*)((const uint16_t*)p.R + rrow + k_index<BF16, KT>(k0, kt, lm.quad, 0));
+                else Rf[g][kt] = ((const float*)p.R)[rrow + k_index<BF16, KT>(k0, kt, lm.quad, 0)];
+            }
+        }
+        float bias[G][PP];
+#pragma unroll
+        for (int g = 0; g < G; ++g) load_io<BF16, PP>(p.bias, ((size_t)n * G + g) * D + e0, bias[g]);
+
+        const int bb_raw = q * BT + lm.bslot;
+        const bool row_valid = bb_raw < B;
+        const int bb = row_valid ? bb_raw : B - 1;
+        const bool lane_ok = row_valid && ks == 0;
+
+        // ---- initial states
+        float st[S][PP];
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            if (p.states0 != nullptr) load_f32<PP>(p.states0, (((size_t)s * B + bb) * NH + n) * D + e0, st[s]);
+            else
+#pragma unroll
+                for (int i = 0; i < PP; ++i) st[s][i] = 0.0f;
+            if (lane_ok) store_f32<PP>(p.states, (((size_t)s * B + bb) * NH + n) * D + e0, st[s]);
+        }
+        if constexpr (!MULTI) {
+            __syncthreads();  // the previous group is done with the operand rows
+            for (int j = threadIdx.x; j < 2 * BT * HP * ESZ / 4; j += blockDim.x) ((uint32_t*)hbuf)[j] = 0u;
+            __syncthreads();
+            write_operand_lds<BF16, PP>(hbuf + (size_t)lm.bslot * HP * ESZ, e0, st[0]);
+            __syncthreads();
+        } else {
+            if (ks == 0 && T > 0) {
+                const uint32_t cnt = (uint32_t)iter * (uint32_t)T;
+                publish4<BF16>(xr, (cnt & 1u) * xbuf + xgroup + (uint32_t)lm.bslot * XROW, e0, st[0], cnt + 1u);
+            }
+        }
+
+        float wx[G][PP];
+        if (T > 0) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) load_io<BF16, PP>(p.Wx, (((size_t)bb * G + g) * NH + n) * D + e0, wx[g]);
+        }
+
+        for (int t = 1; t <= T; ++t) {
+            // ---- prefetch next step's input pre-activations (clamped at the last step)
+            float wxn[G][PP];
+            {
+                const int tn = t < T ? t : T - 1;
+#pragma unroll
+                for (int g = 0; g < G; ++g) load_io<BF16, PP>(p.Wx, ((((size_t)tn * B + bb) * G + g) * NH + n) * D + e0, wxn[g]);
+            }
+            // ---- recurrent product y = R^T h_{t-1} on the matrix cores
+            f32x4 acc[G];
+#pragma unroll
+            for (int g = 0; g < G; ++g) acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if constexpr (!MULTI) {
+                op_t hB[KT];
+                read_operand_lds<BF16, KT>(hbuf + ((size_t)((t - 1) & 1) * BT + lm.bslot) * HP * ESZ, k0, lm.quad, hB);
+#pragma unroll
+                for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                    for (int g = 0; g < G; ++g) acc[g] = OP::mfma(Rf[g][kt], hB[kt], acc[g]);
+            } else {
+                const uint32_t cnt = (uint32_t)iter * (uint32_t)T + (uint32_t)(t - 1);
+                const uint32_t row_off = (cnt & 1u) * xbuf + xgroup + (uint32_t)lm.c * XROW;
+#pragma unroll
+                for (int kc = 0; kc < KT; kc += KC) {
+                    op_t hB[KC];
+                    if (!failed) failed = !poll_operand<BF16, KT, KC>(xr, row_off, k0, kc, lm.quad, cnt + 1u, p.spin_limit, p.err, hB);
+                    if (failed) {
+#pragma unroll
+                        for (int j = 0; j < KC; ++j) hB[j] = op_t{};
+                    }
+#pragma unroll
+                    for (int j = 0; j < KC; ++j)
+#pragma unroll
+                        for (int g = 0; g < G; ++g) acc[g] = OP::mfma(Rf[g][kc + j], hB[j], acc[g]);
+                }
+            }
+            reduce_slices<G, KS>(red, t & 1, ks, wu, p.NWU, lane, acc);
+
+            if (ks == 0) {
+#pragma unroll
+                for (int g = 0; g < G; ++g) compact_tile<BT>(acc[g]);
+                float cvs[NC][PP];
+#pragma unroll
+                for (int i = 0; i < PP; ++i) {
+                    float wxi[G], ybi[G], sti[S], cvi[NC];
+#pragma unroll
+                    for (int g = 0; g < G; ++g) { wxi[g] = wx[g][i]; ybi[g] = acc[g][i] + bias[g][i]; }
+#pragma unroll
+                    for (int s = 0; s < S; ++s) sti[s] = st[s][i];
+                    Cell<CELL, BF16>::fwd(wxi, ybi, sti, cvi);
+#pragma unroll
+                    for (int s = 0; s < S; ++s) st[s][i] = sti[s];
+#pragma unroll
+                    for (int c2 = 0; c2 < NC; ++c2) cvs[c2][i] = cvi[c2];
+                }
+                // ---- hand the new h to the other waves first, then stream out states and saved values
+                if constexpr (!MULTI) {
+                    write_operand_lds<BF16, PP>(hbuf + ((size_t)(t & 1) * BT + lm.bslot) * HP * ESZ, e0, st[0]);
+                } else {
+                    if (t < T) {
+                        const uint32_t cnt = (uint32_t)iter * (uint32_t)T + (uint32_t)t;
+                        publish4<BF16>(xr, (cnt & 1u) * xbuf + xgroup + (uint32_t)lm.bslot * XROW, e0, st[0], cnt + 1u);
+                    }
+                }
+                if (lane_ok) {
+#pragma unroll
+                    for (int s = 0; s < S; ++s) store_f32<PP>(p.states, ((((size_t)t * S + s) * B + bb) * NH + n) * D + e0, st[s]);
+                    if (p.cache != nullptr) {
+#pragma unroll
+                        for (int c2 = 0; c2 < NC; ++c2)
+                            store_io<BF16, PP>(p.cache, ((((size_t)(t - 1) * B + bb) * NH + n) * NC + c2) * D + e0, cvs[c2]);
+                    }
+                }
+            }
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int i = 0; i < PP; ++i) wx[g][i] = wxn[g][i];
+            if constexpr (!MULTI) __syncthreads();
+        }
+    }
+}
+
+// =============================================================================================
+// backward
+// =============================================================================================
+// Wave owns 16 previous-state indices d (= its 16 units) and one of KS slices of the contraction
+// axis k = gate * D + unit (length G*D, padded to DK = KT*KS*KSTEP).  KT counts k-steps per wave.
+// p.R is the packed backward copy of R: Rb[n][d][k], k < DK, zero beyond G*D.
+// The launch guarantees P * NWU * 16 == D, and with MULTI also DK == G*D.
+template <int CELL, bool BF16, int KT, int KS, int BT, bool MULTI, int MAXW>
+__global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
+    using CT = CellTraits<CELL>;
+    using OP = Operand<BF16>;
+    using op_t = typename OP::type;
+    constexpr int G = CT::G, S = CT::S, NC = CT::NC;
+    constexpr int PP = BT / 4;
+    constexpr int ESZ = BF16 ? 2 : 4;
+    constexpr int DK = KT * KS * OP::KSTEP;
+    constexpr int HP = DK + (BF16 ? 8 : 4);
+    constexpr int KC = poll_chunk<BF16>(KT);
+    static_assert(!MULTI || BT == 16, "several workgroups per group exchange full 16-row tiles");
+    static_assert(KS == 1 || MULTI, "contraction slices are only used with several workgroups per group");
+    static_assert(!MULTI || KT % KC == 0, "poll chunks must tile the k-steps");
+
+    extern __shared__ __align__(16) char smem[];
+    const BlockMap bm(p, MULTI);
+    if (!bm.active) return;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int wu = w % p.NWU, ks = w / p.NWU;
+    const LaneMap<BT> lm(lane);
+    const int T = p.T, B = p.B, NH = p.NH, D = p.D;
+    const int e_wave = (bm.member * p.NWU + wu) * 16;
+    const int e0 = e_wave + lm.uoff;
+    const int k0 = ks * KT * OP::KSTEP;
+
+    char* gbuf = smem;          // !MULTI: [2][BT][HP] gate-gradient rows
+    float* red = (float*)smem;  // MULTI, KS > 1
+    __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(p.exch, 0, 0x7FFFFFFF, 0x00020000);
+    constexpr uint32_t XROW = DK * (BF16 ? 4 : 8);
+    const uint32_t xgroup = (uint32_t)bm.gpar * 16u * XROW;
+    const uint32_t xbuf = (uint32_t)p.GPAR * 16u * XROW;
+    bool failed = false;
+
+    int iter = 0;
+    for (int gid = bm.gpar; gid < p.NG; gid += p.GPAR, ++iter) {
+        const int n = gid % NH, q = gid / NH;
+        // ---- load once per group: R fragments, A operand row = previous-state index d = e_wave + c
+        op_t Rf[KT];
+        {
+            const size_t rrow = ((size_t)n * D + e_wave + lm.c) * DK;
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt) {
+                if constexpr (BF16) Rf[kt] = *(const bf16x8*)((const uint16_t*)p.R + rrow + k_index<BF16, KT>(k0, kt, lm.quad, 0));
+                else Rf[kt] = ((const float*)p.R)[rrow + k_index<BF16, KT>(k0, kt, lm.quad, 0)];
+            }
+        }
+        const int bb_raw = q * BT + lm.bslot;
+        const bool row_valid = bb_raw < B;
+        const int bb = row_valid ? bb_raw : B - 1;
+        const bool lane_ok = row_valid && ks == 0;
+
+        // carried state gradients; ds[0] is the part of dh_t that came through R and the direct path
+        float ds[S][PP];
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            if (p.dlast != nullptr && !(CELL == CELL_SLSTM && s == 3)) load_f32<PP>(p.dlast, (((size_t)s * B + bb) * NH + n) * D + e0, ds[s]);
+            else
+#pragma unroll
+                for (int i = 0; i < PP; ++i) ds[s][i] = 0.0f;
+        }
+        float dbacc[G][PP];
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int i = 0; i < PP; ++i) dbacc[g][i] = 0.0f;
+
+        if constexpr (!MULTI) {
+            __syncthreads();
+            for (int j = threadIdx.x; j < 2 * BT * HP * ESZ / 4; j += blockDim.x) ((uint32_t*)gbuf)[j] = 0u;
+            __syncthreads();
+        }
+
+        for (int t = T; t >= 1; --t) {
+            if (ks == 0) {
+                // ---- loads of this step (independent of the recurrence)
+                float cv[NC][PP], sc[S][PP], sp[S][PP], dh_ext[PP];
+#pragma unroll
+                for (int c2 = 0; c2 < NC; ++c2) load_io<BF16, PP>(p.cache, ((((size_t)(t - 1) * B + bb) * NH + n) * NC + c2) * D + e0, cv[c2]);
+#pragma unroll
+                for (int s = 0; s < S; ++s) {
+                    if (CELL != CELL_GRU && s > 0 && s < 3) load_f32<PP>(p.states, ((((size_t)t * S + s) * B + bb) * NH + n) * D + e0, sc[s]);
+                    else
+#pragma unroll
+                        for (int i = 0; i < PP; ++i) sc[s][i] = 1.0f;
+                    if ((CELL == CELL_GRU) ? (s == 0) : (s > 0 && s < 3))
+                        load_f32<PP>(p.states, ((((size_t)(t - 1) * S + s) * B + bb) * NH + n) * D + e0, sp[s]);
+                    else
+#pragma unroll
+                        for (int i = 0; i < PP; ++i) sp[s][i] = 1.0f;
+                }
+                load_io<BF16, PP>(p.dH, (((size_t)(t - 1) * B + bb) * NH + n) * D + e0, dh_ext);
+                // ---- point-wise Jacobians
+                float dwx[G][PP], dg[G][PP];
+#pragma unroll
+                for (int i = 0; i < PP; ++i) {
+                    float cvi[NC], sci[S], spi[S], dsi[S], dwxi[G], dgi[G];
+#pragma unroll
+                    for (int c2 = 0; c2 < NC; ++c2) cvi[c2] = cv[c2][i];
+#pragma unroll
+                    for (int s = 0; s < S; ++s) { sci[s] = sc[s][i]; spi[s] = sp[s][i]; dsi[s] = ds[s][i]; }
+                    dsi[0] += dh_ext[i];
+                    Cell<CELL, BF16>::bwd(cvi, sci, spi, dsi, dwxi, dgi);
+#pragma unroll
+                    for (int s = 0; s < S; ++s) ds[s][i] = dsi[s];
+#pragma unroll
+                    for (int g = 0; g < G; ++g) { dwx[g][i] = dwxi[g]; dg[g][i] = dgi[g]; dbacc[g][i] += dgi[g]; }
+                }
+                // ---- hand dg_t to the other waves, then stream out dWx
+                if constexpr (!MULTI) {
+#pragma unroll
+                    for (int g = 0; g < G; ++g)
+                        write_operand_lds<BF16, PP>(gbuf + ((size_t)(t & 1) * BT + lm.bslot) * HP * ESZ, g * D + e0, dg[g]);
+                } else {
+                    const uint32_t cnt = (uint32_t)iter * (uint32_t)T + (uint32_t)(T - t);
+#pragma unroll
+                    for (int g = 0; g < G; ++g)
+                        publish4<BF16>(xr, (cnt & 1u) * xbuf + xgroup + (uint32_t)lm.bslot * XROW, g * D + e0, dg[g], cnt + 1u);
+                }
+                if (lane_ok) {
+#pragma unroll
+                    for (int g = 0; g < G; ++g) store_io<BF16, PP>(p.dWx, ((((size_t)(t - 1) * B + bb) * G + g) * NH + n) * D + e0, dwx[g]);
+                    if constexpr (CELL == CELL_GRU) store_io<BF16, PP>(p.dgn, (((size_t)(t - 1) * B + bb) * NH + n) * D + e0, dg[2]);
+                }
+            }
+            // ---- dh_{t-1} += R dg_t on the matrix cores; four accumulators break the dependent chain
+            f32x4 a4[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) a4[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if constexpr (!MULTI) {
+                __syncthreads();
+                op_t gB[KT];
+                read_operand_lds<BF16, KT>(gbuf + ((size_t)(t & 1) * BT + lm.bslot) * HP * ESZ, k0, lm.quad, gB);
+#pragma unroll
+                for (int kt = 0; kt < KT; ++kt) a4[kt & 3] = OP::mfma(Rf[kt], gB[kt], a4[kt & 3]);
+            } else {
+                const uint32_t cnt = (uint32_t)iter * (uint32_t)T + (uint32_t)(T - t);
+                const uint32_t row_off = (cnt & 1u) * xbuf + xgroup + (uint32_t)lm.c * XROW;
+#pragma unroll
+                for (int kc = 0; kc < KT; kc += KC) {
+                    op_t gB[KC];
+                    if (!failed) failed = !poll_operand<BF16, KT, KC>(xr, row_off, k0, kc, lm.quad, cnt + 1u, p.spin_limit, p.err, gB);
+                    if (failed) {
+#pragma unroll
+                        for (int j = 0; j < KC; ++j) gB[j] = op_t{};
+                    }
+#pragma unroll
+                    for (int j = 0; j < KC; ++j) a4[(kc + j) & 3] = OP::mfma(Rf[kc + j], gB[j], a4[(kc + j) & 3]);
+                }
+            }
+            f32x4 acc[1];
+            acc[0] = (a4[0] + a4[1]) + (a4[2] + a4[3]);
+            reduce_slices<1, KS>(red, t & 1, ks, wu, p.NWU, lane, acc);
+            if (ks == 0) {
+                compact_tile<BT>(acc[0]);
+#pragma unroll
+                for (int i = 0; i < PP; ++i) ds[0][i] += acc[0][i];
+            }
+        }
+        // ---- gradients w.r.t. the initial states, per-row partial sums of db
+        if (lane_ok) {
+#pragma unroll
+            for (int s = 0; s < S; ++s) store_f32<PP>(p.dstates0, (((size_t)s * B + bb) * NH + n) * D + e0, ds[s]);
+#pragma unroll
+            for (int g = 0; g < G; ++g) store_f32<PP>(p.db_part, (((size_t)bb * NH + n) * G + g) * D + e0, dbacc[g]);
+        }
+    }
+}
+
+}  // namespace flashrnn

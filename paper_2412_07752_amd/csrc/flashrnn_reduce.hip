@@ -1,0 +1,228 @@
+// Weight-gradient reduction after the backward time loop (paper Sec. 4 eq. (6)-(7)):
+//     dR[n,d,g,e] = sum_{t,b} h_{t-1}[b,n,d] * dg_t[b,g,n,e]        db[n,g,e] = sum_{t,b} dg_t[b,g,n,e]
+// dR is one GEMM per head with the (t,b) axis contracted: M = D, N = G*D, K = T*B.  It is the one
+// dense, MFMA-bound contraction of the method and runs outside the sequential loop.  Both operands
+// have the contraction axis as their slow memory axis, so tiles are transposed through LDS.
+// Split-K partial sums are written separately and added in a fixed order (no float atomics).
+#include "flashrnn_common.h"
+#include "flashrnn_host.h"
+
+namespace flashrnn {
+
+constexpr int TM = 64;    // d rows per workgroup
+constexpr int TN = 128;   // (g,e) columns per workgroup
+constexpr int TK = 32;    // contraction rows per LDS round
+
+// LDS tiles hold the operands transposed: [row or column][k], bf16 pairs packed along k (BF16) or floats.
+template <bool BF16>
+__global__ __launch_bounds__(256) void dr_gemm_kernel(const float* __restrict__ states, const void* __restrict__ dWx,
+                                                      const void* __restrict__ dgn, float* __restrict__ out, int T, int B, int NH,
+                                                      int D, int G, int S, int SK, int gru) {
+    constexpr int PITCH = BF16 ? (TK + 8) : (TK + 4);  // elements per LDS row
+    constexpr int ESZ = BF16 ? 2 : 4;
+    __shared__ __align__(16) char ldsA[TM * PITCH * ESZ];
+    __shared__ __align__(16) char ldsB[TN * PITCH * ESZ];
+    const int GD = G * D;
+    const int tiles_n = (GD + TN - 1) / TN, tiles_m = (D + TM - 1) / TM;
+    int bid = blockIdx.x;
+    const int tn = bid % tiles_n; bid /= tiles_n;
+    const int tm = bid % tiles_m; bid /= tiles_m;
+    const int sk = bid % SK;
+    const int n = bid / SK;
+    const int K = T * B;
+    const int kchunk = ((K + SK - 1) / SK + TK - 1) / TK * TK;
+    const int kbeg = sk * kchunk, kend = min(K, kbeg + kchunk);
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int c = lane & 15, quad = lane >> 4;
+    const int wm = w >> 1, wn = w & 1;  // wave tile: rows [32 wm, +32), columns [64 wn, +64)
+
+    f32x4 acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // loader roles: A: thread -> k pair (2 rows) x 4 consecutive d;  B: thread -> k pair x 8 consecutive columns
+    const int a_kp = tid >> 4, a_d = (tid & 15) * 4;        // 16 k pairs x 16 column groups
+    const int b_kp = tid >> 4, b_j = (tid & 15) * 8;        // 16 k pairs x 16 column groups of 8
+    const int d_glob = tm * TM + a_d;
+    const int j_glob = tn * TN + b_j;
+    const bool a_ok = d_glob < D, b_ok = j_glob < GD;
+    const int bg = b_ok ? j_glob / D : 0, be = b_ok ? j_glob % D : 0;
+    const bool b_from_dgn = gru && bg == 2;
+
+    for (int kb = kbeg; kb < kend; kb += TK) {
+        // ---- global loads (rows k = (tt, b)): A row = h_{tt}, tt = 0..T-1 is the state before step tt+1
+        float av[2][4];
+        float bv[2][8];
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const int k = kb + a_kp * 2 + r;
+            if (a_ok && k < kend) {
+                const int tt = k / B, b = k % B;
+                load_f32<4>(states, ((((size_t)tt * S + 0) * B + b) * NH + n) * D + d_glob, av[r]);
+            } else {
+                av[r][0] = av[r][1] = av[r][2] = av[r][3] = 0.f;
+            }
+            const int k2 = kb + b_kp * 2 + r;
+            if (b_ok && k2 < kend) {
+                const int tt = k2 / B, b = k2 % B;
+                const size_t idx = b_from_dgn ? (((size_t)tt * B + b) * NH + n) * D + be
+                                              : ((((size_t)tt * B + b) * G + bg) * NH + n) * D + be;
+                const void* src = b_from_dgn ? dgn : dWx;
+                float lo[4], hi[4];
+                load_io<BF16, 4>(src, idx, lo);
+                load_io<BF16, 4>(src, idx + 4, hi);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) { bv[r][i] = lo[i]; bv[r][4 + i] = hi[i]; }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) bv[r][i] = 0.f;
+            }
+        }
+        __syncthreads();  // previous round's reads are done
+        if constexpr (BF16) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                *(uint32_t*)(ldsA + ((a_d + i) * PITCH + a_kp * 2) * 2) = f32_to_bf16_bits(av[0][i]) | (f32_to_bf16_bits(av[1][i]) << 16);
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                *(uint32_t*)(ldsB + ((b_j + i) * PITCH + b_kp * 2) * 2) = f32_to_bf16_bits(bv[0][i]) | (f32_to_bf16_bits(bv[1][i]) << 16);
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) *(float2*)(ldsA + ((a_d + i) * PITCH + a_kp * 2) * 4) = make_float2(av[0][i], av[1][i]);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) *(float2*)(ldsB + ((b_j + i) * PITCH + b_kp * 2) * 4) = make_float2(bv[0][i], bv[1][i]);
+        }
+        __syncthreads();
+        if constexpr (BF16) {
+            bf16x8 af[2], bf[4];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) af[i] = *(const bf16x8*)(ldsA + ((wm * 32 + i * 16 + c) * PITCH + quad * 8) * 2);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) bf[j] = *(const bf16x8*)(ldsB + ((wn * 64 + j * 16 + c) * PITCH + quad * 8) * 2);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+        } else {
+#pragma unroll
+            for (int kk = 0; kk < TK / 4; ++kk) {
+                float af[2], bf[4];
+#pragma unroll
+                for (int i = 0; i < 2; ++i) af[i] = *(const float*)(ldsA + ((wm * 32 + i * 16 + c) * PITCH + kk * 4 + quad) * 4);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) bf[j] = *(const float*)(ldsB + ((wn * 64 + j * 16 + c) * PITCH + kk * 4 + quad) * 4);
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[i], bf[j], acc[i][j], 0, 0, 0);
+            }
+        }
+    }
+    // ---- store: lane holds column c and rows 4*quad + r of each 16x16 tile
+    float* dst = out + ((size_t)sk * NH + n) * (size_t)D * GD;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int col = tn * TN + wn * 64 + j * 16 + c;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int row = tm * TM + wm * 32 + i * 16 + quad * 4 + r;
+                if (row < D && col < GD) dst[(size_t)row * GD + col] = acc[i][j][r];
+            }
+        }
+}
+
+// out[j] = sum_{s < NS} part[s * stride + j], added in index order
+__global__ void sum_slices_kernel(const float* __restrict__ part, float* __restrict__ out, size_t count, int NS, size_t stride) {
+    const size_t j = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= count) return;
+    float a = 0.f;
+    for (int s = 0; s < NS; ++s) a += part[(size_t)s * stride + j];
+    out[j] = a;
+}
+
+__global__ void fill_zero_kernel(uint32_t* __restrict__ p, size_t count) {
+    const size_t j = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j < count) p[j] = 0u;
+}
+
+// Packed copies of R for the persistent kernels (made once per call, R is read once per launch):
+//   forward   Rt[n][g][e][k] = R[n][k][g][e]   (k = previous-state index, padded with zeros to DK)
+//   backward  Rb[n][d][k]    = R[n][d][k]       (k = gate * D + unit,    padded with zeros to DK)
+template <typename T>
+__global__ void pack_r_fwd_kernel(const T* __restrict__ R, T* __restrict__ out, int NH, int D, int G, int DK) {
+    const size_t j = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t total = (size_t)NH * G * D * DK;
+    if (j >= total) return;
+    const int k = (int)(j % DK);
+    size_t r = j / DK;
+    const int e = (int)(r % D); r /= D;
+    const int g = (int)(r % G);
+    const int n = (int)(r / G);
+    out[j] = k < D ? R[(((size_t)n * D + k) * G + g) * D + e] : T(0);
+}
+template <typename T>
+__global__ void pack_r_bwd_kernel(const T* __restrict__ R, T* __restrict__ out, int NH, int D, int G, int DK) {
+    const size_t j = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t total = (size_t)NH * D * DK;
+    if (j >= total) return;
+    const int k = (int)(j % DK);
+    const size_t row = j / DK;  // n * D + d
+    out[j] = k < G * D ? R[row * (size_t)(G * D) + k] : T(0);
+}
+
+hipError_t launch_pack_r(bool bf16, bool bwd, const void* R, void* out, int NH, int D, int G, int DK, hipStream_t stream) {
+    const size_t total = bwd ? (size_t)NH * D * DK : (size_t)NH * G * D * DK;
+    const dim3 grid((unsigned)((total + 255) / 256)), block(256);
+    if (bf16) {
+        if (bwd) hipLaunchKernelGGL(pack_r_bwd_kernel<uint16_t>, grid, block, 0, stream, (const uint16_t*)R, (uint16_t*)out, NH, D, G, DK);
+        else hipLaunchKernelGGL(pack_r_fwd_kernel<uint16_t>, grid, block, 0, stream, (const uint16_t*)R, (uint16_t*)out, NH, D, G, DK);
+    } else {
+        if (bwd) hipLaunchKernelGGL(pack_r_bwd_kernel<float>, grid, block, 0, stream, (const float*)R, (float*)out, NH, D, G, DK);
+        else hipLaunchKernelGGL(pack_r_fwd_kernel<float>, grid, block, 0, stream, (const float*)R, (float*)out, NH, D, G, DK);
+    }
+    return hipGetLastError();
+}
+
+int dr_split_k(int T, int B, int NH, int D, int G) {
+    const int tiles = NH * ((D + TM - 1) / TM) * ((G * D + TN - 1) / TN);
+    const int K = T * B;
+    int sk = 1;
+    while (tiles * sk < 512 && K / (sk * 2) >= 4 * TK && sk < 64) sk *= 2;
+    return sk;
+}
+
+hipError_t launch_dr_gemm(bool bf16, const float* states, const void* dWx, const void* dgn, float* part, float* dR, int T, int B,
+                          int NH, int D, int G, int S, bool gru, hipStream_t stream) {
+    const int SK = dr_split_k(T, B, NH, D, G);
+    const int GD = G * D;
+    const int grid = NH * SK * ((D + TM - 1) / TM) * ((GD + TN - 1) / TN);
+    float* target = SK == 1 ? dR : part;
+    if (bf16) hipLaunchKernelGGL(dr_gemm_kernel<true>, dim3(grid), dim3(256), 0, stream, states, dWx, dgn, target, T, B, NH, D, G, S, SK, gru ? 1 : 0);
+    else hipLaunchKernelGGL(dr_gemm_kernel<false>, dim3(grid), dim3(256), 0, stream, states, dWx, dgn, target, T, B, NH, D, G, S, SK, gru ? 1 : 0);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (SK > 1) {
+        const size_t count = (size_t)NH * D * GD;
+        hipLaunchKernelGGL(sum_slices_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, stream, part, dR, count, SK, count);
+        e = hipGetLastError();
+    }
+    return e;
+}
+
+hipError_t launch_sum_slices(const float* part, float* out, size_t count, int NS, size_t stride, hipStream_t stream) {
+    hipLaunchKernelGGL(sum_slices_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, stream, part, out, count, NS, stride);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t stream) {
+    const size_t count = bytes / 4;
+    if (count == 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, stream, (uint32_t*)p, count);
+    return hipGetLastError();
+}
+
+}  // namespace flashrnn

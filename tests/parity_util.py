@@ -1,0 +1,94 @@
+"""Helpers of the GPU parity tests: run one workload through the oracle (fp64, CPU) and through the
+C-ABI library (GPU) on the same seeded inputs, and measure the differences.
+
+Error measure per output tensor: max|gpu - ref| / max(max|ref|, tiny)  ("rel"), and max|gpu - ref| ("abs").
+"""
+import numpy as np
+import torch
+
+import oracle
+from paper_2412_07752_amd import api, synth
+
+# spec tolerances
+TOL_F32_REL = 1e-5
+TOL_BF16_REL = 2e-2
+TOL_BF16_ABS_H = 5e-2
+
+
+def to_device(a, dtype):
+    """float32 numpy array (already representable in the I/O dtype) -> device tensor of that dtype."""
+    if a is None:
+        return None
+    if dtype == "bf16":
+        bits = synth.bf16_bits(a)
+        return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+
+def to_host64(t):
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def err(gpu, ref):
+    gpu = np.asarray(gpu, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if ref.size == 0:
+        return 0.0, 0.0
+    d = float(np.max(np.abs(gpu - ref)))
+    if not np.isfinite(d):
+        return float("inf"), float("inf")
+    return d / max(float(np.max(np.abs(ref))), 1e-30), d
+
+
+def run_oracle(w, inp, dstates_last=None):
+    f64 = lambda a: None if a is None else a.astype(np.float64)
+    st = oracle.fwd(w.cell, f64(inp["Wx"]), f64(inp["R"]), f64(inp["b"]), f64(inp["states0"]))
+    out = {"states": st}
+    if w.backward:
+        dWx, dR, db, ds0 = oracle.bwd(w.cell, f64(inp["Wx"]), f64(inp["R"]), f64(inp["b"]), st, f64(inp["dH"]), f64(dstates_last))
+        out.update(dWx=dWx, dR=dR, db=db, dstates0=ds0)
+    return out
+
+
+def run_gpu(w, inp, dstates_last=None, check=True):
+    Wx, R, b = (to_device(inp[k], w.dtype) for k in ("Wx", "R", "b"))
+    s0 = to_device(inp["states0"], "f32")
+    states, cache, ws = api.flashrnn_fwd(w.cell, Wx, R, b, s0, save_for_backward=w.backward)
+    desc = api.make_desc(w.cell, w.T, w.B, w.NH, w.D, api.FLASHRNN_BF16 if w.dtype == "bf16" else api.FLASHRNN_F32)
+    if check:
+        api.flashrnn_check(desc, ws)
+    out = {"states": to_host64(states)}
+    if w.backward:
+        dH = to_device(inp["dH"], w.dtype)
+        dl = to_device(dstates_last, "f32")
+        dWx, dR, db, ds0 = api.flashrnn_bwd(w.cell, R, b, states, cache, dH, dl, workspace=ws)
+        if check:
+            api.flashrnn_check(desc, ws)
+        out.update(dWx=to_host64(dWx), dR=to_host64(dR), db=to_host64(db), dstates0=to_host64(ds0))
+    torch.cuda.synchronize()
+    return out
+
+
+def compare(w, gpu, ref):
+    """dict name -> (rel, abs); states are split per state so that a small state is not hidden by a large one."""
+    res = {}
+    names = "hcnm"
+    for s in range(w.S):
+        res[f"states.{names[s]}"] = err(gpu["states"][:, s], ref["states"][:, s])
+    for k in ("dWx", "dR", "db"):
+        if k in ref:
+            res[k] = err(gpu[k], ref[k])
+    if "dstates0" in ref:
+        for s in range(w.S):
+            res[f"dstates0.{names[s]}"] = err(gpu["dstates0"][s], ref["dstates0"][s])
+    return res
+
+
+def assert_close(w, res):
+    rel = TOL_BF16_REL if w.dtype == "bf16" else TOL_F32_REL
+    for k, (r, a) in res.items():
+        assert np.isfinite(r), f"{w.name} {k}: non-finite"
+        # a reference that is identically zero (e.g. dstates0 of the stabilizer) must be matched exactly
+        assert r <= rel or a == 0.0, f"{w.name} {k}: rel {r:.3e} abs {a:.3e} > {rel}"
+    if w.dtype == "bf16":
+        assert res["states.h"][1] <= TOL_BF16_ABS_H, f"{w.name} h: abs {res['states.h'][1]:.3e}"
