@@ -105,8 +105,11 @@ int flashrnn_bwd(const flashrnn_desc_t* desc, const void* R, const void* b, cons
 
 /*
  * Reads the error word the kernels of the last call on this workspace left behind (synchronizes
- * the stream).  Returns FLASHRNN_OK, FLASHRNN_ERR_TIMEOUT if a cross-CU wait ran into its spin
- * limit (results are then invalid), or FLASHRNN_ERR_LAUNCH.  workspace may be NULL (returns OK).
+ * the stream).  The spin limit of the cross-CU waits is 2^21 polls; the environment variable
+ * FLASHRNN_SPIN_LIMIT overrides it (a negative value makes every wait give up at once, which
+ * exercises this error path without hanging anything).  Returns FLASHRNN_OK, FLASHRNN_ERR_TIMEOUT
+ * if a cross-CU wait ran into its spin limit (results are then invalid), or FLASHRNN_ERR_LAUNCH.
+ * workspace may be NULL (returns OK).
  */
 int flashrnn_check(const flashrnn_desc_t* desc, const void* workspace, void* hip_stream);
 

@@ -77,6 +77,7 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
     const int force_bt = env_int("FLASHRNN_BT", 0);
     const int force_nwu = env_int("FLASHRNN_NWU", 0);
     const int force_ks = env_int("FLASHRNN_KS", 0);
+    const int force_gpar = env_int("FLASHRNN_GPAR", 0);      // groups in flight when groups are split (testing the group loop)
     Plan pl;
 
     if (force_multi != 1) {
@@ -144,6 +145,7 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
                 if (chosen) gpar = kXcds * (cap / (units16 / chosen));
                 if (gpar > NG) gpar = NG;
             }
+            if (chosen && force_gpar > 0 && force_gpar < gpar) gpar = force_gpar;
             if (chosen) {
                 pl.e = best;
                 pl.NWU = chosen;

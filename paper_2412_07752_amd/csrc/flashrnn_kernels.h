@@ -174,6 +174,12 @@ __device__ __forceinline__ bool poll_operand(__amdgpu_buffer_rsrc_t rs, uint32_t
     i32x4 raw[NL];
     bool good = false;
     int spins = 0;
+    if (spin_limit < 0) {  // host-forced failure (tests of the error path): give up without looking
+        __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int j = 0; j < KC; ++j) hB[j] = typename Operand<BF16>::type{};
+        return false;
+    }
     while (true) {
 #pragma unroll
         for (int j = 0; j < NL; ++j) {

@@ -1,0 +1,43 @@
+"""The five benchmark configurations at full size, in the launch configuration bench.py times.
+
+C1-C4: every output element against the oracle.  C5 (0.8 TFLOP in fp64): the GPU runs the whole
+problem; the oracle runs two of its eight heads (heads are independent, so a head's slice of every
+output is computed exactly, including dR/db which sum over the whole batch and all steps)."""
+import numpy as np
+import pytest
+
+import parity_util as pu
+from paper_2412_07752_amd import api, synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("idx", [0, 1, 2, 3])
+def test_config_full_size(idx):
+    w = synth.CONFIGS[idx]
+    print(f"config {w.name}", flush=True)
+    inp = synth.make_inputs(w)
+    ref = pu.run_oracle(w, inp)
+    gpu = pu.run_gpu(w, inp)
+    res = pu.compare(w, gpu, ref)
+    print({k: f"{r:.2e}/{a:.2e}" for k, (r, a) in res.items()}, flush=True)
+    pu.assert_close(w, res)
+
+
+def test_config5_full_size_gpu_against_oracle_on_sampled_heads():
+    w = synth.CONFIGS[4]
+    print(f"config {w.name}: drawing inputs", flush=True)
+    inp = synth.make_inputs(w)
+    print("running GPU", flush=True)
+    gpu = pu.run_gpu(w, inp)
+    for n in (0, w.NH - 1):
+        print(f"oracle on head {n}", flush=True)
+        sub = synth.Workload(f"{w.name}_head{n}", w.cell, w.T, w.B, 1, w.D, w.dtype, True)
+        sinp = {"Wx": np.ascontiguousarray(inp["Wx"][:, :, :, n:n + 1]), "R": inp["R"][n:n + 1], "b": inp["b"][n:n + 1],
+                "states0": np.ascontiguousarray(inp["states0"][:, :, n:n + 1]), "dH": np.ascontiguousarray(inp["dH"][:, :, n:n + 1])}
+        ref = pu.run_oracle(sub, sinp)
+        g = {"states": gpu["states"][:, :, :, n:n + 1], "dWx": gpu["dWx"][:, :, :, n:n + 1], "dR": gpu["dR"][n:n + 1],
+             "db": gpu["db"][n:n + 1], "dstates0": gpu["dstates0"][:, :, n:n + 1]}
+        res = pu.compare(sub, g, ref)
+        print({k: f"{r:.2e}/{a:.2e}" for k, (r, a) in res.items()}, flush=True)
+        pu.assert_close(sub, res)

@@ -1,0 +1,161 @@
+"""GPU parity tests: the HIP path through the C ABI against the fp64 oracle, element by element,
+on the same seeded inputs.  Tolerances (per output tensor, max-norm relative): 1e-5 for f32 I/O,
+2e-2 for bf16 I/O plus max-abs 5e-2 on h."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import parity_util as pu
+from paper_2412_07752_amd import api, synth
+from paper_2412_07752_amd.synth import CELL_GRU, CELL_LSTM, CELL_SLSTM, Workload
+
+pytestmark = pytest.mark.gpu
+CELLS = [CELL_LSTM, CELL_GRU, CELL_SLSTM]
+PLAN_ENV = ("FLASHRNN_MULTI", "FLASHRNN_BT", "FLASHRNN_NWU", "FLASHRNN_KS", "FLASHRNN_GPAR", "FLASHRNN_SPIN_LIMIT")
+
+
+@pytest.fixture(autouse=True)
+def clean_env():
+    for k in PLAN_ENV:
+        os.environ.pop(k, None)
+    os.environ["FLASHRNN_SPIN_LIMIT"] = "400000"
+    yield
+    for k in PLAN_ENV:
+        os.environ.pop(k, None)
+
+
+def _dlast(w, seed=99):
+    rng = np.random.default_rng(seed)
+    return rng.standard_normal((w.S, w.B, w.NH, w.D)).astype(np.float32)
+
+
+def _check(w, env=None, with_dlast=False):
+    os.environ.update(env or {})
+    print(f"case {w.name} env={env}", flush=True)
+    inp = synth.make_inputs(w)
+    dl = _dlast(w) if (with_dlast and w.backward) else None
+    ref = pu.run_oracle(w, inp, dl)
+    gpu = pu.run_gpu(w, inp, dl)
+    res = pu.compare(w, gpu, ref)
+    pu.assert_close(w, res)
+    return gpu
+
+
+@pytest.mark.parametrize("cell", CELLS)
+@pytest.mark.parametrize("dtype,D", [("bf16", 16), ("bf16", 32), ("bf16", 48), ("bf16", 64), ("bf16", 96), ("bf16", 128),
+                                     ("bf16", 160), ("bf16", 192), ("f32", 16), ("f32", 48), ("f32", 64), ("f32", 96),
+                                     ("f32", 128)])
+def test_one_workgroup_per_group(cell, dtype, D):
+    """Ragged batch (13 rows), several heads, non-zero initial states and final-state gradients."""
+    w = Workload(f"single_{cell}_{dtype}_D{D}", cell, 9, 13, 2, D, dtype, True, bias="uniform0.1", init="uniform0.1", seed=D)
+    _check(w, with_dlast=True)
+
+
+@pytest.mark.parametrize("cell", CELLS)
+@pytest.mark.parametrize("bt", [16, 8, 4])
+def test_batch_tiles(cell, bt):
+    """Batch tiles of 16, 8 and 4 rows (idle MFMA lanes take over point-wise work); 21 rows = ragged last tile."""
+    w = Workload(f"bt{bt}_{cell}", cell, 11, 21, 3, 64, "bf16", True, bias="forget3" if cell != CELL_GRU else "uniform0.1",
+                 init="uniform0.1", seed=bt)
+    _check(w, {"FLASHRNN_BT": str(bt)}, with_dlast=True)
+
+
+@pytest.mark.parametrize("cell", CELLS)
+@pytest.mark.parametrize("dtype,D,env", [
+    ("bf16", 64, {"FLASHRNN_NWU": "1"}), ("bf16", 64, {"FLASHRNN_NWU": "2"}), ("bf16", 128, {"FLASHRNN_NWU": "2"}),
+    ("bf16", 192, {"FLASHRNN_NWU": "4"}), ("bf16", 128, {"FLASHRNN_KS": "4"}), ("bf16", 256, {}), ("bf16", 384, {}),
+    ("f32", 64, {"FLASHRNN_NWU": "1"}), ("f32", 128, {"FLASHRNN_KS": "4"}), ("f32", 192, {}), ("f32", 256, {}),
+])
+def test_groups_split_over_workgroups(cell, dtype, D, env):
+    """A head served by several workgroups that exchange h (forward) / dg (backward) every step."""
+    e = {"FLASHRNN_MULTI": "1"}
+    e.update(env)
+    w = Workload(f"multi_{cell}_{dtype}_D{D}", cell, 10, 19, 2, D, dtype, True, bias="uniform0.1", init="uniform0.1", seed=D + 1)
+    _check(w, e, with_dlast=True)
+
+
+@pytest.mark.parametrize("cell", CELLS)
+def test_group_loop_when_groups_do_not_fit(cell):
+    """More groups than run at once: workgroups loop over groups and reload R per head."""
+    w = Workload(f"loop_{cell}", cell, 7, 40, 3, 64, "bf16", True, bias="uniform0.1", init="uniform0.1", seed=5)
+    _check(w, {"FLASHRNN_MULTI": "1", "FLASHRNN_NWU": "2", "FLASHRNN_GPAR": "4"}, with_dlast=True)
+
+
+@pytest.mark.parametrize("cell", CELLS)
+@pytest.mark.parametrize("T", [0, 1])
+def test_degenerate_lengths(cell, T):
+    w = Workload(f"T{T}_{cell}", cell, T, 5, 2, 32, "bf16", True, bias="uniform0.1", init="uniform0.1")
+    gpu = _check(w, with_dlast=True)
+    if T == 0:
+        assert np.all(gpu["dR"] == 0) and np.all(gpu["db"] == 0)
+
+
+def test_large_single_head_split_with_contraction_slices():
+    """D = 768 in one head (R is 4.7 MB): 24 workgroups x 2 unit waves x 4 contraction slices."""
+    w = Workload("lstm_D768", CELL_LSTM, 12, 16, 1, 768, "bf16", True, seed=3)
+    _check(w)
+    wg, per_head, waves = api.flashrnn_plan(api.make_desc(CELL_LSTM, 12, 16, 1, 768, api.FLASHRNN_BF16))
+    assert wg == per_head == 24 and waves == 8
+
+
+def test_runs_are_bitwise_reproducible():
+    """No float atomics anywhere: two runs give identical bits (single and split groups)."""
+    for env in ({}, {"FLASHRNN_MULTI": "1", "FLASHRNN_NWU": "1"}):
+        os.environ.update(env)
+        w = Workload("repro", CELL_SLSTM, 16, 16, 2, 64, "bf16", True, bias="forget3", init="uniform0.1")
+        inp = synth.make_inputs(w)
+        a = pu.run_gpu(w, inp)
+        b = pu.run_gpu(w, inp)
+        for k in a:
+            assert np.array_equal(a[k], b[k]), k
+
+
+def test_chunked_sequence_equals_one_call():
+    """states0 in / last states out: T1 steps then T2 steps from the saved states == T1 + T2 steps (f32 path, exact)."""
+    w = Workload("chunk", CELL_SLSTM, 12, 8, 2, 32, "f32", False, bias="forget3", init="uniform0.1")
+    inp = synth.make_inputs(w)
+    Wx, R, b = (pu.to_device(inp[k], "f32") for k in ("Wx", "R", "b"))
+    s0 = pu.to_device(inp["states0"], "f32")
+    full, _, _ = api.flashrnn_fwd(w.cell, Wx, R, b, s0, save_for_backward=False)
+    a, _, _ = api.flashrnn_fwd(w.cell, Wx[:7].contiguous(), R, b, s0, save_for_backward=False)
+    c, _, _ = api.flashrnn_fwd(w.cell, Wx[7:].contiguous(), R, b, a[7].contiguous(), save_for_backward=False)
+    torch.cuda.synchronize()
+    assert torch.equal(torch.cat([a, c[1:]]), full)
+
+
+def test_exchange_timeout_is_reported_not_hung():
+    """Negative spin limit: every cross-CU wait gives up at once, every kernel still runs to its end,
+    flashrnn_check reports the timeout, and the next call with a normal limit is correct again."""
+    w = Workload("timeout", CELL_LSTM, 6, 16, 1, 64, "bf16", False)
+    inp = synth.make_inputs(w)
+    os.environ.update({"FLASHRNN_MULTI": "1", "FLASHRNN_NWU": "1", "FLASHRNN_SPIN_LIMIT": "-1"})
+    with pytest.raises(api.FlashRNNError) as ei:
+        pu.run_gpu(w, inp)
+    assert ei.value.status == api.FLASHRNN_ERR_TIMEOUT
+    os.environ["FLASHRNN_SPIN_LIMIT"] = "400000"
+    ref = pu.run_oracle(w, inp)
+    pu.assert_close(w, pu.compare(w, pu.run_gpu(w, inp), ref))
+
+
+def test_binding_rejects_wrong_shapes_and_dtypes():
+    dev = "cuda"
+    Wx = torch.zeros((4, 2, 4, 1, 32), dtype=torch.bfloat16, device=dev)
+    R = torch.zeros((1, 32, 4, 32), dtype=torch.bfloat16, device=dev)
+    b = torch.zeros((1, 4, 32), dtype=torch.bfloat16, device=dev)
+    with pytest.raises(ValueError):
+        api.flashrnn_fwd(CELL_LSTM, Wx, R[:, :16].contiguous(), b)
+    with pytest.raises(ValueError):
+        api.flashrnn_fwd(CELL_LSTM, Wx, R.float(), b)
+    with pytest.raises(ValueError):
+        api.flashrnn_fwd(CELL_GRU, Wx, R, b)
+    with pytest.raises(TypeError):
+        api.flashrnn_fwd(CELL_LSTM, Wx.half(), R.half(), b.half())
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device=dev)
+    d = api.make_desc(CELL_LSTM, 4, 2, 1, 32, api.FLASHRNN_BF16)
+    import ctypes
+    st = torch.empty((5, 2, 2, 1, 32), dtype=torch.float32, device=dev)
+    rc = api.lib().flashrnn_fwd(ctypes.byref(d), Wx.data_ptr(), R.data_ptr(), b.data_ptr(), None, st.data_ptr(), None,
+                                ws.data_ptr() + 8, None)
+    assert rc == api.FLASHRNN_ERR_WORKSPACE
