@@ -120,6 +120,18 @@ int flashrnn_check(const flashrnn_desc_t* desc, const void* workspace, void* hip
  */
 int flashrnn_plan(const flashrnn_desc_t* desc, int backward, int* workgroups, int* cus_per_head, int* waves_per_wg);
 
+/*
+ * Measurement aid (the only state the library keeps; meant for benchmarks, not thread-hot paths).
+ * While enabled, every flashrnn_fwd / flashrnn_bwd call records one HIP event immediately before and
+ * one immediately after its persistent time-loop kernel, on the call's stream (up to 256 calls per
+ * direction; later calls are not recorded).  flashrnn_profile_enable(on) also resets the record.
+ * flashrnn_profile_kernel_ms waits for the recorded events and returns the mean duration in
+ * milliseconds of the forward (backward = 0) or backward (backward = 1) persistent kernel and the
+ * number of launches recorded.
+ */
+int flashrnn_profile_enable(int on);
+int flashrnn_profile_kernel_ms(int backward, float* mean_ms, int* launches);
+
 const char* flashrnn_status_string(int status);
 
 #ifdef __cplusplus

@@ -60,6 +60,10 @@ def lib():
         L.flashrnn_check.restype = ctypes.c_int
         L.flashrnn_plan.argtypes = [dp, ctypes.c_int] + [ctypes.POINTER(ctypes.c_int)] * 3
         L.flashrnn_plan.restype = ctypes.c_int
+        L.flashrnn_profile_enable.argtypes = [ctypes.c_int]
+        L.flashrnn_profile_enable.restype = ctypes.c_int
+        L.flashrnn_profile_kernel_ms.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int)]
+        L.flashrnn_profile_kernel_ms.restype = ctypes.c_int
         L.flashrnn_status_string.argtypes = [ctypes.c_int]
         L.flashrnn_status_string.restype = ctypes.c_char_p
         _lib = L
@@ -67,7 +71,8 @@ def lib():
 
 
 EXPORTS = ["flashrnn_num_states", "flashrnn_num_gates", "flashrnn_gate_cache_bytes", "flashrnn_workspace_bytes", "flashrnn_fwd",
-           "flashrnn_bwd", "flashrnn_check", "flashrnn_plan", "flashrnn_status_string"]
+           "flashrnn_bwd", "flashrnn_check", "flashrnn_plan", "flashrnn_profile_enable", "flashrnn_profile_kernel_ms",
+           "flashrnn_status_string"]
 
 
 def status_string(status):
@@ -101,6 +106,21 @@ def flashrnn_plan(desc, backward=False):
     if rc != FLASHRNN_OK:
         raise FlashRNNError(rc, "flashrnn_plan")
     return a.value, b.value, c.value
+
+
+def flashrnn_profile_enable(on):
+    rc = lib().flashrnn_profile_enable(int(bool(on)))
+    if rc != FLASHRNN_OK:
+        raise FlashRNNError(rc, "flashrnn_profile_enable")
+
+
+def flashrnn_profile_kernel_ms(backward):
+    """(mean ms, launches) of the persistent kernel of the recorded forward / backward calls."""
+    ms, n = ctypes.c_float(), ctypes.c_int()
+    rc = lib().flashrnn_profile_kernel_ms(int(bool(backward)), ctypes.byref(ms), ctypes.byref(n))
+    if rc != FLASHRNN_OK:
+        raise FlashRNNError(rc, "flashrnn_profile_kernel_ms")
+    return ms.value, n.value
 
 
 def _ptr(t):

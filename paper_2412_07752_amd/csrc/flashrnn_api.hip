@@ -205,15 +205,39 @@ int prepare_kernel(const Plan& pl) {
     return FLASHRNN_OK;
 }
 
+// optional bracketing of the persistent kernels with HIP events (flashrnn_profile_*)
+constexpr int kProfSlots = 256;
+struct Profile {
+    bool on = false;
+    int count[2] = {0, 0};
+    hipEvent_t ev[2][kProfSlots][2] = {};
+};
+Profile g_prof;
+std::mutex g_prof_mu;
+
 int launch_persistent(const Plan& pl, KernelParams& kp, hipStream_t stream) {
     if (prepare_kernel(pl) != FLASHRNN_OK) return FLASHRNN_ERR_LAUNCH;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_prof_mu);
+        const int dir = pl.e->bwd;
+        if (g_prof.on && g_prof.count[dir] < kProfSlots) {
+            const int i = g_prof.count[dir]++;
+            for (int j = 0; j < 2; ++j)
+                if (!g_prof.ev[dir][i][j] && hipEventCreate(&g_prof.ev[dir][i][j]) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
+            e0 = g_prof.ev[dir][i][0];
+            e1 = g_prof.ev[dir][i][1];
+        }
+    }
     kp.P = pl.P;
     kp.NWU = pl.NWU;
     kp.NG = pl.NG;
     kp.GPAR = pl.GPAR;
     kp.spin_limit = env_int("FLASHRNN_SPIN_LIMIT", 1 << 21);
     void* args[] = {&kp};
+    if (e0 && hipEventRecord(e0, stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
     if (hipLaunchKernel(pl.e->fn, dim3(pl.grid), dim3(pl.block), args, pl.smem, stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
+    if (e1 && hipEventRecord(e1, stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
     return FLASHRNN_OK;
 }
 
@@ -329,6 +353,28 @@ int flashrnn_check(const flashrnn_desc_t* d, const void* workspace, void* hip_st
     if (hipMemcpyAsync(&flag, workspace, sizeof(int), hipMemcpyDeviceToHost, stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
     if (hipStreamSynchronize(stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
     return flag == 0 ? FLASHRNN_OK : FLASHRNN_ERR_TIMEOUT;
+}
+
+int flashrnn_profile_enable(int on) {
+    std::lock_guard<std::mutex> lock(g_prof_mu);
+    g_prof.on = on != 0;
+    g_prof.count[0] = g_prof.count[1] = 0;
+    return FLASHRNN_OK;
+}
+
+int flashrnn_profile_kernel_ms(int backward, float* mean_ms, int* launches) {
+    std::lock_guard<std::mutex> lock(g_prof_mu);
+    const int dir = backward ? 1 : 0;
+    double sum = 0.0;
+    for (int i = 0; i < g_prof.count[dir]; ++i) {
+        float ms = 0.f;
+        if (hipEventSynchronize(g_prof.ev[dir][i][1]) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
+        if (hipEventElapsedTime(&ms, g_prof.ev[dir][i][0], g_prof.ev[dir][i][1]) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
+        sum += ms;
+    }
+    if (mean_ms) *mean_ms = g_prof.count[dir] ? (float)(sum / g_prof.count[dir]) : 0.f;
+    if (launches) *launches = g_prof.count[dir];
+    return FLASHRNN_OK;
 }
 
 const char* flashrnn_status_string(int status) {
