@@ -65,12 +65,13 @@ struct KernelParams {
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t u16) { return __builtin_bit_cast(float, u16 << 16); }
 
-// round to nearest even; inputs are finite in every use below
-__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
-    uint32_t u = __builtin_bit_cast(uint32_t, f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return u >> 16;
+// f32 -> bf16, round to nearest even: one v_cvt_pk_bf16_f32 on gfx950
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{lo, hi}, bf16x2_t));
 }
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) { return (uint32_t)__builtin_bit_cast(uint16_t, (__bf16)f); }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
@@ -142,11 +143,11 @@ template <bool BF16, int PP> __device__ __forceinline__ void store_io(void* base
         uint16_t* p = (uint16_t*)base + idx;
         if constexpr (PP == 4) {
             uint2 o;
-            o.x = f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16);
-            o.y = f32_to_bf16_bits(v[2]) | (f32_to_bf16_bits(v[3]) << 16);
+            o.x = pack_bf16x2(v[0], v[1]);
+            o.y = pack_bf16x2(v[2], v[3]);
             *(uint2*)p = o;
         } else if constexpr (PP == 2) {
-            *(uint32_t*)p = f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16);
+            *(uint32_t*)p = pack_bf16x2(v[0], v[1]);
         } else {
             *p = (uint16_t)f32_to_bf16_bits(v[0]);
         }
@@ -156,6 +157,15 @@ template <bool BF16, int PP> __device__ __forceinline__ void store_io(void* base
         else if constexpr (PP == 2) *(float2*)p = make_float2(v[0], v[1]);
         else *p = v[0];
     }
+}
+
+// byte-addressed variants: uniform base (kept in scalar registers) + 32-bit per-lane byte offset, the
+// form the global load/store instructions take directly (no per-step 64-bit vector address math)
+template <bool BF16, int PP> __device__ __forceinline__ void load_io_b(const char* sbase, uint32_t voff, float (&out)[PP]) {
+    load_io<BF16, PP>(sbase + voff, 0, out);
+}
+template <bool BF16, int PP> __device__ __forceinline__ void store_io_b(char* sbase, uint32_t voff, const float (&v)[PP]) {
+    store_io<BF16, PP>(sbase + voff, 0, v);
 }
 
 template <int PP> __device__ __forceinline__ void load_f32(const float* base, size_t idx, float (&out)[PP]) {

@@ -216,8 +216,7 @@ __device__ __forceinline__ bool poll_operand(__amdgpu_buffer_rsrc_t rs, uint32_t
 template <bool BF16>
 __device__ __forceinline__ void publish4(__amdgpu_buffer_rsrc_t rs, uint32_t row_off, int k, const float (&v)[4], uint32_t stamp) {
     if constexpr (BF16) {
-        const i32x4 w = {(int)(f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16)), (int)stamp,
-                         (int)(f32_to_bf16_bits(v[2]) | (f32_to_bf16_bits(v[3]) << 16)), (int)stamp};
+        const i32x4 w = {(int)pack_bf16x2(v[0], v[1]), (int)stamp, (int)pack_bf16x2(v[2], v[3]), (int)stamp};
         __builtin_amdgcn_raw_buffer_store_b128(w, rs, row_off + k * 4, 0, kAuxAgent);
     } else {
         const i32x4 w0 = {__builtin_bit_cast(int, v[0]), (int)stamp, __builtin_bit_cast(int, v[1]), (int)stamp};
@@ -243,11 +242,11 @@ template <bool BF16, int PP> __device__ __forceinline__ void write_operand_lds(c
     if constexpr (BF16) {
         if constexpr (PP == 4) {
             uint2 o;
-            o.x = f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16);
-            o.y = f32_to_bf16_bits(v[2]) | (f32_to_bf16_bits(v[3]) << 16);
+            o.x = pack_bf16x2(v[0], v[1]);
+            o.y = pack_bf16x2(v[2], v[3]);
             *(uint2*)(row + k * 2) = o;
         } else if constexpr (PP == 2) {
-            *(uint32_t*)(row + k * 2) = f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16);
+            *(uint32_t*)(row + k * 2) = pack_bf16x2(v[0], v[1]);
         } else {
             *(uint16_t*)(row + k * 2) = (uint16_t)f32_to_bf16_bits(v[0]);
         }
@@ -288,6 +287,7 @@ __device__ __forceinline__ void reduce_slices(float* red, int parity, int ks, in
 // MULTI several workgroups per group, MAXW launch bound in waves.
 // p.R is the packed forward copy of R: Rt[n][g][e][k], k < DK = KT*KS*KSTEP, zero beyond D.
 // The launch guarantees P * NWU * 16 == D, and with MULTI also DK == D.
+// Global addresses are formed as (uniform base advanced per step on the scalar unit) + (32-bit lane offset).
 template <bool BF16> constexpr int poll_chunk(int KT) {
     if (!BF16) return 8;
     if (KT <= 6) return KT;
@@ -301,9 +301,10 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
     using op_t = typename OP::type;
     constexpr int G = CT::G, S = CT::S, NC = CT::NC;
     constexpr int PP = BT / 4;
-    constexpr int ESZ = BF16 ? 2 : 4;               // operand element size in LDS
+    constexpr int ESZ = BF16 ? 2 : 4;               // element size of the I/O dtype and of LDS operand rows
     constexpr int DK = KT * KS * OP::KSTEP;         // padded contraction length
     constexpr int HP = DK + (BF16 ? 8 : 4);         // LDS row pitch in elements
+    constexpr int BUF = BT * HP * ESZ;              // bytes of one LDS operand buffer
     constexpr int KC = poll_chunk<BF16>(KT);
     static_assert(!MULTI || BT == 16, "several workgroups per group exchange full 16-row tiles");
     static_assert(KS == 1 || MULTI, "contraction slices are only used with several workgroups per group");
@@ -328,6 +329,18 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
     const uint32_t xbuf = (uint32_t)p.GPAR * 16u * XROW;       // bytes per buffer
     bool failed = false;
 
+    // uniform strides in bytes
+    const uint32_t HD = (uint32_t)NH * D;
+    const size_t wx_step = (size_t)B * G * HD * ESZ;
+    const uint32_t wx_gate = HD * ESZ;
+    const size_t st_step = (size_t)S * B * HD * 4;
+    const uint32_t st_state = (uint32_t)B * HD * 4;
+    const size_t c_step = (size_t)B * HD * NC * ESZ;
+    const uint32_t c_slot = (uint32_t)D * ESZ;
+    // LDS lane offsets inside one operand buffer
+    const uint32_t lds_rd = (uint32_t)lm.bslot * HP * ESZ;     // row this lane reads as the B operand column
+    const uint32_t lds_wr = (uint32_t)lm.bslot * HP * ESZ;     // row this lane writes its new h into
+
     int iter = 0;
     for (int gid = bm.gpar; gid < p.NG; gid += p.GPAR, ++iter) {
         const int n = gid % NH, q = gid / NH;
@@ -351,22 +364,29 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
         const bool row_valid = bb_raw < B;
         const int bb = row_valid ? bb_raw : B - 1;
         const bool lane_ok = row_valid && ks == 0;
+        // per-group uniform bases and per-lane offsets
+        const char* wx_g = (const char*)p.Wx + (size_t)n * D * ESZ;
+        char* st_g = (char*)p.states + (size_t)n * D * 4;
+        char* c_g = (char*)p.cache + (size_t)n * NC * D * ESZ;
+        const uint32_t voff_wx = ((uint32_t)bb * G * HD + e0) * ESZ;
+        const uint32_t voff_st = ((uint32_t)bb * HD + e0) * 4;
+        const uint32_t voff_c = ((uint32_t)bb * HD * NC + e0) * ESZ;
 
         // ---- initial states
         float st[S][PP];
 #pragma unroll
         for (int s = 0; s < S; ++s) {
-            if (p.states0 != nullptr) load_f32<PP>(p.states0, (((size_t)s * B + bb) * NH + n) * D + e0, st[s]);
+            if (p.states0 != nullptr) load_io_b<false, PP>((const char*)p.states0 + (size_t)n * D * 4 + (size_t)s * st_state, voff_st, st[s]);
             else
 #pragma unroll
                 for (int i = 0; i < PP; ++i) st[s][i] = 0.0f;
-            if (lane_ok) store_f32<PP>(p.states, (((size_t)s * B + bb) * NH + n) * D + e0, st[s]);
+            if (lane_ok) store_io_b<false, PP>(st_g + (size_t)s * st_state, voff_st, st[s]);
         }
         if constexpr (!MULTI) {
             __syncthreads();  // the previous group is done with the operand rows
-            for (int j = threadIdx.x; j < 2 * BT * HP * ESZ / 4; j += blockDim.x) ((uint32_t*)hbuf)[j] = 0u;
+            for (int j = threadIdx.x; j < 2 * BUF / 4; j += blockDim.x) ((uint32_t*)hbuf)[j] = 0u;
             __syncthreads();
-            write_operand_lds<BF16, PP>(hbuf + (size_t)lm.bslot * HP * ESZ, e0, st[0]);
+            write_operand_lds<BF16, PP>(hbuf + lds_wr, e0, st[0]);
             __syncthreads();
         } else {
             if (ks == 0 && T > 0) {
@@ -378,16 +398,16 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
         float wx[G][PP];
         if (T > 0) {
 #pragma unroll
-            for (int g = 0; g < G; ++g) load_io<BF16, PP>(p.Wx, (((size_t)bb * G + g) * NH + n) * D + e0, wx[g]);
+            for (int g = 0; g < G; ++g) load_io_b<BF16, PP>(wx_g + g * wx_gate, voff_wx, wx[g]);
         }
 
         for (int t = 1; t <= T; ++t) {
             // ---- prefetch next step's input pre-activations (clamped at the last step)
             float wxn[G][PP];
             {
-                const int tn = t < T ? t : T - 1;
+                const char* wx_t = wx_g + (size_t)(t < T ? t : T - 1) * wx_step;
 #pragma unroll
-                for (int g = 0; g < G; ++g) load_io<BF16, PP>(p.Wx, ((((size_t)tn * B + bb) * G + g) * NH + n) * D + e0, wxn[g]);
+                for (int g = 0; g < G; ++g) load_io_b<BF16, PP>(wx_t + g * wx_gate, voff_wx, wxn[g]);
             }
             // ---- recurrent product y = R^T h_{t-1} on the matrix cores
             f32x4 acc[G];
@@ -395,7 +415,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
             for (int g = 0; g < G; ++g) acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
             if constexpr (!MULTI) {
                 op_t hB[KT];
-                read_operand_lds<BF16, KT>(hbuf + ((size_t)((t - 1) & 1) * BT + lm.bslot) * HP * ESZ, k0, lm.quad, hB);
+                read_operand_lds<BF16, KT>(hbuf + ((t - 1) & 1) * BUF + lds_rd, k0, lm.quad, hB);
 #pragma unroll
                 for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
@@ -438,7 +458,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
                 }
                 // ---- hand the new h to the other waves first, then stream out states and saved values
                 if constexpr (!MULTI) {
-                    write_operand_lds<BF16, PP>(hbuf + ((size_t)(t & 1) * BT + lm.bslot) * HP * ESZ, e0, st[0]);
+                    write_operand_lds<BF16, PP>(hbuf + (t & 1) * BUF + lds_wr, e0, st[0]);
                 } else {
                     if (t < T) {
                         const uint32_t cnt = (uint32_t)iter * (uint32_t)T + (uint32_t)t;
@@ -446,12 +466,13 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
                     }
                 }
                 if (lane_ok) {
+                    char* st_t = st_g + (size_t)t * st_step;
 #pragma unroll
-                    for (int s = 0; s < S; ++s) store_f32<PP>(p.states, ((((size_t)t * S + s) * B + bb) * NH + n) * D + e0, st[s]);
+                    for (int s = 0; s < S; ++s) store_io_b<false, PP>(st_t + (size_t)s * st_state, voff_st, st[s]);
                     if (p.cache != nullptr) {
+                        char* c_t = c_g + (size_t)(t - 1) * c_step;
 #pragma unroll
-                        for (int c2 = 0; c2 < NC; ++c2)
-                            store_io<BF16, PP>(p.cache, ((((size_t)(t - 1) * B + bb) * NH + n) * NC + c2) * D + e0, cvs[c2]);
+                        for (int c2 = 0; c2 < NC; ++c2) store_io_b<BF16, PP>(c_t + c2 * c_slot, voff_c, cvs[c2]);
                     }
                 }
             }
@@ -481,6 +502,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
     constexpr int ESZ = BF16 ? 2 : 4;
     constexpr int DK = KT * KS * OP::KSTEP;
     constexpr int HP = DK + (BF16 ? 8 : 4);
+    constexpr int BUF = BT * HP * ESZ;
     constexpr int KC = poll_chunk<BF16>(KT);
     static_assert(!MULTI || BT == 16, "several workgroups per group exchange full 16-row tiles");
     static_assert(KS == 1 || MULTI, "contraction slices are only used with several workgroups per group");
@@ -505,6 +527,16 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
     const uint32_t xbuf = (uint32_t)p.GPAR * 16u * XROW;
     bool failed = false;
 
+    const uint32_t HD = (uint32_t)NH * D;
+    const size_t wx_step = (size_t)B * G * HD * ESZ;
+    const uint32_t wx_gate = HD * ESZ;
+    const size_t st_step = (size_t)S * B * HD * 4;
+    const uint32_t st_state = (uint32_t)B * HD * 4;
+    const size_t c_step = (size_t)B * HD * NC * ESZ;
+    const uint32_t c_slot = (uint32_t)D * ESZ;
+    const size_t dh_step = (size_t)B * HD * ESZ;
+    const uint32_t lds_row = (uint32_t)lm.bslot * HP * ESZ;
+
     int iter = 0;
     for (int gid = bm.gpar; gid < p.NG; gid += p.GPAR, ++iter) {
         const int n = gid % NH, q = gid / NH;
@@ -522,12 +554,22 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
         const bool row_valid = bb_raw < B;
         const int bb = row_valid ? bb_raw : B - 1;
         const bool lane_ok = row_valid && ks == 0;
+        const char* c_g = (const char*)p.cache + (size_t)n * NC * D * ESZ;
+        const char* st_g = (const char*)p.states + (size_t)n * D * 4;
+        const char* dh_g = (const char*)p.dH + (size_t)n * D * ESZ;
+        char* dwx_g = (char*)p.dWx + (size_t)n * D * ESZ;
+        char* dgn_g = (char*)p.dgn + (size_t)n * D * ESZ;
+        const uint32_t voff_wx = ((uint32_t)bb * G * HD + e0) * ESZ;
+        const uint32_t voff_st = ((uint32_t)bb * HD + e0) * 4;
+        const uint32_t voff_c = ((uint32_t)bb * HD * NC + e0) * ESZ;
+        const uint32_t voff_dh = ((uint32_t)bb * HD + e0) * ESZ;
 
         // carried state gradients; ds[0] is the part of dh_t that came through R and the direct path
         float ds[S][PP];
 #pragma unroll
         for (int s = 0; s < S; ++s) {
-            if (p.dlast != nullptr && !(CELL == CELL_SLSTM && s == 3)) load_f32<PP>(p.dlast, (((size_t)s * B + bb) * NH + n) * D + e0, ds[s]);
+            if (p.dlast != nullptr && !(CELL == CELL_SLSTM && s == 3))
+                load_io_b<false, PP>((const char*)p.dlast + (size_t)n * D * 4 + (size_t)s * st_state, voff_st, ds[s]);
             else
 #pragma unroll
                 for (int i = 0; i < PP; ++i) ds[s][i] = 0.0f;
@@ -540,7 +582,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
 
         if constexpr (!MULTI) {
             __syncthreads();
-            for (int j = threadIdx.x; j < 2 * BT * HP * ESZ / 4; j += blockDim.x) ((uint32_t*)gbuf)[j] = 0u;
+            for (int j = threadIdx.x; j < 2 * BUF / 4; j += blockDim.x) ((uint32_t*)gbuf)[j] = 0u;
             __syncthreads();
         }
 
@@ -548,21 +590,23 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
             if (ks == 0) {
                 // ---- loads of this step (independent of the recurrence)
                 float cv[NC][PP], sc[S][PP], sp[S][PP], dh_ext[PP];
+                const char* c_t = c_g + (size_t)(t - 1) * c_step;
+                const char* st_t = st_g + (size_t)t * st_step;
+                const char* st_p = st_g + (size_t)(t - 1) * st_step;
 #pragma unroll
-                for (int c2 = 0; c2 < NC; ++c2) load_io<BF16, PP>(p.cache, ((((size_t)(t - 1) * B + bb) * NH + n) * NC + c2) * D + e0, cv[c2]);
+                for (int c2 = 0; c2 < NC; ++c2) load_io_b<BF16, PP>(c_t + c2 * c_slot, voff_c, cv[c2]);
 #pragma unroll
                 for (int s = 0; s < S; ++s) {
-                    if (CELL != CELL_GRU && s > 0 && s < 3) load_f32<PP>(p.states, ((((size_t)t * S + s) * B + bb) * NH + n) * D + e0, sc[s]);
+                    if (CELL != CELL_GRU && s > 0 && s < 3) load_io_b<false, PP>(st_t + (size_t)s * st_state, voff_st, sc[s]);
                     else
 #pragma unroll
                         for (int i = 0; i < PP; ++i) sc[s][i] = 1.0f;
-                    if ((CELL == CELL_GRU) ? (s == 0) : (s > 0 && s < 3))
-                        load_f32<PP>(p.states, ((((size_t)(t - 1) * S + s) * B + bb) * NH + n) * D + e0, sp[s]);
+                    if ((CELL == CELL_GRU) ? (s == 0) : (s > 0 && s < 3)) load_io_b<false, PP>(st_p + (size_t)s * st_state, voff_st, sp[s]);
                     else
 #pragma unroll
                         for (int i = 0; i < PP; ++i) sp[s][i] = 1.0f;
                 }
-                load_io<BF16, PP>(p.dH, (((size_t)(t - 1) * B + bb) * NH + n) * D + e0, dh_ext);
+                load_io_b<BF16, PP>(dh_g + (size_t)(t - 1) * dh_step, voff_dh, dh_ext);
                 // ---- point-wise Jacobians
                 float dwx[G][PP], dg[G][PP];
 #pragma unroll
@@ -582,8 +626,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
                 // ---- hand dg_t to the other waves, then stream out dWx
                 if constexpr (!MULTI) {
 #pragma unroll
-                    for (int g = 0; g < G; ++g)
-                        write_operand_lds<BF16, PP>(gbuf + ((size_t)(t & 1) * BT + lm.bslot) * HP * ESZ, g * D + e0, dg[g]);
+                    for (int g = 0; g < G; ++g) write_operand_lds<BF16, PP>(gbuf + (t & 1) * BUF + lds_row, g * D + e0, dg[g]);
                 } else {
                     const uint32_t cnt = (uint32_t)iter * (uint32_t)T + (uint32_t)(T - t);
 #pragma unroll
@@ -591,9 +634,10 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
                         publish4<BF16>(xr, (cnt & 1u) * xbuf + xgroup + (uint32_t)lm.bslot * XROW, g * D + e0, dg[g], cnt + 1u);
                 }
                 if (lane_ok) {
+                    char* dwx_t = dwx_g + (size_t)(t - 1) * wx_step;
 #pragma unroll
-                    for (int g = 0; g < G; ++g) store_io<BF16, PP>(p.dWx, ((((size_t)(t - 1) * B + bb) * G + g) * NH + n) * D + e0, dwx[g]);
-                    if constexpr (CELL == CELL_GRU) store_io<BF16, PP>(p.dgn, (((size_t)(t - 1) * B + bb) * NH + n) * D + e0, dg[2]);
+                    for (int g = 0; g < G; ++g) store_io_b<BF16, PP>(dwx_t + g * wx_gate, voff_wx, dwx[g]);
+                    if constexpr (CELL == CELL_GRU) store_io_b<BF16, PP>(dgn_g + (size_t)(t - 1) * dh_step, voff_dh, dg[2]);
                 }
             }
             // ---- dh_{t-1} += R dg_t on the matrix cores; four accumulators break the dependent chain
@@ -603,7 +647,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
             if constexpr (!MULTI) {
                 __syncthreads();
                 op_t gB[KT];
-                read_operand_lds<BF16, KT>(gbuf + ((size_t)(t & 1) * BT + lm.bslot) * HP * ESZ, k0, lm.quad, gB);
+                read_operand_lds<BF16, KT>(gbuf + (t & 1) * BUF + lds_row, k0, lm.quad, gB);
 #pragma unroll
                 for (int kt = 0; kt < KT; ++kt) a4[kt & 3] = OP::mfma(Rf[kt], gB[kt], a4[kt & 3]);
             } else {
@@ -633,7 +677,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
         // ---- gradients w.r.t. the initial states, per-row partial sums of db
         if (lane_ok) {
 #pragma unroll
-            for (int s = 0; s < S; ++s) store_f32<PP>(p.dstates0, (((size_t)s * B + bb) * NH + n) * D + e0, ds[s]);
+            for (int s = 0; s < S; ++s) store_io_b<false, PP>((char*)p.dstates0 + (size_t)n * D * 4 + (size_t)s * st_state, voff_st, ds[s]);
 #pragma unroll
             for (int g = 0; g < G; ++g) store_f32<PP>(p.db_part, (((size_t)bb * NH + n) * G + g) * D + e0, dbacc[g]);
         }

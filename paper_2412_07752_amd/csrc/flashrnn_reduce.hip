@@ -84,10 +84,10 @@ __global__ __launch_bounds__(256) void dr_gemm_kernel(const float* __restrict__ 
         if constexpr (BF16) {
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-                *(uint32_t*)(ldsA + ((a_d + i) * PITCH + a_kp * 2) * 2) = f32_to_bf16_bits(av[0][i]) | (f32_to_bf16_bits(av[1][i]) << 16);
+                *(uint32_t*)(ldsA + ((a_d + i) * PITCH + a_kp * 2) * 2) = pack_bf16x2(av[0][i], av[1][i]);
 #pragma unroll
             for (int i = 0; i < 8; ++i)
-                *(uint32_t*)(ldsB + ((b_j + i) * PITCH + b_kp * 2) * 2) = f32_to_bf16_bits(bv[0][i]) | (f32_to_bf16_bits(bv[1][i]) << 16);
+                *(uint32_t*)(ldsB + ((b_j + i) * PITCH + b_kp * 2) * 2) = pack_bf16x2(bv[0][i], bv[1][i]);
         } else {
 #pragma unroll
             for (int i = 0; i < 4; ++i) *(float2*)(ldsA + ((a_d + i) * PITCH + a_kp * 2) * 4) = make_float2(av[0][i], av[1][i]);
