@@ -159,13 +159,48 @@ template <bool BF16, int PP> __device__ __forceinline__ void store_io(void* base
     }
 }
 
-// byte-addressed variants: uniform base (kept in scalar registers) + 32-bit per-lane byte offset, the
-// form the global load/store instructions take directly (no per-step 64-bit vector address math)
-template <bool BF16, int PP> __device__ __forceinline__ void load_io_b(const char* sbase, uint32_t voff, float (&out)[PP]) {
-    load_io<BF16, PP>(sbase + voff, 0, out);
+// Per-step streams go through buffer instructions: a resource built from a uniform pointer (advanced
+// per step on the scalar unit), a loop-invariant 32-bit lane offset and a scalar offset.  No vector
+// address arithmetic and no 64-bit pointer registers in the time loop.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void* p) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, 0x7FFFFFFF, 0x00020000);
 }
-template <bool BF16, int PP> __device__ __forceinline__ void store_io_b(char* sbase, uint32_t voff, const float (&v)[PP]) {
-    store_io<BF16, PP>(sbase + voff, 0, v);
+template <bool BF16, int PP> __device__ __forceinline__ void load_io_r(rsrc_t r, uint32_t voff, uint32_t soff, float (&out)[PP]) {
+    if constexpr (BF16) {
+        if constexpr (PP == 4) {
+            const i32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0);
+            out[0] = bf16_bits_to_f32((uint32_t)v[0] & 0xFFFFu); out[1] = __builtin_bit_cast(float, (uint32_t)v[0] & 0xFFFF0000u);
+            out[2] = bf16_bits_to_f32((uint32_t)v[1] & 0xFFFFu); out[3] = __builtin_bit_cast(float, (uint32_t)v[1] & 0xFFFF0000u);
+        } else if constexpr (PP == 2) {
+            const uint32_t v = __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0);
+            out[0] = bf16_bits_to_f32(v & 0xFFFFu); out[1] = __builtin_bit_cast(float, v & 0xFFFF0000u);
+        } else {
+            out[0] = bf16_bits_to_f32((uint32_t)__builtin_amdgcn_raw_buffer_load_b16(r, voff, soff, 0));
+        }
+    } else {
+        if constexpr (PP == 4) {
+            const f32x4 v = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0));
+            out[0] = v[0]; out[1] = v[1]; out[2] = v[2]; out[3] = v[3];
+        } else if constexpr (PP == 2) {
+            const i32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0);
+            const int a = v[0], b = v[1];
+            out[0] = __builtin_bit_cast(float, a); out[1] = __builtin_bit_cast(float, b);
+        } else {
+            out[0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0));
+        }
+    }
+}
+template <bool BF16, int PP> __device__ __forceinline__ void store_io_r(rsrc_t r, uint32_t voff, uint32_t soff, const float (&v)[PP]) {
+    if constexpr (BF16) {
+        if constexpr (PP == 4) __builtin_amdgcn_raw_buffer_store_b64(i32x2{(int)pack_bf16x2(v[0], v[1]), (int)pack_bf16x2(v[2], v[3])}, r, voff, soff, 0);
+        else if constexpr (PP == 2) __builtin_amdgcn_raw_buffer_store_b32(pack_bf16x2(v[0], v[1]), r, voff, soff, 0);
+        else __builtin_amdgcn_raw_buffer_store_b16((unsigned short)f32_to_bf16_bits(v[0]), r, voff, soff, 0);
+    } else {
+        if constexpr (PP == 4) __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(i32x4, f32x4{v[0], v[1], v[2], v[3]}), r, voff, soff, 0);
+        else if constexpr (PP == 2) __builtin_amdgcn_raw_buffer_store_b64(i32x2{__builtin_bit_cast(int, v[0]), __builtin_bit_cast(int, v[1])}, r, voff, soff, 0);
+        else __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, v[0]), r, voff, soff, 0);
+    }
 }
 
 template <int PP> __device__ __forceinline__ void load_f32(const float* base, size_t idx, float (&out)[PP]) {

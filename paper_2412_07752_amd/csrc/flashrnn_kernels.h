@@ -118,6 +118,20 @@ template <bool FAST> struct Cell<CELL_GRU, FAST> {
     }
 };
 
+// Forces prefetched values to be complete (and converted) at this point of the program.  Vector
+// memory operations retire in order, so a wait placed later would also wait for the stores issued
+// in between; placing it before them keeps the store latency off the per-step critical path.
+template <int N, int M> __device__ __forceinline__ void pin(float (&v)[N][M]) {
+#pragma unroll
+    for (int i = 0; i < N; ++i)
+#pragma unroll
+        for (int j = 0; j < M; ++j) asm volatile("" : "+v"(v[i][j]) : : "memory");
+}
+template <int N> __device__ __forceinline__ void pin(float (&v)[N]) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) asm volatile("" : "+v"(v[i]) : : "memory");
+}
+
 // ---------------------------------------------------------------------------------------------
 // common per-lane geometry
 // ---------------------------------------------------------------------------------------------
@@ -152,6 +166,18 @@ struct BlockMap {
         active = gpar < p.GPAR;
     }
 };
+
+// Waves that share a SIMD (wave w runs on SIMD w % 4) get different issue priorities.  After the
+// per-step barrier all of them want the matrix pipe; with equal priorities they take turns and all
+// finish their MFMA chains late and together, then fight for the VALU.  With distinct priorities the
+// first wave finishes its chain early and its point-wise phase overlaps the next wave's MFMA chain.
+__device__ __forceinline__ void stagger_waves(int w) {
+    const int slot = w >> 2;
+    if (slot == 0) __builtin_amdgcn_s_setprio(3);
+    else if (slot == 1) __builtin_amdgcn_s_setprio(2);
+    else if (slot == 2) __builtin_amdgcn_s_setprio(1);
+    else __builtin_amdgcn_s_setprio(0);
+}
 
 // ---------------------------------------------------------------------------------------------
 // operand hand-over between waves: LDS (one workgroup per group) or stamped words in global memory
@@ -315,6 +341,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
     if (!bm.active) return;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int wu = w % p.NWU, ks = w / p.NWU;
+    stagger_waves(w);
     const LaneMap<BT> lm(lane);
     const int T = p.T, B = p.B, NH = p.NH, D = p.D;
     const int e_wave = (bm.member * p.NWU + wu) * 16;  // first unit of this wave
@@ -368,19 +395,21 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
         const char* wx_g = (const char*)p.Wx + (size_t)n * D * ESZ;
         char* st_g = (char*)p.states + (size_t)n * D * 4;
         char* c_g = (char*)p.cache + (size_t)n * NC * D * ESZ;
+        constexpr uint32_t kDrop = 0x80000000u;  // beyond every resource's range: the access is dropped
         const uint32_t voff_wx = ((uint32_t)bb * G * HD + e0) * ESZ;
         const uint32_t voff_st = ((uint32_t)bb * HD + e0) * 4;
-        const uint32_t voff_c = ((uint32_t)bb * HD * NC + e0) * ESZ;
+        const uint32_t soff_st = lane_ok ? voff_st : kDrop;
+        const uint32_t soff_c = (lane_ok && p.cache != nullptr) ? ((uint32_t)bb * HD * NC + e0) * ESZ : kDrop;
 
         // ---- initial states
         float st[S][PP];
 #pragma unroll
         for (int s = 0; s < S; ++s) {
-            if (p.states0 != nullptr) load_io_b<false, PP>((const char*)p.states0 + (size_t)n * D * 4 + (size_t)s * st_state, voff_st, st[s]);
+            if (p.states0 != nullptr) load_io_r<false, PP>(make_rsrc((const char*)p.states0 + (size_t)n * D * 4), voff_st, s * st_state, st[s]);
             else
 #pragma unroll
                 for (int i = 0; i < PP; ++i) st[s][i] = 0.0f;
-            if (lane_ok) store_io_b<false, PP>(st_g + (size_t)s * st_state, voff_st, st[s]);
+            store_io_r<false, PP>(make_rsrc(st_g), soff_st, s * st_state, st[s]);
         }
         if constexpr (!MULTI) {
             __syncthreads();  // the previous group is done with the operand rows
@@ -395,19 +424,20 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
             }
         }
 
+        // input pre-activations are fetched one step ahead
         float wx[G][PP];
         if (T > 0) {
 #pragma unroll
-            for (int g = 0; g < G; ++g) load_io_b<BF16, PP>(wx_g + g * wx_gate, voff_wx, wx[g]);
+            for (int g = 0; g < G; ++g) load_io_r<BF16, PP>(make_rsrc(wx_g), voff_wx, g * wx_gate, wx[g]);
         }
 
         for (int t = 1; t <= T; ++t) {
-            // ---- prefetch next step's input pre-activations (clamped at the last step)
+            // ---- prefetch the inputs of step t + 1 (clamped at the end)
             float wxn[G][PP];
             {
-                const char* wx_t = wx_g + (size_t)(t < T ? t : T - 1) * wx_step;
+                const rsrc_t rsn = make_rsrc(wx_g + (size_t)(t < T ? t : T - 1) * wx_step);
 #pragma unroll
-                for (int g = 0; g < G; ++g) load_io_b<BF16, PP>(wx_t + g * wx_gate, voff_wx, wxn[g]);
+                for (int g = 0; g < G; ++g) load_io_r<BF16, PP>(rsn, voff_wx, g * wx_gate, wxn[g]);
             }
             // ---- recurrent product y = R^T h_{t-1} on the matrix cores
             f32x4 acc[G];
@@ -439,7 +469,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
             }
             reduce_slices<G, KS>(red, t & 1, ks, wu, p.NWU, lane, acc);
 
-            if (ks == 0) {
+            if (KS == 1 || ks == 0) {
 #pragma unroll
                 for (int g = 0; g < G; ++g) compact_tile<BT>(acc[g]);
                 float cvs[NC][PP];
@@ -465,15 +495,16 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
                         publish4<BF16>(xr, (cnt & 1u) * xbuf + xgroup + (uint32_t)lm.bslot * XROW, e0, st[0], cnt + 1u);
                     }
                 }
-                if (lane_ok) {
-                    char* st_t = st_g + (size_t)t * st_step;
+                // stores of lanes without a valid row (and of the saved values in a forward-only call) carry
+                // an out-of-range offset and are dropped by the buffer bounds check: no branch, so the
+                // wait for the prefetched inputs at the end of the step does not have to cover them
+                {
+                    const rsrc_t rs_st = make_rsrc(st_g + (size_t)t * st_step);
 #pragma unroll
-                    for (int s = 0; s < S; ++s) store_io_b<false, PP>(st_t + (size_t)s * st_state, voff_st, st[s]);
-                    if (p.cache != nullptr) {
-                        char* c_t = c_g + (size_t)(t - 1) * c_step;
+                    for (int s = 0; s < S; ++s) store_io_r<false, PP>(rs_st, soff_st, s * st_state, st[s]);
+                    const rsrc_t rs_c = make_rsrc(c_g + (size_t)(t - 1) * c_step);
 #pragma unroll
-                        for (int c2 = 0; c2 < NC; ++c2) store_io_b<BF16, PP>(c_t + c2 * c_slot, voff_c, cvs[c2]);
-                    }
+                    for (int c2 = 0; c2 < NC; ++c2) store_io_r<BF16, PP>(rs_c, soff_c, c2 * c_slot, cvs[c2]);
                 }
             }
 #pragma unroll
@@ -513,6 +544,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
     if (!bm.active) return;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int wu = w % p.NWU, ks = w / p.NWU;
+    stagger_waves(w);
     const LaneMap<BT> lm(lane);
     const int T = p.T, B = p.B, NH = p.NH, D = p.D;
     const int e_wave = (bm.member * p.NWU + wu) * 16;
@@ -559,17 +591,19 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
         const char* dh_g = (const char*)p.dH + (size_t)n * D * ESZ;
         char* dwx_g = (char*)p.dWx + (size_t)n * D * ESZ;
         char* dgn_g = (char*)p.dgn + (size_t)n * D * ESZ;
-        const uint32_t voff_wx = ((uint32_t)bb * G * HD + e0) * ESZ;
+        constexpr uint32_t kDrop = 0x80000000u;  // beyond every resource's range: the access is dropped
         const uint32_t voff_st = ((uint32_t)bb * HD + e0) * 4;
         const uint32_t voff_c = ((uint32_t)bb * HD * NC + e0) * ESZ;
         const uint32_t voff_dh = ((uint32_t)bb * HD + e0) * ESZ;
+        const uint32_t soff_wx = lane_ok ? ((uint32_t)bb * G * HD + e0) * ESZ : kDrop;
+        const uint32_t soff_dh = lane_ok ? voff_dh : kDrop;
 
         // carried state gradients; ds[0] is the part of dh_t that came through R and the direct path
         float ds[S][PP];
 #pragma unroll
         for (int s = 0; s < S; ++s) {
             if (p.dlast != nullptr && !(CELL == CELL_SLSTM && s == 3))
-                load_io_b<false, PP>((const char*)p.dlast + (size_t)n * D * 4 + (size_t)s * st_state, voff_st, ds[s]);
+                load_io_r<false, PP>(make_rsrc((const char*)p.dlast + (size_t)n * D * 4), voff_st, s * st_state, ds[s]);
             else
 #pragma unroll
                 for (int i = 0; i < PP; ++i) ds[s][i] = 0.0f;
@@ -586,27 +620,34 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
             __syncthreads();
         }
 
+        // inputs of a step: saved values, the states the cell's Jacobian needs, external dh
+        float cv[NC][PP], sc[S][PP], sp[S][PP], dh_ext[PP];
+        auto load_step = [&](int t, float (&cv_)[NC][PP], float (&sc_)[S][PP], float (&sp_)[S][PP], float (&dh_)[PP]) {
+            const rsrc_t c_t = make_rsrc(c_g + (size_t)(t - 1) * c_step);
+            const rsrc_t st_t = make_rsrc(st_g + (size_t)t * st_step);
+            const rsrc_t st_p = make_rsrc(st_g + (size_t)(t - 1) * st_step);
+#pragma unroll
+            for (int c2 = 0; c2 < NC; ++c2) load_io_r<BF16, PP>(c_t, voff_c, c2 * c_slot, cv_[c2]);
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+                if (CELL != CELL_GRU && s > 0 && s < 3) load_io_r<false, PP>(st_t, voff_st, s * st_state, sc_[s]);
+                else
+#pragma unroll
+                    for (int i = 0; i < PP; ++i) sc_[s][i] = 1.0f;
+                if ((CELL == CELL_GRU) ? (s == 0) : (s > 0 && s < 3)) load_io_r<false, PP>(st_p, voff_st, s * st_state, sp_[s]);
+                else
+#pragma unroll
+                    for (int i = 0; i < PP; ++i) sp_[s][i] = 1.0f;
+            }
+            load_io_r<BF16, PP>(make_rsrc(dh_g + (size_t)(t - 1) * dh_step), voff_dh, 0, dh_);
+        };
+        if ((KS == 1 || ks == 0) && T > 0) load_step(T, cv, sc, sp, dh_ext);
+
         for (int t = T; t >= 1; --t) {
-            if (ks == 0) {
-                // ---- loads of this step (independent of the recurrence)
-                float cv[NC][PP], sc[S][PP], sp[S][PP], dh_ext[PP];
-                const char* c_t = c_g + (size_t)(t - 1) * c_step;
-                const char* st_t = st_g + (size_t)t * st_step;
-                const char* st_p = st_g + (size_t)(t - 1) * st_step;
-#pragma unroll
-                for (int c2 = 0; c2 < NC; ++c2) load_io_b<BF16, PP>(c_t + c2 * c_slot, voff_c, cv[c2]);
-#pragma unroll
-                for (int s = 0; s < S; ++s) {
-                    if (CELL != CELL_GRU && s > 0 && s < 3) load_io_b<false, PP>(st_t + (size_t)s * st_state, voff_st, sc[s]);
-                    else
-#pragma unroll
-                        for (int i = 0; i < PP; ++i) sc[s][i] = 1.0f;
-                    if ((CELL == CELL_GRU) ? (s == 0) : (s > 0 && s < 3)) load_io_b<false, PP>(st_p + (size_t)s * st_state, voff_st, sp[s]);
-                    else
-#pragma unroll
-                        for (int i = 0; i < PP; ++i) sp[s][i] = 1.0f;
-                }
-                load_io_b<BF16, PP>(dh_g + (size_t)(t - 1) * dh_step, voff_dh, dh_ext);
+            float cvn[NC][PP], scn[S][PP], spn[S][PP], dhn[PP];
+            if (KS == 1 || ks == 0) {
+                // ---- prefetch the inputs of the next (earlier) step; they are pinned after the MFMA phase
+                load_step(t > 1 ? t - 1 : 1, cvn, scn, spn, dhn);
                 // ---- point-wise Jacobians
                 float dwx[G][PP], dg[G][PP];
 #pragma unroll
@@ -633,11 +674,11 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
                     for (int g = 0; g < G; ++g)
                         publish4<BF16>(xr, (cnt & 1u) * xbuf + xgroup + (uint32_t)lm.bslot * XROW, g * D + e0, dg[g], cnt + 1u);
                 }
-                if (lane_ok) {
-                    char* dwx_t = dwx_g + (size_t)(t - 1) * wx_step;
+                {
+                    const rsrc_t dwx_t = make_rsrc(dwx_g + (size_t)(t - 1) * wx_step);
 #pragma unroll
-                    for (int g = 0; g < G; ++g) store_io_b<BF16, PP>(dwx_t + g * wx_gate, voff_wx, dwx[g]);
-                    if constexpr (CELL == CELL_GRU) store_io_b<BF16, PP>(dgn_g + (size_t)(t - 1) * dh_step, voff_dh, dg[2]);
+                    for (int g = 0; g < G; ++g) store_io_r<BF16, PP>(dwx_t, soff_wx, g * wx_gate, dwx[g]);
+                    if constexpr (CELL == CELL_GRU) store_io_r<BF16, PP>(make_rsrc(dgn_g + (size_t)(t - 1) * dh_step), soff_dh, 0, dg[2]);
                 }
             }
             // ---- dh_{t-1} += R dg_t on the matrix cores; four accumulators break the dependent chain
@@ -668,16 +709,26 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
             f32x4 acc[1];
             acc[0] = (a4[0] + a4[1]) + (a4[2] + a4[3]);
             reduce_slices<1, KS>(red, t & 1, ks, wu, p.NWU, lane, acc);
-            if (ks == 0) {
+            if (KS == 1 || ks == 0) {
                 compact_tile<BT>(acc[0]);
 #pragma unroll
                 for (int i = 0; i < PP; ++i) ds[0][i] += acc[0][i];
+                // wait for the prefetched inputs here, where only this step's stores are younger
+                pin(cvn); pin(scn); pin(spn); pin(dhn);
+#pragma unroll
+                for (int i = 0; i < PP; ++i) {
+#pragma unroll
+                    for (int c2 = 0; c2 < NC; ++c2) cv[c2][i] = cvn[c2][i];
+#pragma unroll
+                    for (int s = 0; s < S; ++s) { sc[s][i] = scn[s][i]; sp[s][i] = spn[s][i]; }
+                    dh_ext[i] = dhn[i];
+                }
             }
         }
         // ---- gradients w.r.t. the initial states, per-row partial sums of db
         if (lane_ok) {
 #pragma unroll
-            for (int s = 0; s < S; ++s) store_io_b<false, PP>((char*)p.dstates0 + (size_t)n * D * 4 + (size_t)s * st_state, voff_st, ds[s]);
+            for (int s = 0; s < S; ++s) store_io_r<false, PP>(make_rsrc((char*)p.dstates0 + (size_t)n * D * 4), voff_st, s * st_state, ds[s]);
 #pragma unroll
             for (int g = 0; g < G; ++g) store_f32<PP>(p.db_part, (((size_t)bb * NH + n) * G + g) * D + e0, dbacc[g]);
         }
