@@ -77,7 +77,8 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
     const int force_bt = env_int("FLASHRNN_BT", 0);
     const int force_nwu = env_int("FLASHRNN_NWU", 0);
     const int force_ks = env_int("FLASHRNN_KS", 0);
-    const int force_gpar = env_int("FLASHRNN_GPAR", 0);      // groups in flight when groups are split (testing the group loop)
+    const int force_gpar = env_int("FLASHRNN_GPAR", 0);
+    const int force_eb = env_int("FLASHRNN_EB", 0);          // blocks of 16 units per wave (one workgroup per group)      // groups in flight when groups are split (testing the group loop)
     Plan pl;
 
     if (force_multi != 1) {
@@ -95,12 +96,14 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
             for (int i = 0; i < tab.count; ++i) {
                 const KernelEntry& e = tab.entries[i];
                 if (e.bwd != bwd || e.multi || e.KS != 1 || e.BT != bt_pref[b]) continue;
-                if (e.KT * kstep < kdim || e.maxw < units16) continue;
-                if (!best || e.KT < best->KT) best = &e;
+                if (e.KT * kstep < kdim || units16 % e.eb != 0 || e.maxw * e.eb < units16) continue;
+                if (force_eb ? e.eb != force_eb : false) continue;
+                // smallest contraction padding first, then the thinnest waves (measured faster: more overlap between waves)
+                if (!best || e.KT < best->KT || (e.KT == best->KT && e.eb < best->eb)) best = &e;
             }
             if (best) {
                 pl.e = best;
-                pl.NWU = units16;
+                pl.NWU = units16 / best->eb;
                 pl.P = 1;
                 pl.NG = d->NH * ((d->B + best->BT - 1) / best->BT);
                 pl.GPAR = pl.NG;

@@ -15,6 +15,7 @@ struct KernelEntry {
     int BT;     // valid batch slots per tile (16, 8, 4)
     int multi;  // several workgroups per group
     int maxw;   // launch bound in waves
+    int eb;     // blocks of 16 units per wave
     const void* fn;
 };
 

@@ -10,12 +10,14 @@
 
 namespace flashrnn {
 
-#define FRNN_F(KT, KS, BT, MULTI, MAXW) \
-    {FRNN_CELL, FRNN_BF16, 0, KT, KS, BT, MULTI, MAXW, (const void*)&fwd_kernel<FRNN_CELL, (FRNN_BF16 != 0), KT, KS, BT, (MULTI != 0), MAXW>},
-#define FRNN_B(KT, KS, BT, MULTI, MAXW) \
-    {FRNN_CELL, FRNN_BF16, 1, (KT) * FRNN_G, KS, BT, MULTI, MAXW, (const void*)&bwd_kernel<FRNN_CELL, (FRNN_BF16 != 0), (KT) * FRNN_G, KS, BT, (MULTI != 0), MAXW>},
+#define FRNN_F(KT, KS, BT, MULTI, MAXW, EB) \
+    {FRNN_CELL, FRNN_BF16, 0, KT, KS, BT, MULTI, MAXW, EB, (const void*)&fwd_kernel<FRNN_CELL, (FRNN_BF16 != 0), KT, KS, BT, (MULTI != 0), MAXW, EB>},
+#define FRNN_B(KT, KS, BT, MULTI, MAXW, EB) \
+    {FRNN_CELL, FRNN_BF16, 1, (KT) * FRNN_G, KS, BT, MULTI, MAXW, EB, (const void*)&bwd_kernel<FRNN_CELL, (FRNN_BF16 != 0), (KT) * FRNN_G, KS, BT, (MULTI != 0), MAXW, EB>},
 // forward and backward share the shape list: the backward contraction axis is G times longer
-#define FRNN_FB(KT, KS, BT, MULTI, MAXW) FRNN_F(KT, KS, BT, MULTI, MAXW) FRNN_B(KT, KS, BT, MULTI, MAXW)
+#define FRNN_FB(KT, KS, BT, MULTI, MAXW) FRNN_F(KT, KS, BT, MULTI, MAXW, 1) FRNN_B(KT, KS, BT, MULTI, MAXW, 1)
+// EB blocks of 16 units per wave (fewer, fatter waves: the operand is read from LDS once per wave)
+#define FRNN_FBE(KT, BT, MAXW, EB) FRNN_F(KT, 1, BT, 0, MAXW, EB) FRNN_B(KT, 1, BT, 0, MAXW, EB)
 
 static const KernelEntry kEntries[] = {
 #if FRNN_BF16
@@ -23,6 +25,8 @@ static const KernelEntry kEntries[] = {
     FRNN_FB(2, 1, 16, 0, 4) FRNN_FB(2, 1, 8, 0, 4) FRNN_FB(2, 1, 4, 0, 4)
     FRNN_FB(4, 1, 16, 0, 8) FRNN_FB(4, 1, 8, 0, 8) FRNN_FB(4, 1, 4, 0, 8)
     FRNN_FB(6, 1, 16, 0, 12) FRNN_FB(6, 1, 8, 0, 12) FRNN_FB(6, 1, 4, 0, 12)
+    FRNN_FBE(4, 16, 4, 2) FRNN_FBE(4, 8, 4, 2) FRNN_FBE(4, 4, 4, 2)
+    FRNN_FBE(6, 16, 4, 3) FRNN_FBE(6, 8, 4, 3) FRNN_FBE(6, 4, 4, 3)
     FRNN_FB(2, 1, 16, 1, 4) FRNN_FB(4, 1, 16, 1, 4) FRNN_FB(6, 1, 16, 1, 4) FRNN_FB(1, 4, 16, 1, 4)
     FRNN_FB(8, 1, 16, 1, 8) FRNN_FB(12, 1, 16, 1, 8) FRNN_FB(16, 1, 16, 1, 4) FRNN_FB(24, 1, 16, 1, 4)
     FRNN_FB(6, 4, 16, 1, 8) FRNN_FB(8, 4, 16, 1, 8)
@@ -36,5 +40,6 @@ static const KernelEntry kEntries[] = {
 #undef FRNN_F
 #undef FRNN_B
 #undef FRNN_FB
+#undef FRNN_FBE
 
 }  // namespace flashrnn

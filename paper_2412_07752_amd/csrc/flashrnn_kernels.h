@@ -320,7 +320,8 @@ template <bool BF16> constexpr int poll_chunk(int KT) {
     return KT % 6 == 0 ? 6 : KT % 4 == 0 ? 4 : KT % 3 == 0 ? 3 : KT % 2 == 0 ? 2 : 1;
 }
 
-template <int CELL, bool BF16, int KT, int KS, int BT, bool MULTI, int MAXW>
+// EB = blocks of 16 units per wave: the wave reads the operand h once and uses it for all of them.
+template <int CELL, bool BF16, int KT, int KS, int BT, bool MULTI, int MAXW, int EB = 1>
 __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
     using CT = CellTraits<CELL>;
     using OP = Operand<BF16>;
@@ -335,6 +336,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
     static_assert(!MULTI || BT == 16, "several workgroups per group exchange full 16-row tiles");
     static_assert(KS == 1 || MULTI, "contraction slices are only used with several workgroups per group");
     static_assert(!MULTI || KT % KC == 0, "poll chunks must tile the k-steps");
+    static_assert(EB == 1 || !MULTI, "several unit blocks per wave only with one workgroup per group");
 
     extern __shared__ __align__(16) char smem[];
     const BlockMap bm(p, MULTI);
@@ -344,7 +346,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
     stagger_waves(w);
     const LaneMap<BT> lm(lane);
     const int T = p.T, B = p.B, NH = p.NH, D = p.D;
-    const int e_wave = (bm.member * p.NWU + wu) * 16;  // first unit of this wave
+    const int e_wave = (bm.member * p.NWU + wu) * 16 * EB;  // first unit of this wave
     const int e0 = e_wave + lm.uoff;                    // first unit of this lane's pairs
     const int k0 = ks * KT * OP::KSTEP;
 
@@ -373,19 +375,20 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
         const int n = gid % NH, q = gid / NH;
         // ---- load once per group: R fragments (A operand: row = unit e_wave + c) and bias; they stay
         // in registers for all T steps
-        op_t Rf[G][KT];
+        op_t Rf[EB][G][KT];
+        float bias[EB][G][PP];
+#pragma unroll
+        for (int eb = 0; eb < EB; ++eb)
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            const size_t rrow = (((size_t)n * G + g) * D + e_wave + lm.c) * DK;
+            const size_t rrow = (((size_t)n * G + g) * D + e_wave + 16 * eb + lm.c) * DK;
 #pragma unroll
             for (int kt = 0; kt < KT; ++kt) {
-                if constexpr (BF16) Rf[g][kt] = *(const bf16x8*)((const uint16_t*)p.R + rrow + k_index<BF16, KT>(k0, kt, lm.quad, 0));
-                else Rf[g][kt] = ((const float*)p.R)[rrow + k_index<BF16, KT>(k0, kt, lm.quad, 0)];
+                if constexpr (BF16) Rf[eb][g][kt] = *(const bf16x8*)((const uint16_t*)p.R + rrow + k_index<BF16, KT>(k0, kt, lm.quad, 0));
+                else Rf[eb][g][kt] = ((const float*)p.R)[rrow + k_index<BF16, KT>(k0, kt, lm.quad, 0)];
             }
+            load_io<BF16, PP>(p.bias, ((size_t)n * G + g) * D + e0 + 16 * eb, bias[eb][g]);
         }
-        float bias[G][PP];
-#pragma unroll
-        for (int g = 0; g < G; ++g) load_io<BF16, PP>(p.bias, ((size_t)n * G + g) * D + e0, bias[g]);
 
         const int bb_raw = q * BT + lm.bslot;
         const bool row_valid = bb_raw < B;
@@ -402,54 +405,66 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
         const uint32_t soff_c = (lane_ok && p.cache != nullptr) ? ((uint32_t)bb * HD * NC + e0) * ESZ : kDrop;
 
         // ---- initial states
-        float st[S][PP];
+        float st[EB][S][PP];
+#pragma unroll
+        for (int eb = 0; eb < EB; ++eb)
 #pragma unroll
         for (int s = 0; s < S; ++s) {
-            if (p.states0 != nullptr) load_io_r<false, PP>(make_rsrc((const char*)p.states0 + (size_t)n * D * 4), voff_st, s * st_state, st[s]);
+            if (p.states0 != nullptr) load_io_r<false, PP>(make_rsrc((const char*)p.states0 + (size_t)n * D * 4), voff_st + eb * 64, s * st_state, st[eb][s]);
             else
 #pragma unroll
-                for (int i = 0; i < PP; ++i) st[s][i] = 0.0f;
-            store_io_r<false, PP>(make_rsrc(st_g), soff_st, s * st_state, st[s]);
+                for (int i = 0; i < PP; ++i) st[eb][s][i] = 0.0f;
+            store_io_r<false, PP>(make_rsrc(st_g), soff_st + eb * 64, s * st_state, st[eb][s]);
         }
         if constexpr (!MULTI) {
             __syncthreads();  // the previous group is done with the operand rows
             for (int j = threadIdx.x; j < 2 * BUF / 4; j += blockDim.x) ((uint32_t*)hbuf)[j] = 0u;
             __syncthreads();
-            write_operand_lds<BF16, PP>(hbuf + lds_wr, e0, st[0]);
+#pragma unroll
+            for (int eb = 0; eb < EB; ++eb) write_operand_lds<BF16, PP>(hbuf + lds_wr, e0 + 16 * eb, st[eb][0]);
             __syncthreads();
         } else {
             if (ks == 0 && T > 0) {
                 const uint32_t cnt = (uint32_t)iter * (uint32_t)T;
-                publish4<BF16>(xr, (cnt & 1u) * xbuf + xgroup + (uint32_t)lm.bslot * XROW, e0, st[0], cnt + 1u);
+                publish4<BF16>(xr, (cnt & 1u) * xbuf + xgroup + (uint32_t)lm.bslot * XROW, e0, st[0][0], cnt + 1u);
             }
         }
 
         // input pre-activations are fetched one step ahead
-        float wx[G][PP];
+        float wx[EB][G][PP];
         if (T > 0) {
 #pragma unroll
-            for (int g = 0; g < G; ++g) load_io_r<BF16, PP>(make_rsrc(wx_g), voff_wx, g * wx_gate, wx[g]);
+            for (int eb = 0; eb < EB; ++eb)
+#pragma unroll
+            for (int g = 0; g < G; ++g) load_io_r<BF16, PP>(make_rsrc(wx_g), voff_wx + eb * 16 * ESZ, g * wx_gate, wx[eb][g]);
         }
 
         for (int t = 1; t <= T; ++t) {
             // ---- prefetch the inputs of step t + 1 (clamped at the end)
-            float wxn[G][PP];
+            float wxn[EB][G][PP];
             {
                 const rsrc_t rsn = make_rsrc(wx_g + (size_t)(t < T ? t : T - 1) * wx_step);
 #pragma unroll
-                for (int g = 0; g < G; ++g) load_io_r<BF16, PP>(rsn, voff_wx, g * wx_gate, wxn[g]);
+                for (int eb = 0; eb < EB; ++eb)
+#pragma unroll
+                for (int g = 0; g < G; ++g) load_io_r<BF16, PP>(rsn, voff_wx + eb * 16 * ESZ, g * wx_gate, wxn[eb][g]);
             }
             // ---- recurrent product y = R^T h_{t-1} on the matrix cores
-            f32x4 acc[G];
+            f32x4 accs[EB][G];
 #pragma unroll
-            for (int g = 0; g < G; ++g) acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int eb = 0; eb < EB; ++eb)
+#pragma unroll
+            for (int g = 0; g < G; ++g) accs[eb][g] = f32x4{0.f, 0.f, 0.f, 0.f};
+            f32x4 (&acc)[G] = accs[0];
             if constexpr (!MULTI) {
                 op_t hB[KT];
                 read_operand_lds<BF16, KT>(hbuf + ((t - 1) & 1) * BUF + lds_rd, k0, lm.quad, hB);
 #pragma unroll
+                for (int eb = 0; eb < EB; ++eb)
+#pragma unroll
                 for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
-                    for (int g = 0; g < G; ++g) acc[g] = OP::mfma(Rf[g][kt], hB[kt], acc[g]);
+                    for (int g = 0; g < G; ++g) accs[eb][g] = OP::mfma(Rf[eb][g][kt], hB[kt], accs[eb][g]);
             } else {
                 const uint32_t cnt = (uint32_t)iter * (uint32_t)T + (uint32_t)(t - 1);
                 const uint32_t row_off = (cnt & 1u) * xbuf + xgroup + (uint32_t)lm.c * XROW;
@@ -464,35 +479,38 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
 #pragma unroll
                     for (int j = 0; j < KC; ++j)
 #pragma unroll
-                        for (int g = 0; g < G; ++g) acc[g] = OP::mfma(Rf[g][kc + j], hB[j], acc[g]);
+                        for (int g = 0; g < G; ++g) acc[g] = OP::mfma(Rf[0][g][kc + j], hB[j], acc[g]);
                 }
             }
             reduce_slices<G, KS>(red, t & 1, ks, wu, p.NWU, lane, acc);
 
             if (KS == 1 || ks == 0) {
+                float cvs[EB][NC][PP];
 #pragma unroll
-                for (int g = 0; g < G; ++g) compact_tile<BT>(acc[g]);
-                float cvs[NC][PP];
+                for (int eb = 0; eb < EB; ++eb) {
 #pragma unroll
-                for (int i = 0; i < PP; ++i) {
-                    float wxi[G], ybi[G], sti[S], cvi[NC];
+                    for (int g = 0; g < G; ++g) compact_tile<BT>(accs[eb][g]);
 #pragma unroll
-                    for (int g = 0; g < G; ++g) { wxi[g] = wx[g][i]; ybi[g] = acc[g][i] + bias[g][i]; }
+                    for (int i = 0; i < PP; ++i) {
+                        float wxi[G], ybi[G], sti[S], cvi[NC];
 #pragma unroll
-                    for (int s = 0; s < S; ++s) sti[s] = st[s][i];
-                    Cell<CELL, BF16>::fwd(wxi, ybi, sti, cvi);
+                        for (int g = 0; g < G; ++g) { wxi[g] = wx[eb][g][i]; ybi[g] = accs[eb][g][i] + bias[eb][g][i]; }
 #pragma unroll
-                    for (int s = 0; s < S; ++s) st[s][i] = sti[s];
+                        for (int s = 0; s < S; ++s) sti[s] = st[eb][s][i];
+                        Cell<CELL, BF16>::fwd(wxi, ybi, sti, cvi);
 #pragma unroll
-                    for (int c2 = 0; c2 < NC; ++c2) cvs[c2][i] = cvi[c2];
-                }
-                // ---- hand the new h to the other waves first, then stream out states and saved values
-                if constexpr (!MULTI) {
-                    write_operand_lds<BF16, PP>(hbuf + (t & 1) * BUF + lds_wr, e0, st[0]);
-                } else {
-                    if (t < T) {
-                        const uint32_t cnt = (uint32_t)iter * (uint32_t)T + (uint32_t)t;
-                        publish4<BF16>(xr, (cnt & 1u) * xbuf + xgroup + (uint32_t)lm.bslot * XROW, e0, st[0], cnt + 1u);
+                        for (int s = 0; s < S; ++s) st[eb][s][i] = sti[s];
+#pragma unroll
+                        for (int c2 = 0; c2 < NC; ++c2) cvs[eb][c2][i] = cvi[c2];
+                    }
+                    // ---- hand the new h to the other waves as soon as it exists
+                    if constexpr (!MULTI) {
+                        write_operand_lds<BF16, PP>(hbuf + (t & 1) * BUF + lds_wr, e0 + 16 * eb, st[eb][0]);
+                    } else {
+                        if (t < T) {
+                            const uint32_t cnt = (uint32_t)iter * (uint32_t)T + (uint32_t)t;
+                            publish4<BF16>(xr, (cnt & 1u) * xbuf + xgroup + (uint32_t)lm.bslot * XROW, e0, st[0][0], cnt + 1u);
+                        }
                     }
                 }
                 // stores of lanes without a valid row (and of the saved values in a forward-only call) carry
@@ -500,17 +518,22 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
                 // wait for the prefetched inputs at the end of the step does not have to cover them
                 {
                     const rsrc_t rs_st = make_rsrc(st_g + (size_t)t * st_step);
-#pragma unroll
-                    for (int s = 0; s < S; ++s) store_io_r<false, PP>(rs_st, soff_st, s * st_state, st[s]);
                     const rsrc_t rs_c = make_rsrc(c_g + (size_t)(t - 1) * c_step);
 #pragma unroll
-                    for (int c2 = 0; c2 < NC; ++c2) store_io_r<BF16, PP>(rs_c, soff_c, c2 * c_slot, cvs[c2]);
+                    for (int eb = 0; eb < EB; ++eb) {
+#pragma unroll
+                        for (int s = 0; s < S; ++s) store_io_r<false, PP>(rs_st, soff_st + eb * 64, s * st_state, st[eb][s]);
+#pragma unroll
+                        for (int c2 = 0; c2 < NC; ++c2) store_io_r<BF16, PP>(rs_c, soff_c + eb * 16 * ESZ, c2 * c_slot, cvs[eb][c2]);
+                    }
                 }
             }
 #pragma unroll
+            for (int eb = 0; eb < EB; ++eb)
+#pragma unroll
             for (int g = 0; g < G; ++g)
 #pragma unroll
-                for (int i = 0; i < PP; ++i) wx[g][i] = wxn[g][i];
+                for (int i = 0; i < PP; ++i) wx[eb][g][i] = wxn[eb][g][i];
             if constexpr (!MULTI) __syncthreads();
         }
     }
@@ -523,7 +546,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
 // axis k = gate * D + unit (length G*D, padded to DK = KT*KS*KSTEP).  KT counts k-steps per wave.
 // p.R is the packed backward copy of R: Rb[n][d][k], k < DK, zero beyond G*D.
 // The launch guarantees P * NWU * 16 == D, and with MULTI also DK == G*D.
-template <int CELL, bool BF16, int KT, int KS, int BT, bool MULTI, int MAXW>
+template <int CELL, bool BF16, int KT, int KS, int BT, bool MULTI, int MAXW, int EB = 1>
 __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
     using CT = CellTraits<CELL>;
     using OP = Operand<BF16>;
@@ -538,6 +561,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
     static_assert(!MULTI || BT == 16, "several workgroups per group exchange full 16-row tiles");
     static_assert(KS == 1 || MULTI, "contraction slices are only used with several workgroups per group");
     static_assert(!MULTI || KT % KC == 0, "poll chunks must tile the k-steps");
+    static_assert(EB == 1 || !MULTI, "several unit blocks per wave only with one workgroup per group");
 
     extern __shared__ __align__(16) char smem[];
     const BlockMap bm(p, MULTI);
@@ -547,7 +571,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
     stagger_waves(w);
     const LaneMap<BT> lm(lane);
     const int T = p.T, B = p.B, NH = p.NH, D = p.D;
-    const int e_wave = (bm.member * p.NWU + wu) * 16;
+    const int e_wave = (bm.member * p.NWU + wu) * 16 * EB;
     const int e0 = e_wave + lm.uoff;
     const int k0 = ks * KT * OP::KSTEP;
 
@@ -573,13 +597,14 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
     for (int gid = bm.gpar; gid < p.NG; gid += p.GPAR, ++iter) {
         const int n = gid % NH, q = gid / NH;
         // ---- load once per group: R fragments, A operand row = previous-state index d = e_wave + c
-        op_t Rf[KT];
-        {
-            const size_t rrow = ((size_t)n * D + e_wave + lm.c) * DK;
+        op_t Rf[EB][KT];
+#pragma unroll
+        for (int eb = 0; eb < EB; ++eb) {
+            const size_t rrow = ((size_t)n * D + e_wave + 16 * eb + lm.c) * DK;
 #pragma unroll
             for (int kt = 0; kt < KT; ++kt) {
-                if constexpr (BF16) Rf[kt] = *(const bf16x8*)((const uint16_t*)p.R + rrow + k_index<BF16, KT>(k0, kt, lm.quad, 0));
-                else Rf[kt] = ((const float*)p.R)[rrow + k_index<BF16, KT>(k0, kt, lm.quad, 0)];
+                if constexpr (BF16) Rf[eb][kt] = *(const bf16x8*)((const uint16_t*)p.R + rrow + k_index<BF16, KT>(k0, kt, lm.quad, 0));
+                else Rf[eb][kt] = ((const float*)p.R)[rrow + k_index<BF16, KT>(k0, kt, lm.quad, 0)];
             }
         }
         const int bb_raw = q * BT + lm.bslot;
@@ -599,20 +624,23 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
         const uint32_t soff_dh = lane_ok ? voff_dh : kDrop;
 
         // carried state gradients; ds[0] is the part of dh_t that came through R and the direct path
-        float ds[S][PP];
+        float ds[EB][S][PP];
+        float dbacc[EB][G][PP];
+#pragma unroll
+        for (int eb = 0; eb < EB; ++eb) {
 #pragma unroll
         for (int s = 0; s < S; ++s) {
             if (p.dlast != nullptr && !(CELL == CELL_SLSTM && s == 3))
-                load_io_r<false, PP>(make_rsrc((const char*)p.dlast + (size_t)n * D * 4), voff_st, s * st_state, ds[s]);
+                load_io_r<false, PP>(make_rsrc((const char*)p.dlast + (size_t)n * D * 4), voff_st + eb * 64, s * st_state, ds[eb][s]);
             else
 #pragma unroll
-                for (int i = 0; i < PP; ++i) ds[s][i] = 0.0f;
+                for (int i = 0; i < PP; ++i) ds[eb][s][i] = 0.0f;
         }
-        float dbacc[G][PP];
 #pragma unroll
         for (int g = 0; g < G; ++g)
 #pragma unroll
-            for (int i = 0; i < PP; ++i) dbacc[g][i] = 0.0f;
+            for (int i = 0; i < PP; ++i) dbacc[eb][g][i] = 0.0f;
+        }
 
         if constexpr (!MULTI) {
             __syncthreads();
@@ -621,76 +649,88 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
         }
 
         // inputs of a step: saved values, the states the cell's Jacobian needs, external dh
-        float cv[NC][PP], sc[S][PP], sp[S][PP], dh_ext[PP];
-        auto load_step = [&](int t, float (&cv_)[NC][PP], float (&sc_)[S][PP], float (&sp_)[S][PP], float (&dh_)[PP]) {
+        float cv[EB][NC][PP], sc[EB][S][PP], sp[EB][S][PP], dh_ext[EB][PP];
+        auto load_step = [&](int t, float (&cv_)[EB][NC][PP], float (&sc_)[EB][S][PP], float (&sp_)[EB][S][PP], float (&dh_)[EB][PP]) {
             const rsrc_t c_t = make_rsrc(c_g + (size_t)(t - 1) * c_step);
             const rsrc_t st_t = make_rsrc(st_g + (size_t)t * st_step);
             const rsrc_t st_p = make_rsrc(st_g + (size_t)(t - 1) * st_step);
+            const rsrc_t dh_t = make_rsrc(dh_g + (size_t)(t - 1) * dh_step);
 #pragma unroll
-            for (int c2 = 0; c2 < NC; ++c2) load_io_r<BF16, PP>(c_t, voff_c, c2 * c_slot, cv_[c2]);
+            for (int eb = 0; eb < EB; ++eb) {
+#pragma unroll
+            for (int c2 = 0; c2 < NC; ++c2) load_io_r<BF16, PP>(c_t, voff_c + eb * 16 * ESZ, c2 * c_slot, cv_[eb][c2]);
 #pragma unroll
             for (int s = 0; s < S; ++s) {
-                if (CELL != CELL_GRU && s > 0 && s < 3) load_io_r<false, PP>(st_t, voff_st, s * st_state, sc_[s]);
+                if (CELL != CELL_GRU && s > 0 && s < 3) load_io_r<false, PP>(st_t, voff_st + eb * 64, s * st_state, sc_[eb][s]);
                 else
 #pragma unroll
-                    for (int i = 0; i < PP; ++i) sc_[s][i] = 1.0f;
-                if ((CELL == CELL_GRU) ? (s == 0) : (s > 0 && s < 3)) load_io_r<false, PP>(st_p, voff_st, s * st_state, sp_[s]);
+                    for (int i = 0; i < PP; ++i) sc_[eb][s][i] = 1.0f;
+                if ((CELL == CELL_GRU) ? (s == 0) : (s > 0 && s < 3)) load_io_r<false, PP>(st_p, voff_st + eb * 64, s * st_state, sp_[eb][s]);
                 else
 #pragma unroll
-                    for (int i = 0; i < PP; ++i) sp_[s][i] = 1.0f;
+                    for (int i = 0; i < PP; ++i) sp_[eb][s][i] = 1.0f;
             }
-            load_io_r<BF16, PP>(make_rsrc(dh_g + (size_t)(t - 1) * dh_step), voff_dh, 0, dh_);
+            load_io_r<BF16, PP>(dh_t, voff_dh + eb * 16 * ESZ, 0, dh_[eb]);
+            }
         };
         if ((KS == 1 || ks == 0) && T > 0) load_step(T, cv, sc, sp, dh_ext);
 
         for (int t = T; t >= 1; --t) {
-            float cvn[NC][PP], scn[S][PP], spn[S][PP], dhn[PP];
+            float cvn[EB][NC][PP], scn[EB][S][PP], spn[EB][S][PP], dhn[EB][PP];
             if (KS == 1 || ks == 0) {
                 // ---- prefetch the inputs of the next (earlier) step; they are pinned after the MFMA phase
                 load_step(t > 1 ? t - 1 : 1, cvn, scn, spn, dhn);
                 // ---- point-wise Jacobians
-                float dwx[G][PP], dg[G][PP];
+                const rsrc_t dwx_t = make_rsrc(dwx_g + (size_t)(t - 1) * wx_step);
 #pragma unroll
-                for (int i = 0; i < PP; ++i) {
-                    float cvi[NC], sci[S], spi[S], dsi[S], dwxi[G], dgi[G];
+                for (int eb = 0; eb < EB; ++eb) {
+                    float dwx[G][PP], dg[G][PP];
 #pragma unroll
-                    for (int c2 = 0; c2 < NC; ++c2) cvi[c2] = cv[c2][i];
+                    for (int i = 0; i < PP; ++i) {
+                        float cvi[NC], sci[S], spi[S], dsi[S], dwxi[G], dgi[G];
 #pragma unroll
-                    for (int s = 0; s < S; ++s) { sci[s] = sc[s][i]; spi[s] = sp[s][i]; dsi[s] = ds[s][i]; }
-                    dsi[0] += dh_ext[i];
-                    Cell<CELL, BF16>::bwd(cvi, sci, spi, dsi, dwxi, dgi);
+                        for (int c2 = 0; c2 < NC; ++c2) cvi[c2] = cv[eb][c2][i];
 #pragma unroll
-                    for (int s = 0; s < S; ++s) ds[s][i] = dsi[s];
+                        for (int s = 0; s < S; ++s) { sci[s] = sc[eb][s][i]; spi[s] = sp[eb][s][i]; dsi[s] = ds[eb][s][i]; }
+                        dsi[0] += dh_ext[eb][i];
+                        Cell<CELL, BF16>::bwd(cvi, sci, spi, dsi, dwxi, dgi);
 #pragma unroll
-                    for (int g = 0; g < G; ++g) { dwx[g][i] = dwxi[g]; dg[g][i] = dgi[g]; dbacc[g][i] += dgi[g]; }
-                }
-                // ---- hand dg_t to the other waves, then stream out dWx
-                if constexpr (!MULTI) {
+                        for (int s = 0; s < S; ++s) ds[eb][s][i] = dsi[s];
 #pragma unroll
-                    for (int g = 0; g < G; ++g) write_operand_lds<BF16, PP>(gbuf + (t & 1) * BUF + lds_row, g * D + e0, dg[g]);
-                } else {
-                    const uint32_t cnt = (uint32_t)iter * (uint32_t)T + (uint32_t)(T - t);
+                        for (int g2 = 0; g2 < G; ++g2) { dwx[g2][i] = dwxi[g2]; dg[g2][i] = dgi[g2]; dbacc[eb][g2][i] += dgi[g2]; }
+                    }
+                    // ---- hand dg_t to the other waves, then stream out dWx
+                    if constexpr (!MULTI) {
 #pragma unroll
-                    for (int g = 0; g < G; ++g)
-                        publish4<BF16>(xr, (cnt & 1u) * xbuf + xgroup + (uint32_t)lm.bslot * XROW, g * D + e0, dg[g], cnt + 1u);
-                }
-                {
-                    const rsrc_t dwx_t = make_rsrc(dwx_g + (size_t)(t - 1) * wx_step);
+                        for (int g2 = 0; g2 < G; ++g2)
+                            write_operand_lds<BF16, PP>(gbuf + (t & 1) * BUF + lds_row, g2 * D + e0 + 16 * eb, dg[g2]);
+                    } else {
+                        const uint32_t cnt = (uint32_t)iter * (uint32_t)T + (uint32_t)(T - t);
 #pragma unroll
-                    for (int g = 0; g < G; ++g) store_io_r<BF16, PP>(dwx_t, soff_wx, g * wx_gate, dwx[g]);
-                    if constexpr (CELL == CELL_GRU) store_io_r<BF16, PP>(make_rsrc(dgn_g + (size_t)(t - 1) * dh_step), soff_dh, 0, dg[2]);
+                        for (int g2 = 0; g2 < G; ++g2)
+                            publish4<BF16>(xr, (cnt & 1u) * xbuf + xgroup + (uint32_t)lm.bslot * XROW, g2 * D + e0, dg[g2], cnt + 1u);
+                    }
+#pragma unroll
+                    for (int g2 = 0; g2 < G; ++g2) store_io_r<BF16, PP>(dwx_t, soff_wx + eb * 16 * ESZ, g2 * wx_gate, dwx[g2]);
+                    if constexpr (CELL == CELL_GRU)
+                        store_io_r<BF16, PP>(make_rsrc(dgn_g + (size_t)(t - 1) * dh_step), soff_dh + eb * 16 * ESZ, 0, dg[2]);
                 }
             }
-            // ---- dh_{t-1} += R dg_t on the matrix cores; four accumulators break the dependent chain
-            f32x4 a4[4];
+            // ---- dh_{t-1} += R dg_t on the matrix cores; NA accumulators per unit block break the dependent chain
+            constexpr int NA = EB == 1 ? 4 : 2;
+            f32x4 a4[EB][NA];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) a4[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int eb = 0; eb < EB; ++eb)
+#pragma unroll
+            for (int j = 0; j < NA; ++j) a4[eb][j] = f32x4{0.f, 0.f, 0.f, 0.f};
             if constexpr (!MULTI) {
                 __syncthreads();
                 op_t gB[KT];
                 read_operand_lds<BF16, KT>(gbuf + (t & 1) * BUF + lds_row, k0, lm.quad, gB);
 #pragma unroll
-                for (int kt = 0; kt < KT; ++kt) a4[kt & 3] = OP::mfma(Rf[kt], gB[kt], a4[kt & 3]);
+                for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                    for (int eb = 0; eb < EB; ++eb) a4[eb][kt % NA] = OP::mfma(Rf[eb][kt], gB[kt], a4[eb][kt % NA]);
             } else {
                 const uint32_t cnt = (uint32_t)iter * (uint32_t)T + (uint32_t)(T - t);
                 const uint32_t row_off = (cnt & 1u) * xbuf + xgroup + (uint32_t)lm.c * XROW;
@@ -703,34 +743,48 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
                         for (int j = 0; j < KC; ++j) gB[j] = op_t{};
                     }
 #pragma unroll
-                    for (int j = 0; j < KC; ++j) a4[(kc + j) & 3] = OP::mfma(Rf[kc + j], gB[j], a4[(kc + j) & 3]);
+                    for (int j = 0; j < KC; ++j) a4[0][(kc + j) % NA] = OP::mfma(Rf[0][kc + j], gB[j], a4[0][(kc + j) % NA]);
                 }
             }
-            f32x4 acc[1];
-            acc[0] = (a4[0] + a4[1]) + (a4[2] + a4[3]);
-            reduce_slices<1, KS>(red, t & 1, ks, wu, p.NWU, lane, acc);
-            if (KS == 1 || ks == 0) {
-                compact_tile<BT>(acc[0]);
+            f32x4 accs[EB][1];
 #pragma unroll
-                for (int i = 0; i < PP; ++i) ds[0][i] += acc[0][i];
+            for (int eb = 0; eb < EB; ++eb) {
+                if constexpr (NA == 4) accs[eb][0] = (a4[eb][0] + a4[eb][1]) + (a4[eb][2] + a4[eb][3]);
+                else accs[eb][0] = a4[eb][0] + a4[eb][1];
+            }
+            reduce_slices<1, KS>(red, t & 1, ks, wu, p.NWU, lane, accs[0]);
+            if (KS == 1 || ks == 0) {
+#pragma unroll
+                for (int eb = 0; eb < EB; ++eb) {
+                    compact_tile<BT>(accs[eb][0]);
+#pragma unroll
+                    for (int i = 0; i < PP; ++i) ds[eb][0][i] += accs[eb][0][i];
+                }
                 // wait for the prefetched inputs here, where only this step's stores are younger
-                pin(cvn); pin(scn); pin(spn); pin(dhn);
+#pragma unroll
+                for (int eb = 0; eb < EB; ++eb) { pin(cvn[eb]); pin(scn[eb]); pin(spn[eb]); pin(dhn[eb]); }
+#pragma unroll
+                for (int eb = 0; eb < EB; ++eb)
 #pragma unroll
                 for (int i = 0; i < PP; ++i) {
 #pragma unroll
-                    for (int c2 = 0; c2 < NC; ++c2) cv[c2][i] = cvn[c2][i];
+                    for (int c2 = 0; c2 < NC; ++c2) cv[eb][c2][i] = cvn[eb][c2][i];
 #pragma unroll
-                    for (int s = 0; s < S; ++s) { sc[s][i] = scn[s][i]; sp[s][i] = spn[s][i]; }
-                    dh_ext[i] = dhn[i];
+                    for (int s = 0; s < S; ++s) { sc[eb][s][i] = scn[eb][s][i]; sp[eb][s][i] = spn[eb][s][i]; }
+                    dh_ext[eb][i] = dhn[eb][i];
                 }
             }
         }
         // ---- gradients w.r.t. the initial states, per-row partial sums of db
         if (lane_ok) {
 #pragma unroll
-            for (int s = 0; s < S; ++s) store_io_r<false, PP>(make_rsrc((char*)p.dstates0 + (size_t)n * D * 4), voff_st, s * st_state, ds[s]);
+            for (int eb = 0; eb < EB; ++eb) {
 #pragma unroll
-            for (int g = 0; g < G; ++g) store_f32<PP>(p.db_part, (((size_t)bb * NH + n) * G + g) * D + e0, dbacc[g]);
+                for (int s = 0; s < S; ++s)
+                    store_io_r<false, PP>(make_rsrc((char*)p.dstates0 + (size_t)n * D * 4), voff_st + eb * 64, s * st_state, ds[eb][s]);
+#pragma unroll
+                for (int g2 = 0; g2 < G; ++g2) store_f32<PP>(p.db_part, (((size_t)bb * NH + n) * G + g2) * D + e0 + 16 * eb, dbacc[eb][g2]);
+            }
         }
     }
 }
