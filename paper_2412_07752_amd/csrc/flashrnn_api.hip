@@ -112,12 +112,9 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
                 pl.DK = best->KT * kstep;
                 const int hp = pl.DK + (bf ? 8 : 4);
                 pl.smem = (size_t)2 * best->BT * hp * (bf ? 2 : 4);
-                if (bf && best->BT < 16) {
-                    // LDS row images of one step's inputs and outputs, two of each (staged I/O)
-                    const size_t S = num_states(d->cell), NCV = num_cached(d->cell), bt = best->BT, D = d->D;
-                    const size_t in_b = bwd ? bt * D * (NCV * 2 + 2 * S * 4 + 2) : bt * G * D * 2;
-                    const size_t out_b = bwd ? bt * (G + 1) * D * 2 : bt * S * D * 4 + bt * NCV * D * 2;
-                    pl.smem += 2 * in_b + 2 * out_b + 64;
+                if (bf && best->BT < 16 && !bwd && best->eb == 1) {
+                    // tile kernel: operand rows + LDS row images of one step's inputs and outputs
+                    pl.smem = tile_lds(best->BT, G, num_states(d->cell), d->D, pl.block, pl.DK * 2, 0, 0, 0).total_fwd;
                 }
                 pl.exch_bytes = 0;
             }
@@ -260,7 +257,7 @@ int flashrnn_num_gates(int cell) { return num_gates(cell); }
 
 size_t flashrnn_gate_cache_bytes(const flashrnn_desc_t* d) {
     if (validate(d) != FLASHRNN_OK) return 0;
-    return (size_t)d->T * d->B * d->NH * num_cached(d->cell) * d->D * io_size(d->io_dtype);
+    return (size_t)d->T * d->B * d->NH * d->D * kCacheSlots * io_size(d->io_dtype);
 }
 
 size_t flashrnn_workspace_bytes(const flashrnn_desc_t* d) {

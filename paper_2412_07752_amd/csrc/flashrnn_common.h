@@ -31,6 +31,56 @@ template <> struct CellTraits<CELL_SLSTM> { static constexpr int G = 4, S = 4, N
 //   GRU   sig(r), sig(z), tanh(candidate), yn = R_n h + b_n
 //   sLSTM input weight exp(i - m_t), forget weight exp(log sig(f) + m_{t-1} - m_t), tanh(z), sig(o), sig(-f)
 
+// The saved values of one (t, batch row, head, unit) form one 16-byte record of kCacheSlots elements
+// (bf16 I/O; with f32 I/O the record is 32 bytes): cache[T][B][NH][D][kCacheSlots].  One record is one
+// wide store in the forward pass and one wide load in the backward pass.
+constexpr int kCacheSlots = 8;
+
+// Row pitch (bytes) of an LDS row image whose rows hold `row_bytes` of data: padded so that
+// consecutive rows start 16 banks (64 bytes) apart modulo the 64 banks, which keeps the 4-rows x
+// 16-units access pattern of a wave free of bank conflicts.
+__host__ __device__ inline uint32_t lds_row_pitch(uint32_t row_bytes) {
+    const uint32_t dw = row_bytes / 4;
+    return (dw + (16u + 64u - dw % 64u) % 64u) * 4u;
+}
+
+// LDS layout of the tile kernels (bf16 I/O, one workgroup per group, BT < 16), shared by the kernels
+// and by the host code that sizes the dynamic LDS.  NT threads; every thread moves NCH 16-byte chunks
+// of each image per step, threads without a real chunk own a private pad chunk behind the image.
+struct TileLds {
+    uint32_t hp;                              // operand row pitch (bytes), buf = BT * hp
+    uint32_t rp_io, rp_st;                    // image row pitches: bf16 rows, f32 rows
+    uint32_t in_bytes, in_pitch;              // forward inputs Wx (BT*G rows) / backward outputs dWx (+dgn)
+    uint32_t st_bytes, st_pitch;              // f32 state rows
+    uint32_t c_bytes, c_pitch;                // saved-values records (BT*D records of 16 bytes)
+    uint32_t dh_bytes, dh_pitch;              // backward: external dh rows (BT rows)
+    uint32_t total_fwd, total_bwd;
+};
+__host__ __device__ inline uint32_t div_up(uint32_t a, uint32_t b) { return (a + b - 1) / b; }
+__host__ __device__ inline TileLds tile_lds(int BT, int G, int S, int D, int NT, int k_bytes_fwd, int k_bytes_bwd, int st_rows_bwd, int out_rows_bwd) {
+    TileLds L;
+    const uint32_t nt16 = (uint32_t)NT * 16;
+    L.rp_io = lds_row_pitch((uint32_t)D * 2);
+    L.rp_st = lds_row_pitch((uint32_t)D * 4);
+    L.in_bytes = (uint32_t)BT * G * L.rp_io;
+    L.in_pitch = L.in_bytes + div_up((uint32_t)BT * G * (D / 8), NT) * nt16;
+    L.st_bytes = (uint32_t)BT * S * L.rp_st;
+    L.st_pitch = L.st_bytes + div_up((uint32_t)BT * S * (D / 4), NT) * nt16;
+    L.c_bytes = (uint32_t)BT * D * 16;
+    L.c_pitch = div_up((uint32_t)BT * D, NT) * nt16;
+    L.dh_bytes = (uint32_t)BT * L.rp_io;
+    L.dh_pitch = L.dh_bytes + div_up((uint32_t)BT * (D / 8), NT) * nt16;
+    L.hp = lds_row_pitch((uint32_t)k_bytes_fwd);
+    L.total_fwd = 2 * BT * L.hp + 2 * L.in_pitch + 2 * (L.st_pitch + L.c_pitch);
+    // backward: operand rows of k_bytes_bwd; images: saved values, st_rows_bwd state rows per batch row
+    // (at two time levels they are loaded as one image per step), dh, and out_rows_bwd bf16 output rows
+    const uint32_t hpb = lds_row_pitch((uint32_t)k_bytes_bwd);
+    const uint32_t stb = (uint32_t)BT * st_rows_bwd * L.rp_st, stbp = stb + div_up((uint32_t)BT * st_rows_bwd * (D / 4), NT) * nt16;
+    const uint32_t ob = (uint32_t)BT * out_rows_bwd * L.rp_io, obp = ob + div_up((uint32_t)BT * out_rows_bwd * (D / 8), NT) * nt16;
+    L.total_bwd = 2 * BT * hpb + 2 * L.c_pitch + 3 * stbp + 2 * L.dh_pitch + 2 * obp;
+    return L;
+}
+
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -43,7 +93,7 @@ struct KernelParams {
     const void* bias;      // [NH,G,D] io
     const float* states0;  // fwd: [S,B,NH,D] or null
     float* states;         // [T+1,S,B,NH,D]
-    void* cache;           // [T,B,NH,NC,D] io dtype, may be null in fwd
+    void* cache;           // [T,B,NH,D,kCacheSlots] io dtype, may be null in fwd
     const void* dH;        // bwd: [T,B,NH,D] io
     const float* dlast;    // bwd: [S,B,NH,D] or null
     void* dWx;             // bwd: [T,B,G,NH,D] io
@@ -201,6 +251,41 @@ template <bool BF16, int PP> __device__ __forceinline__ void store_io_r(rsrc_t r
         else if constexpr (PP == 2) __builtin_amdgcn_raw_buffer_store_b64(i32x2{__builtin_bit_cast(int, v[0]), __builtin_bit_cast(int, v[1])}, r, voff, soff, 0);
         else __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, v[0]), r, voff, soff, 0);
     }
+}
+
+// one saved-values record (NC values used of kCacheSlots) at byte offset voff + soff of resource r
+template <bool BF16, int NC> __device__ __forceinline__ void store_record(rsrc_t r, uint32_t voff, uint32_t soff, const float (&v)[NC]) {
+    float w[kCacheSlots];
+#pragma unroll
+    for (int j = 0; j < kCacheSlots; ++j) w[j] = j < NC ? v[j] : 0.0f;
+    if constexpr (BF16) {
+        __builtin_amdgcn_raw_buffer_store_b128(i32x4{(int)pack_bf16x2(w[0], w[1]), (int)pack_bf16x2(w[2], w[3]), (int)pack_bf16x2(w[4], w[5]),
+                                                     (int)pack_bf16x2(w[6], w[7])}, r, voff, soff, 0);
+    } else {
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(i32x4, f32x4{w[0], w[1], w[2], w[3]}), r, voff, soff, 0);
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(i32x4, f32x4{w[4], w[5], w[6], w[7]}), r, voff + 16, soff, 0);
+    }
+}
+template <bool BF16, int NC> __device__ __forceinline__ void unpack_record(const i32x4 lo, const i32x4 hi, float (&v)[NC]) {
+    float w[kCacheSlots];
+    if constexpr (BF16) {
+        const int a = lo[0], b = lo[1], c2 = lo[2], d = lo[3];
+        w[0] = bf16_bits_to_f32((uint32_t)a & 0xFFFFu); w[1] = __builtin_bit_cast(float, (uint32_t)a & 0xFFFF0000u);
+        w[2] = bf16_bits_to_f32((uint32_t)b & 0xFFFFu); w[3] = __builtin_bit_cast(float, (uint32_t)b & 0xFFFF0000u);
+        w[4] = bf16_bits_to_f32((uint32_t)c2 & 0xFFFFu); w[5] = __builtin_bit_cast(float, (uint32_t)c2 & 0xFFFF0000u);
+        w[6] = bf16_bits_to_f32((uint32_t)d & 0xFFFFu); w[7] = __builtin_bit_cast(float, (uint32_t)d & 0xFFFF0000u);
+    } else {
+        const f32x4 x = __builtin_bit_cast(f32x4, lo), y = __builtin_bit_cast(f32x4, hi);
+        w[0] = x[0]; w[1] = x[1]; w[2] = x[2]; w[3] = x[3]; w[4] = y[0]; w[5] = y[1]; w[6] = y[2]; w[7] = y[3];
+    }
+#pragma unroll
+    for (int j = 0; j < NC; ++j) v[j] = w[j];
+}
+template <bool BF16, int NC> __device__ __forceinline__ void load_record(rsrc_t r, uint32_t voff, uint32_t soff, float (&v)[NC]) {
+    const i32x4 lo = __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
+    i32x4 hi = lo;
+    if constexpr (!BF16) hi = __builtin_amdgcn_raw_buffer_load_b128(r, voff + 16, soff, 0);
+    unpack_record<BF16, NC>(lo, hi, v);
 }
 
 template <int PP> __device__ __forceinline__ void load_f32(const float* base, size_t idx, float (&out)[PP]) {

@@ -337,14 +337,6 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
     static_assert(KS == 1 || MULTI, "contraction slices are only used with several workgroups per group");
     static_assert(!MULTI || KT % KC == 0, "poll chunks must tile the k-steps");
     static_assert(EB == 1 || !MULTI, "several unit blocks per wave only with one workgroup per group");
-    // Small batch tiles leave each lane one or two values per row: their global accesses would be many
-    // narrow, scattered instructions, and the CU's single memory pipeline (about 16 cycles per such
-    // instruction) would bound the step.  They go through LDS instead: lanes write their values into
-    // row images in LDS, and every thread moves one 16-byte chunk per row image between LDS and HBM.
-    constexpr bool STAGE = BF16 && !MULTI && BT < 16;
-    constexpr int NCH_IN = (BT * G * EB + 31) / 32;    // 16-byte chunks per thread: inputs,
-    constexpr int NCH_ST = (BT * S * EB + 15) / 16;    // states,
-    constexpr int NCH_C = (BT * NC * EB + 31) / 32;    // saved values
 
     extern __shared__ __align__(16) char smem[];
     const BlockMap bm(p, MULTI);
@@ -372,15 +364,8 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
     const uint32_t wx_gate = HD * ESZ;
     const size_t st_step = (size_t)S * B * HD * 4;
     const uint32_t st_state = (uint32_t)B * HD * 4;
-    const size_t c_step = (size_t)B * HD * NC * ESZ;
-    const uint32_t c_slot = (uint32_t)D * ESZ;
-    // staged I/O: LDS images of the rows of one step (runtime sizes, D is a launch parameter)
-    const uint32_t IN_BYTES = (uint32_t)BT * G * D * ESZ, ST_BYTES = (uint32_t)BT * S * D * 4, C_BYTES = (uint32_t)BT * NC * D * ESZ;
-    const uint32_t OUT_BYTES = ST_BYTES + C_BYTES;
-    char* in_stage = smem + 2 * BUF;                 // [2][IN_BYTES]
-    char* out_stage = in_stage + 2 * IN_BYTES;       // [2][OUT_BYTES]
-    char* dummy = out_stage + 2 * OUT_BYTES;         // 16 bytes nobody reads
-    const int NT = blockDim.x, tid = threadIdx.x;
+    constexpr uint32_t REC = kCacheSlots * ESZ;                 // bytes of one saved-values record
+    const size_t c_step = (size_t)B * HD * REC;
     // LDS lane offsets inside one operand buffer
     const uint32_t lds_rd = (uint32_t)lm.bslot * HP * ESZ;     // row this lane reads as the B operand column
     const uint32_t lds_wr = (uint32_t)lm.bslot * HP * ESZ;     // row this lane writes its new h into
@@ -412,48 +397,12 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
         // per-group uniform bases and per-lane offsets
         const char* wx_g = (const char*)p.Wx + (size_t)n * D * ESZ;
         char* st_g = (char*)p.states + (size_t)n * D * 4;
-        char* c_g = (char*)p.cache + (size_t)n * NC * D * ESZ;
+        char* c_g = (char*)p.cache + (size_t)n * D * REC;
         constexpr uint32_t kDrop = 0x80000000u;  // beyond every resource's range: the access is dropped
         const uint32_t voff_wx = ((uint32_t)bb * G * HD + e0) * ESZ;
         const uint32_t voff_st = ((uint32_t)bb * HD + e0) * 4;
         const uint32_t soff_st = lane_ok ? voff_st : kDrop;
-        const uint32_t soff_c = (lane_ok && p.cache != nullptr) ? ((uint32_t)bb * HD * NC + e0) * ESZ : kDrop;
-
-        // staged I/O roles of this thread: which 16-byte chunks it moves (global offset, LDS offset)
-        uint32_t cin_g[NCH_IN], cin_l[NCH_IN], cst_g[NCH_ST], cst_l[NCH_ST], cc_g[NCH_C], cc_l[NCH_C];
-        if constexpr (STAGE) {
-            const uint32_t cpr_io = (uint32_t)D / 8, cpr_st = (uint32_t)D / 4;   // chunks per row
-            const uint32_t dummy_off = (uint32_t)(dummy - smem);
-#pragma unroll
-            for (int k2 = 0; k2 < NCH_IN; ++k2) {
-                const uint32_t idx = tid + k2 * NT, row = idx / cpr_io, ch = idx % cpr_io;
-                const uint32_t bs = row / G, g = row % G, brow = q * BT + bs;
-                const bool ok = idx < IN_BYTES / 16 && brow < (uint32_t)B;
-                cin_g[k2] = ok ? ((brow * G + g) * HD) * ESZ + ch * 16 : kDrop;
-                cin_l[k2] = idx < IN_BYTES / 16 ? idx * 16 : dummy_off;
-            }
-#pragma unroll
-            for (int k2 = 0; k2 < NCH_ST; ++k2) {
-                const uint32_t idx = tid + k2 * NT, row = idx / cpr_st, ch = idx % cpr_st;
-                const uint32_t s = row / BT, bs = row % BT, brow = q * BT + bs;
-                const bool ok = idx < ST_BYTES / 16 && brow < (uint32_t)B;
-                cst_g[k2] = ok ? s * st_state + (brow * HD) * 4 + ch * 16 : kDrop;
-                cst_l[k2] = idx < ST_BYTES / 16 ? idx * 16 : dummy_off;
-            }
-#pragma unroll
-            for (int k2 = 0; k2 < NCH_C; ++k2) {
-                const uint32_t idx = tid + k2 * NT, row = idx / cpr_io, ch = idx % cpr_io;
-                const uint32_t c2 = row / BT, bs = row % BT, brow = q * BT + bs;
-                const bool ok = idx < C_BYTES / 16 && brow < (uint32_t)B && p.cache != nullptr;
-                cc_g[k2] = ok ? (brow * HD * NC + c2 * D) * ESZ + ch * 16 : kDrop;
-                cc_l[k2] = idx < C_BYTES / 16 ? ST_BYTES + idx * 16 : dummy_off;
-            }
-        }
-        // this lane's places in the row images: inputs (row = slot * G + g), states (row = s * BT + slot),
-        // saved values (row = c2 * BT + slot)
-        const uint32_t l_in = ((uint32_t)lm.bslot * G * D + e0) * ESZ;
-        const uint32_t l_st = ((uint32_t)lm.bslot * D + e0) * 4;
-        const uint32_t l_c = ST_BYTES + ((uint32_t)lm.bslot * D + e0) * ESZ;
+        const uint32_t soff_c = (lane_ok && p.cache != nullptr) ? ((uint32_t)bb * HD + e0) * REC : kDrop;
 
         // ---- initial states
         float st[EB][S][PP];
@@ -483,16 +432,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
 
         // input pre-activations are fetched one step ahead
         float wx[EB][G][PP];
-        if constexpr (STAGE) {
-            // the row image of step 1's inputs; the images of later steps are filled one step ahead
-            if (T > 0) {
-                const rsrc_t rs1 = make_rsrc(wx_g);
-#pragma unroll
-                for (int k2 = 0; k2 < NCH_IN; ++k2)
-                    *(i32x4*)(in_stage + IN_BYTES + cin_l[k2]) = __builtin_amdgcn_raw_buffer_load_b128(rs1, cin_g[k2], 0, 0);
-            }
-            __syncthreads();
-        } else if (T > 0) {
+        if (T > 0) {
 #pragma unroll
             for (int eb = 0; eb < EB; ++eb)
 #pragma unroll
@@ -502,36 +442,12 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
         for (int t = 1; t <= T; ++t) {
             // ---- prefetch the inputs of step t + 1 (clamped at the end)
             float wxn[EB][G][PP];
-            i32x4 pre[NCH_IN];
             {
                 const rsrc_t rsn = make_rsrc(wx_g + (size_t)(t < T ? t : T - 1) * wx_step);
-                if constexpr (STAGE) {
-                    // this thread's chunk of the next step's inputs (lands in LDS at the end of the step)
 #pragma unroll
-                    for (int k2 = 0; k2 < NCH_IN; ++k2) pre[k2] = __builtin_amdgcn_raw_buffer_load_b128(rsn, cin_g[k2], 0, 0);
-                    // move the previous step's outputs from their LDS image to HBM (nothing at t = 1)
-                    const uint32_t none = t == 1 ? kDrop : 0u;
-                    const char* img = out_stage + ((t - 1) & 1) * OUT_BYTES;
-                    const rsrc_t rs_st = make_rsrc(st_g + (size_t)(t - 1) * st_step);
-                    const rsrc_t rs_c = make_rsrc(c_g + (size_t)(t >= 2 ? t - 2 : 0) * c_step);
+                for (int eb = 0; eb < EB; ++eb)
 #pragma unroll
-                    for (int k2 = 0; k2 < NCH_ST; ++k2)
-                        __builtin_amdgcn_raw_buffer_store_b128(*(const i32x4*)(img + cst_l[k2]), rs_st, cst_g[k2] | none, 0, 0);
-#pragma unroll
-                    for (int k2 = 0; k2 < NCH_C; ++k2)
-                        __builtin_amdgcn_raw_buffer_store_b128(*(const i32x4*)(img + cc_l[k2]), rs_c, cc_g[k2] | none, 0, 0);
-                    // this step's inputs from their LDS image
-                    const char* im_in = in_stage + (t & 1) * IN_BYTES + l_in;
-#pragma unroll
-                    for (int eb = 0; eb < EB; ++eb)
-#pragma unroll
-                    for (int g = 0; g < G; ++g) load_io<BF16, PP>(im_in + ((uint32_t)g * D + 16 * eb) * ESZ, 0, wx[eb][g]);
-                } else {
-#pragma unroll
-                    for (int eb = 0; eb < EB; ++eb)
-#pragma unroll
-                    for (int g = 0; g < G; ++g) load_io_r<BF16, PP>(rsn, voff_wx + eb * 16 * ESZ, g * wx_gate, wxn[eb][g]);
-                }
+                for (int g = 0; g < G; ++g) load_io_r<BF16, PP>(rsn, voff_wx + eb * 16 * ESZ, g * wx_gate, wxn[eb][g]);
             }
             // ---- recurrent product y = R^T h_{t-1} on the matrix cores
             f32x4 accs[EB][G];
@@ -600,20 +516,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
                 // stores of lanes without a valid row (and of the saved values in a forward-only call) carry
                 // an out-of-range offset and are dropped by the buffer bounds check: no branch, so the
                 // wait for the prefetched inputs at the end of the step does not have to cover them
-                if constexpr (STAGE) {
-                    char* img = out_stage + (t & 1) * OUT_BYTES;
-#pragma unroll
-                    for (int eb = 0; eb < EB; ++eb) {
-#pragma unroll
-                        for (int s = 0; s < S; ++s) store_io<false, PP>(img + l_st + ((uint32_t)s * BT * D + 16 * eb) * 4, 0, st[eb][s]);
-#pragma unroll
-                        for (int c2 = 0; c2 < NC; ++c2) store_io<BF16, PP>(img + l_c + ((uint32_t)c2 * BT * D + 16 * eb) * ESZ, 0, cvs[eb][c2]);
-                    }
-                    // the next step's input chunk has had the whole step to arrive
-                    char* im_in = in_stage + ((t + 1) & 1) * IN_BYTES;
-#pragma unroll
-                    for (int k2 = 0; k2 < NCH_IN; ++k2) *(i32x4*)(im_in + cin_l[k2]) = pre[k2];
-                } else {
+                {
                     const rsrc_t rs_st = make_rsrc(st_g + (size_t)t * st_step);
                     const rsrc_t rs_c = make_rsrc(c_g + (size_t)(t - 1) * c_step);
 #pragma unroll
@@ -621,7 +524,12 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
 #pragma unroll
                         for (int s = 0; s < S; ++s) store_io_r<false, PP>(rs_st, soff_st + eb * 64, s * st_state, st[eb][s]);
 #pragma unroll
-                        for (int c2 = 0; c2 < NC; ++c2) store_io_r<BF16, PP>(rs_c, soff_c + eb * 16 * ESZ, c2 * c_slot, cvs[eb][c2]);
+                        for (int i = 0; i < PP; ++i) {
+                            float rec[NC];
+#pragma unroll
+                            for (int c2 = 0; c2 < NC; ++c2) rec[c2] = cvs[eb][c2][i];
+                            store_record<BF16, NC>(rs_c, soff_c + (eb * 16 + i) * REC, 0, rec);
+                        }
                     }
                 }
             }
@@ -630,19 +538,8 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
 #pragma unroll
             for (int g = 0; g < G; ++g)
 #pragma unroll
-                for (int i = 0; i < PP; ++i) if constexpr (!STAGE) wx[eb][g][i] = wxn[eb][g][i];
+                for (int i = 0; i < PP; ++i) wx[eb][g][i] = wxn[eb][g][i];
             if constexpr (!MULTI) __syncthreads();
-        }
-        if constexpr (STAGE) {
-            if (T > 0) {
-                const char* img = out_stage + (T & 1) * OUT_BYTES;
-                const rsrc_t rs_st = make_rsrc(st_g + (size_t)T * st_step);
-                const rsrc_t rs_c = make_rsrc(c_g + (size_t)(T - 1) * c_step);
-#pragma unroll
-                for (int k2 = 0; k2 < NCH_ST; ++k2) __builtin_amdgcn_raw_buffer_store_b128(*(const i32x4*)(img + cst_l[k2]), rs_st, cst_g[k2], 0, 0);
-#pragma unroll
-                for (int k2 = 0; k2 < NCH_C; ++k2) __builtin_amdgcn_raw_buffer_store_b128(*(const i32x4*)(img + cc_l[k2]), rs_c, cc_g[k2], 0, 0);
-            }
         }
     }
 }
@@ -696,8 +593,8 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
     const uint32_t wx_gate = HD * ESZ;
     const size_t st_step = (size_t)S * B * HD * 4;
     const uint32_t st_state = (uint32_t)B * HD * 4;
-    const size_t c_step = (size_t)B * HD * NC * ESZ;
-    const uint32_t c_slot = (uint32_t)D * ESZ;
+    constexpr uint32_t REC = kCacheSlots * ESZ;                 // bytes of one saved-values record
+    const size_t c_step = (size_t)B * HD * REC;
     const size_t dh_step = (size_t)B * HD * ESZ;
     const uint32_t lds_row = (uint32_t)lm.bslot * HP * ESZ;
 
@@ -719,14 +616,14 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
         const bool row_valid = bb_raw < B;
         const int bb = row_valid ? bb_raw : B - 1;
         const bool lane_ok = row_valid && ks == 0;
-        const char* c_g = (const char*)p.cache + (size_t)n * NC * D * ESZ;
+        const char* c_g = (const char*)p.cache + (size_t)n * D * REC;
         const char* st_g = (const char*)p.states + (size_t)n * D * 4;
         const char* dh_g = (const char*)p.dH + (size_t)n * D * ESZ;
         char* dwx_g = (char*)p.dWx + (size_t)n * D * ESZ;
         char* dgn_g = (char*)p.dgn + (size_t)n * D * ESZ;
         constexpr uint32_t kDrop = 0x80000000u;  // beyond every resource's range: the access is dropped
         const uint32_t voff_st = ((uint32_t)bb * HD + e0) * 4;
-        const uint32_t voff_c = ((uint32_t)bb * HD * NC + e0) * ESZ;
+        const uint32_t voff_c = ((uint32_t)bb * HD + e0) * REC;
         const uint32_t voff_dh = ((uint32_t)bb * HD + e0) * ESZ;
         const uint32_t soff_wx = lane_ok ? ((uint32_t)bb * G * HD + e0) * ESZ : kDrop;
         const uint32_t soff_dh = lane_ok ? voff_dh : kDrop;
@@ -766,7 +663,12 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
 #pragma unroll
             for (int eb = 0; eb < EB; ++eb) {
 #pragma unroll
-            for (int c2 = 0; c2 < NC; ++c2) load_io_r<BF16, PP>(c_t, voff_c + eb * 16 * ESZ, c2 * c_slot, cv_[eb][c2]);
+            for (int i = 0; i < PP; ++i) {
+                float rec[NC];
+                load_record<BF16, NC>(c_t, voff_c + (eb * 16 + i) * REC, 0, rec);
+#pragma unroll
+                for (int c2 = 0; c2 < NC; ++c2) cv_[eb][c2][i] = rec[c2];
+            }
 #pragma unroll
             for (int s = 0; s < S; ++s) {
                 if (CELL != CELL_GRU && s > 0 && s < 3) load_io_r<false, PP>(st_t, voff_st + eb * 64, s * st_state, sc_[eb][s]);

@@ -1,0 +1,249 @@
+// Persistent kernels for the case that carries the headline workload: bf16 I/O, one workgroup per
+// group, batch tiles of 4 or 8 rows (BT < 16), one block of 16 units per wave.
+//
+// What bounds a step here (measured with per-phase cycle stamps on MI355X) is the matrix pipe of each
+// SIMD: three waves share it and their MFMA chains fill about 1150 cycles per step, while the
+// point-wise function takes about 100.  Everything that is not on the dependency chain
+//     h_{t-1} in LDS -> MFMA chain -> point-wise -> h_t in LDS -> barrier
+// is therefore issued between the MFMAs of the chain, where it costs nothing:
+//   - global traffic goes through LDS row images and moves as one 16-byte chunk per thread (a lane
+//     holds only one or two values per row, and the CU's memory pipeline needs about 16 cycles per
+//     narrow scattered instruction: 13 of them per wave and step would cost more than the MFMAs);
+//   - the outputs of step t-1 are written to their image during the chain of step t and leave for HBM
+//     during the chain of step t+1; the inputs of step t+1 are fetched during the chain of step t.
+// Image rows are padded (lds_row_pitch) so that a wave's 4-rows x 16-units accesses hit 64 distinct banks.
+#pragma once
+#include "flashrnn_kernels.h"
+
+namespace flashrnn {
+
+__device__ __forceinline__ void pin_order() { __builtin_amdgcn_sched_barrier(0); }
+
+// =============================================================================================
+// forward
+// =============================================================================================
+// LDS: [2] operand rows | [2] input image (BT*G bf16 rows) | [2] output image (BT*S f32 rows, then
+// BT*D saved-values records); sizes from tile_lds().
+template <int CELL, int KT, int BT, int MAXW>
+__global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams p) {
+    using CT = CellTraits<CELL>;
+    using OP = Operand<true>;
+    constexpr int G = CT::G, S = CT::S, NC = CT::NC;
+    constexpr int PP = BT / 4;
+    constexpr int ESZ = 2;
+    constexpr int DK = KT * 32;
+    constexpr int NCH_IN = (BT * G + 31) / 32, NCH_ST = (BT * S + 15) / 16, NCH_C = (BT + 3) / 4;
+    constexpr uint32_t kDrop = 0x80000000u;
+    constexpr uint32_t REC = kCacheSlots * ESZ;
+    static_assert(BT == 4 || BT == 8, "batch tiles of 4 or 8 rows");
+
+    extern __shared__ __align__(16) char smem[];
+    const int gid = blockIdx.x;
+    if (gid >= p.NG) return;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, tid = threadIdx.x, NT = blockDim.x;
+    stagger_waves(w);
+    const LaneMap<BT> lm(lane);
+    const int T = p.T, B = p.B, NH = p.NH, D = p.D;
+    const int n = gid % NH, q = gid / NH;
+    const int e_wave = w * 16, e0 = e_wave + lm.uoff;
+
+    const uint32_t HD = (uint32_t)NH * D;
+    const size_t wx_step = (size_t)B * G * HD * ESZ, st_step = (size_t)S * B * HD * 4, c_step = (size_t)B * HD * REC;
+    const uint32_t st_state = (uint32_t)B * HD * 4;
+    const TileLds L = tile_lds(BT, G, S, D, NT, DK * 2, 0, 0, 0);
+    const uint32_t BUF = BT * L.hp, OUT_PITCH = L.st_pitch + L.c_pitch;
+    const uint32_t tid16 = (uint32_t)tid * 16, NT16 = (uint32_t)NT * 16;
+    char* hbuf = smem;
+    char* in_img = smem + 2 * BUF;
+    char* out_img = in_img + 2 * L.in_pitch;
+
+    // ---- R fragments and bias: resident for all T steps
+    bf16x8 Rf[G][KT];
+    float bias[G][PP];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const size_t rrow = (((size_t)n * G + g) * D + e_wave + lm.c) * DK;
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt) Rf[g][kt] = *(const bf16x8*)((const uint16_t*)p.R + rrow + kt * 32 + lm.quad * 8);
+        load_io<true, PP>(p.bias, ((size_t)n * G + g) * D + e0, bias[g]);
+    }
+
+    const int bb_raw = q * BT + lm.bslot;
+    const bool row_valid = bb_raw < B;
+    const int bb = row_valid ? bb_raw : B - 1;
+    const char* wx_g = (const char*)p.Wx + (size_t)n * D * ESZ;
+    char* st_g = (char*)p.states + (size_t)n * D * 4;
+    char* c_g = (char*)p.cache + (size_t)n * D * REC;
+    const uint32_t voff_st = ((uint32_t)bb * HD + e0) * 4;
+
+    // ---- chunk roles: global byte offset (out of range = nothing to move) and LDS offset inside the image
+    uint32_t cin_g[NCH_IN], cin_l[NCH_IN], cst_g[NCH_ST], cst_l[NCH_ST], cc_g[NCH_C];
+    {
+        const uint32_t cpr_io = (uint32_t)D / 8, cpr_st = (uint32_t)D / 4;
+#pragma unroll
+        for (int k2 = 0; k2 < NCH_IN; ++k2) {
+            const uint32_t idx = tid + k2 * NT, row = idx / cpr_io, ch = idx % cpr_io, brow = q * BT + row / G, g = row % G;
+            const bool in = row < (uint32_t)BT * G;
+            cin_g[k2] = (in && brow < (uint32_t)B) ? ((brow * G + g) * HD) * ESZ + ch * 16 : kDrop;
+            cin_l[k2] = in ? row * L.rp_io + ch * 16 : L.in_bytes + tid16 + k2 * NT16;
+        }
+#pragma unroll
+        for (int k2 = 0; k2 < NCH_ST; ++k2) {
+            const uint32_t idx = tid + k2 * NT, row = idx / cpr_st, ch = idx % cpr_st, s = row / BT, brow = q * BT + row % BT;
+            const bool in = row < (uint32_t)BT * S;
+            cst_g[k2] = (in && brow < (uint32_t)B) ? s * st_state + (brow * HD) * 4 + ch * 16 : kDrop;
+            cst_l[k2] = in ? row * L.rp_st + ch * 16 : L.st_bytes + tid16 + k2 * NT16;
+        }
+#pragma unroll
+        for (int k2 = 0; k2 < NCH_C; ++k2) {  // records: chunk idx = slot * D + unit, LDS offset idx * 16
+            const uint32_t idx = tid + k2 * NT, row = idx / (uint32_t)D, u = idx % (uint32_t)D, brow = q * BT + row;
+            cc_g[k2] = (row < (uint32_t)BT && brow < (uint32_t)B && p.cache != nullptr) ? (brow * HD + u) * REC : kDrop;
+        }
+    }
+    // this lane's places: inputs row = slot*G + g, states row = s*BT + slot, records slot*D + unit
+    const uint32_t l_in = (uint32_t)lm.bslot * G * L.rp_io + e0 * ESZ;
+    const uint32_t l_st = (uint32_t)lm.bslot * L.rp_st + e0 * 4;
+    const uint32_t l_c = L.st_pitch + ((uint32_t)lm.bslot * D + e0) * REC;
+    const uint32_t lds_row = (uint32_t)lm.bslot * L.hp;
+
+    // ---- initial states: slot 0 is written directly (once)
+    float st[S][PP];
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+        if (p.states0 != nullptr) load_io_r<false, PP>(make_rsrc((const char*)p.states0 + (size_t)n * D * 4), voff_st, s * st_state, st[s]);
+        else
+#pragma unroll
+            for (int i = 0; i < PP; ++i) st[s][i] = 0.0f;
+        store_io_r<false, PP>(make_rsrc(st_g), row_valid ? voff_st : kDrop, s * st_state, st[s]);
+    }
+    for (uint32_t j = tid; j < 2 * BUF / 4; j += NT) ((uint32_t*)hbuf)[j] = 0u;
+    __syncthreads();
+    write_operand_lds<true, PP>(hbuf + lds_row, e0, st[0]);
+    if (T > 0) {
+        const rsrc_t rs1 = make_rsrc(wx_g);
+#pragma unroll
+        for (int k2 = 0; k2 < NCH_IN; ++k2) *(i32x4*)(in_img + L.in_pitch + cin_l[k2]) = __builtin_amdgcn_raw_buffer_load_b128(rs1, cin_g[k2], 0, 0);
+    }
+    __syncthreads();
+
+    float cvs[NC][PP];
+#pragma unroll
+    for (int c2 = 0; c2 < NC; ++c2)
+#pragma unroll
+        for (int i = 0; i < PP; ++i) cvs[c2][i] = 0.0f;
+
+    // move the image of the outputs of step j to HBM: states slot j, saved values slot j - 1
+    auto copy_out_load = [&](int j, i32x4 (&vs)[NCH_ST], i32x4 (&vc)[NCH_C]) {
+        const char* img = out_img + (j & 1) * OUT_PITCH;
+#pragma unroll
+        for (int k2 = 0; k2 < NCH_ST; ++k2) vs[k2] = *(const i32x4*)(img + cst_l[k2]);
+#pragma unroll
+        for (int k2 = 0; k2 < NCH_C; ++k2) vc[k2] = *(const i32x4*)(img + L.st_pitch + tid16 + k2 * NT16);
+    };
+    auto copy_out_store = [&](int j, const i32x4 (&vs)[NCH_ST], const i32x4 (&vc)[NCH_C]) {
+        const uint32_t none = j < 1 ? kDrop : 0u;
+        const rsrc_t rs_st = make_rsrc(st_g + (size_t)(j < 1 ? 0 : j) * st_step);
+        const rsrc_t rs_c = make_rsrc(c_g + (size_t)(j < 1 ? 0 : j - 1) * c_step);
+#pragma unroll
+        for (int k2 = 0; k2 < NCH_ST; ++k2) __builtin_amdgcn_raw_buffer_store_b128(vs[k2], rs_st, cst_g[k2] | none, 0, 0);
+#pragma unroll
+        for (int k2 = 0; k2 < NCH_C; ++k2) __builtin_amdgcn_raw_buffer_store_b128(vc[k2], rs_c, cc_g[k2] | none, 0, 0);
+    };
+    auto write_image = [&](int j) {  // outputs of step j (current st, cvs) into their image
+        char* img = out_img + (j & 1) * OUT_PITCH;
+#pragma unroll
+        for (int s = 0; s < S; ++s) store_io<false, PP>(img + l_st + (uint32_t)s * BT * L.rp_st, 0, st[s]);
+#pragma unroll
+        for (int i = 0; i < PP; ++i) {
+            float wv[kCacheSlots];
+#pragma unroll
+            for (int c2 = 0; c2 < kCacheSlots; ++c2) wv[c2] = c2 < NC ? cvs[c2 < NC ? c2 : 0][i] : 0.0f;
+            *(i32x4*)(img + l_c + i * REC) = i32x4{(int)pack_bf16x2(wv[0], wv[1]), (int)pack_bf16x2(wv[2], wv[3]),
+                                                   (int)pack_bf16x2(wv[4], wv[5]), (int)pack_bf16x2(wv[6], wv[7])};
+        }
+    };
+
+    for (int t = 1; t <= T; ++t) {
+        // The MFMA chain of the step, k-step by k-step, with the work that is off the dependency chain
+        // issued in between (the sched barriers keep the compiler from bunching it up in front).
+        constexpr int H1 = KT < 3 ? KT : 3;   // operand k-steps fetched up front
+        bf16x8 hB[KT];
+        const char* hrow = hbuf + ((t - 1) & 1) * BUF + lds_row;
+#pragma unroll
+        for (int kt = 0; kt < H1; ++kt) hB[kt] = *(const bf16x8*)(hrow + (size_t)(kt * 32 + lm.quad * 8) * 2);
+        i32x4 pre[NCH_IN], vs[NCH_ST], vc[NCH_C];
+        {
+            const rsrc_t rsn = make_rsrc(wx_g + (size_t)(t < T ? t : T - 1) * wx_step);
+#pragma unroll
+            for (int k2 = 0; k2 < NCH_IN; ++k2) pre[k2] = __builtin_amdgcn_raw_buffer_load_b128(rsn, cin_g[k2], 0, 0);
+        }
+        pin_order();
+        f32x4 acc[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) acc[g] = OP::mfma(Rf[g][0], hB[0], f32x4{0.f, 0.f, 0.f, 0.f});
+        pin_order();
+        write_image(t - 1);                    // outputs of step t-1 into their image
+#pragma unroll
+        for (int kt = H1; kt < KT; ++kt) hB[kt] = *(const bf16x8*)(hrow + (size_t)(kt * 32 + lm.quad * 8) * 2);
+        pin_order();
+        if constexpr (KT > 1) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) acc[g] = OP::mfma(Rf[g][1], hB[1], acc[g]);
+        }
+        pin_order();
+        copy_out_load(t - 2, vs, vc);          // outputs of step t-2: image -> registers
+        float wx[G][PP];
+        {
+            const char* im = in_img + (t & 1) * L.in_pitch + l_in;   // this step's inputs from their image
+#pragma unroll
+            for (int g = 0; g < G; ++g) load_io<true, PP>(im + (uint32_t)g * L.rp_io, 0, wx[g]);
+        }
+        pin_order();
+        if constexpr (KT > 2) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) acc[g] = OP::mfma(Rf[g][2], hB[2], acc[g]);
+        }
+        pin_order();
+        copy_out_store(t - 2, vs, vc);         // ... -> HBM
+        pin_order();
+#pragma unroll
+        for (int kt = 3; kt < KT; ++kt)
+#pragma unroll
+            for (int g = 0; g < G; ++g) acc[g] = OP::mfma(Rf[g][kt], hB[kt], acc[g]);
+        // ---- point-wise function
+#pragma unroll
+        for (int g = 0; g < G; ++g) compact_tile<BT>(acc[g]);
+#pragma unroll
+        for (int i = 0; i < PP; ++i) {
+            float wxi[G], ybi[G], sti[S], cvi[NC];
+#pragma unroll
+            for (int g = 0; g < G; ++g) { wxi[g] = wx[g][i]; ybi[g] = acc[g][i] + bias[g][i]; }
+#pragma unroll
+            for (int s = 0; s < S; ++s) sti[s] = st[s][i];
+            Cell<CELL, true>::fwd(wxi, ybi, sti, cvi);
+#pragma unroll
+            for (int s = 0; s < S; ++s) st[s][i] = sti[s];
+#pragma unroll
+            for (int c2 = 0; c2 < NC; ++c2) cvs[c2][i] = cvi[c2];
+        }
+        write_operand_lds<true, PP>(hbuf + (t & 1) * BUF + lds_row, e0, st[0]);
+        {
+            char* im = in_img + ((t + 1) & 1) * L.in_pitch;
+#pragma unroll
+            for (int k2 = 0; k2 < NCH_IN; ++k2) *(i32x4*)(im + cin_l[k2]) = pre[k2];
+        }
+        __syncthreads();
+    }
+    // ---- drain: outputs of step T-1 (image written during step T) and of step T
+    if (T > 0) {
+        i32x4 vs[NCH_ST], vc[NCH_C];
+        copy_out_load(T - 1, vs, vc);
+        copy_out_store(T - 1, vs, vc);
+        write_image(T);
+        __syncthreads();
+        copy_out_load(T, vs, vc);
+        copy_out_store(T, vs, vc);
+    }
+}
+
+}  // namespace flashrnn

@@ -67,8 +67,7 @@ def test_sizes_and_plans_of_the_benchmark_configurations():
     from paper_2412_07752_amd import synth
     for w in synth.CONFIGS:
         d = api.make_desc(w.cell, w.T, w.B, w.NH, w.D, api.FLASHRNN_BF16 if w.dtype == "bf16" else api.FLASHRNN_F32)
-        nc = 5 if w.cell == synth.CELL_SLSTM else 4
-        assert api.flashrnn_gate_cache_bytes(d) == w.T * w.B * w.NH * nc * w.D * (2 if w.dtype == "bf16" else 4)
+        assert api.flashrnn_gate_cache_bytes(d) == w.T * w.B * w.NH * w.D * 8 * (2 if w.dtype == "bf16" else 4)
         assert api.flashrnn_workspace_bytes(d) > 0
         for bwd in (False, True):
             wgs, per_head, waves = api.flashrnn_plan(d, bwd)
