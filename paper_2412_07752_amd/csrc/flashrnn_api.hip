@@ -78,6 +78,8 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
     const int force_nwu = env_int("FLASHRNN_NWU", 0);
     const int force_ks = env_int("FLASHRNN_KS", 0);
     const int force_gpar = env_int("FLASHRNN_GPAR", 0);
+    const int force_ebk = env_int("FLASHRNN_EBK", 0);        // contraction slices of the backward tile kernel
+    const int force_kind = env_int("FLASHRNN_KIND", -1);     // kernel family (KernelEntry::tile)
     const int force_eb = env_int("FLASHRNN_EB", 0);          // blocks of 16 units per wave (one workgroup per group)      // groups in flight when groups are split (testing the group loop)
     Plan pl;
 
@@ -96,14 +98,21 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
             for (int i = 0; i < tab.count; ++i) {
                 const KernelEntry& e = tab.entries[i];
                 if (e.bwd != bwd || e.multi || e.KS != 1 || e.BT != bt_pref[b]) continue;
-                if (e.KT * kstep < kdim || units16 % e.eb != 0 || e.maxw * e.eb < units16) continue;
+                if (e.KT * kstep < kdim || units16 % e.eb != 0 || e.maxw * (e.tile == 1 ? 1 : e.eb) < units16) continue;
                 if (force_eb ? e.eb != force_eb : false) continue;
-                // smallest contraction padding first, then the thinnest waves (measured faster: more overlap between waves)
-                if (!best || e.KT < best->KT || (e.KT == best->KT && e.eb < best->eb)) best = &e;
+                if (force_kind >= 0 && e.tile != force_kind) continue;
+                if (force_ebk && bwd && e.tile == 1 && e.eb != force_ebk) continue;
+                // smallest contraction padding first; then the staged tile kernels before the generic one,
+                // there the thinnest waves
+                // the backward tile kernel splits the contraction over its waves only when the operand
+                // reads are many (k-steps x waves); otherwise the second barrier costs more than it saves
+                const bool split = bwd && e.KT * units16 >= 256;
+                auto rank_of = [&](const KernelEntry& x) { return x.tile == 1 ? ((x.eb > 1) == split ? 0 : 1) : 1 + x.eb; };
+                if (!best || e.KT < best->KT || (e.KT == best->KT && rank_of(e) < rank_of(*best))) best = &e;
             }
             if (best) {
                 pl.e = best;
-                pl.NWU = units16 / best->eb;
+                pl.NWU = best->tile == 1 ? units16 : units16 / best->eb;   // the tile kernels run one wave per block of 16 units
                 pl.P = 1;
                 pl.NG = d->NH * ((d->B + best->BT - 1) / best->BT);
                 pl.GPAR = pl.NG;
@@ -112,7 +121,10 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
                 pl.DK = best->KT * kstep;
                 const int hp = pl.DK + (bf ? 8 : 4);
                 pl.smem = (size_t)2 * best->BT * hp * (bf ? 2 : 4);
-                if (bf && best->BT < 16 && !bwd && best->eb == 1) {
+                if (best->tile == 1 && bwd) {
+                    const int nsb = d->cell == FLASHRNN_SLSTM ? 2 : 1, go = d->cell == FLASHRNN_GRU ? G + 1 : G;
+                    pl.smem = tile_lds_bwd(best->BT, go, nsb, d->D, pl.DK * 2, best->eb).total;
+                } else if (best->tile != 0 && !bwd) {
                     // tile kernel: operand rows + LDS row images of one step's inputs and outputs
                     pl.smem = tile_lds(best->BT, G, num_states(d->cell), d->D, pl.block, pl.DK * 2, 0, 0, 0).total_fwd;
                 }

@@ -81,6 +81,38 @@ __host__ __device__ inline TileLds tile_lds(int BT, int G, int S, int D, int NT,
     return L;
 }
 
+// LDS layout of the backward tile kernel (bf16 I/O, one workgroup per group, BT < 16, NT = 4 * D threads).
+// The input images are filled by loads that write LDS directly: a wave's 64 chunks of 16 bytes land
+// back to back, so these images are plain arrays of chunks (no row padding), each rounded up to whole waves.
+struct TileLdsBwd {
+    uint32_t hp;                 // operand (gate-gradient) row pitch, buf = BT * hp, two buffers
+    uint32_t rp_io;              // row pitch of the output image (bf16 rows)
+    uint32_t red_off;            // partial sums of the contraction slices
+    uint32_t in_off, in_pitch;   // two input images: records | state rows | dh rows
+    uint32_t st_off, dh_off;     // ... offsets of the state rows and the dh rows inside an input image
+    uint32_t out_off, out_pitch; // two output images: BT * GO bf16 rows
+    uint32_t db_off;             // per-row bias-gradient sums: [G][D][BT] f32
+    uint32_t total;
+};
+__host__ __device__ inline uint32_t round_up(uint32_t a, uint32_t b) { return (a + b - 1) / b * b; }
+__host__ __device__ inline TileLdsBwd tile_lds_bwd(int BT, int GO, int NSB, int D, int k_bytes, int EBK) {
+    TileLdsBwd L;
+    const uint32_t NT = 4u * (uint32_t)D, PP = (uint32_t)BT / 4u;
+    L.hp = lds_row_pitch((uint32_t)k_bytes);
+    L.rp_io = lds_row_pitch((uint32_t)D * 2);
+    L.red_off = 2u * BT * L.hp;
+    const uint32_t red_bytes = EBK > 1 ? (NT / 64u) * EBK * 64u * PP * 4u : 0u;
+    L.in_off = L.red_off + red_bytes;
+    L.st_off = (uint32_t)BT * D * 16u;
+    L.dh_off = L.st_off + round_up((uint32_t)BT * NSB * D * 4u, 1024u);
+    L.in_pitch = L.dh_off + round_up((uint32_t)BT * D * 2u, 1024u);
+    L.out_off = L.in_off + 2u * L.in_pitch;
+    L.out_pitch = (uint32_t)BT * GO * L.rp_io;
+    L.db_off = L.out_off + 2u * L.out_pitch;
+    L.total = L.db_off + (uint32_t)(GO > 3 ? 4 : 3) * D * BT * 4u;
+    return L;
+}
+
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -251,6 +283,16 @@ template <bool BF16, int PP> __device__ __forceinline__ void store_io_r(rsrc_t r
         else if constexpr (PP == 2) __builtin_amdgcn_raw_buffer_store_b64(i32x2{__builtin_bit_cast(int, v[0]), __builtin_bit_cast(int, v[1])}, r, voff, soff, 0);
         else __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, v[0]), r, voff, soff, 0);
     }
+}
+
+// 16 bytes per lane from global memory straight into LDS, without passing through registers: lane l's
+// chunk lands at lds + 16 * l (lds is wave-uniform), read from byte offset voff of resource r (out of
+// range: zeros land).  Completion counts in vmcnt like any load.  The host pass only needs the declaration.
+__device__ __forceinline__ void load_chunk_to_lds(rsrc_t r, char* lds, uint32_t voff) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef __attribute__((address_space(3))) char lds_char;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_char*)lds, 16, voff, 0, 0, 0);
+#endif
 }
 
 // one saved-values record (NC values used of kCacheSlots) at byte offset voff + soff of resource r

@@ -16,6 +16,7 @@ struct KernelEntry {
     int multi;  // several workgroups per group
     int maxw;   // launch bound in waves
     int eb;     // blocks of 16 units per wave
+    int tile;   // 0: generic kernel, 1: staged tile kernel (bf16, one workgroup per group, BT < 16)
     const void* fn;
 };
 

@@ -12,24 +12,27 @@
 namespace flashrnn {
 
 #define FRNN_F(KT, KS, BT, MULTI, MAXW, EB) \
-    {FRNN_CELL, FRNN_BF16, 0, KT, KS, BT, MULTI, MAXW, EB, (const void*)&fwd_kernel<FRNN_CELL, (FRNN_BF16 != 0), KT, KS, BT, (MULTI != 0), MAXW, EB>},
+    {FRNN_CELL, FRNN_BF16, 0, KT, KS, BT, MULTI, MAXW, EB, 0, (const void*)&fwd_kernel<FRNN_CELL, (FRNN_BF16 != 0), KT, KS, BT, (MULTI != 0), MAXW, EB>},
 #define FRNN_B(KT, KS, BT, MULTI, MAXW, EB) \
-    {FRNN_CELL, FRNN_BF16, 1, (KT) * FRNN_G, KS, BT, MULTI, MAXW, EB, (const void*)&bwd_kernel<FRNN_CELL, (FRNN_BF16 != 0), (KT) * FRNN_G, KS, BT, (MULTI != 0), MAXW, EB>},
+    {FRNN_CELL, FRNN_BF16, 1, (KT) * FRNN_G, KS, BT, MULTI, MAXW, EB, 0, (const void*)&bwd_kernel<FRNN_CELL, (FRNN_BF16 != 0), (KT) * FRNN_G, KS, BT, (MULTI != 0), MAXW, EB>},
 // forward and backward share the shape list: the backward contraction axis is G times longer
 #define FRNN_FB(KT, KS, BT, MULTI, MAXW) FRNN_F(KT, KS, BT, MULTI, MAXW, 1) FRNN_B(KT, KS, BT, MULTI, MAXW, 1)
 // small batch tiles (bf16, one workgroup per group): forward from the dedicated tile kernel
 #define FRNN_FT(KT, BT, MAXW) \
-    {FRNN_CELL, FRNN_BF16, 0, KT, 1, BT, 0, MAXW, 1, (const void*)&fwd_tile_kernel<FRNN_CELL, KT, BT, MAXW>},
-#define FRNN_TILE(KT, BT, MAXW) FRNN_FT(KT, BT, MAXW) FRNN_B(KT, 1, BT, 0, MAXW, 1)
+    {FRNN_CELL, FRNN_BF16, 0, KT, 1, BT, 0, MAXW, 1, 1, (const void*)&fwd_tile_kernel<FRNN_CELL, KT, BT, MAXW>},
+// ... backward with the contraction split over EBK waves per set of EBK unit blocks
+#define FRNN_BTL(KT, EBK, BT, MAXW) \
+    {FRNN_CELL, FRNN_BF16, 1, (KT) * FRNN_G, 1, BT, 0, MAXW, EBK, 1, (const void*)&bwd_tile_kernel<FRNN_CELL, (KT) * FRNN_G / (EBK), EBK, BT, MAXW>},
+#define FRNN_TILE(KT, EBK, BT, MAXW) FRNN_FT(KT, BT, MAXW) FRNN_B(KT, 1, BT, 0, MAXW, 1) FRNN_BTL(KT, EBK, BT, MAXW)
 // EB blocks of 16 units per wave (fewer, fatter waves: the operand is read from LDS once per wave)
 #define FRNN_FBE(KT, BT, MAXW, EB) FRNN_F(KT, 1, BT, 0, MAXW, EB) FRNN_B(KT, 1, BT, 0, MAXW, EB)
 
 static const KernelEntry kEntries[] = {
 #if FRNN_BF16
-    FRNN_FB(1, 1, 16, 0, 4) FRNN_TILE(1, 8, 4) FRNN_TILE(1, 4, 4)
-    FRNN_FB(2, 1, 16, 0, 4) FRNN_TILE(2, 8, 4) FRNN_TILE(2, 4, 4)
-    FRNN_FB(4, 1, 16, 0, 8) FRNN_TILE(4, 8, 8) FRNN_TILE(4, 4, 8)
-    FRNN_FB(6, 1, 16, 0, 12) FRNN_TILE(6, 8, 12) FRNN_TILE(6, 4, 12)
+    FRNN_FB(1, 1, 16, 0, 4) FRNN_TILE(1, 1, 8, 4) FRNN_TILE(1, 1, 4, 4)
+    FRNN_FB(2, 1, 16, 0, 4) FRNN_TILE(2, 2, 8, 4) FRNN_TILE(2, 2, 4, 4) FRNN_BTL(2, 1, 8, 4) FRNN_BTL(2, 1, 4, 4)
+    FRNN_FB(4, 1, 16, 0, 8) FRNN_TILE(4, 2, 8, 8) FRNN_TILE(4, 2, 4, 8) FRNN_BTL(4, 1, 8, 8) FRNN_BTL(4, 1, 4, 8) FRNN_BTL(4, 4, 8, 8) FRNN_BTL(4, 4, 4, 8)
+    FRNN_FB(6, 1, 16, 0, 12) FRNN_TILE(6, 3, 8, 12) FRNN_TILE(6, 3, 4, 12) FRNN_BTL(6, 1, 8, 12) FRNN_BTL(6, 1, 4, 12)
     FRNN_FBE(4, 16, 4, 2) FRNN_FBE(4, 8, 4, 2) FRNN_FBE(4, 4, 4, 2)
     FRNN_FBE(6, 16, 4, 3) FRNN_FBE(6, 8, 4, 3) FRNN_FBE(6, 4, 4, 3)
     FRNN_FB(2, 1, 16, 1, 4) FRNN_FB(4, 1, 16, 1, 4) FRNN_FB(6, 1, 16, 1, 4) FRNN_FB(1, 4, 16, 1, 4)
@@ -47,6 +50,7 @@ static const KernelEntry kEntries[] = {
 #undef FRNN_FB
 #undef FRNN_FBE
 #undef FRNN_FT
+#undef FRNN_BTL
 #undef FRNN_TILE
 
 }  // namespace flashrnn

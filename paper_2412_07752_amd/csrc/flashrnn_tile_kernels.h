@@ -246,4 +246,301 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
     }
 }
 
+
+// =============================================================================================
+// backward, one block of 16 units per wave, contraction split over EBK waves
+// =============================================================================================
+// A step of the backward pass is the chain
+//     point-wise Jacobians of step t -> dg_t in LDS -> barrier -> MFMA chain R dg_t -> dh_{t-1}.
+// The contraction axis (G * D gate gradients) is G times longer than in the forward pass; if every wave
+// read all of it from LDS, the LDS would bound the step.  Here waves come in sets of EBK: a set owns EBK
+// blocks of units, and each of its waves contracts all of the set's blocks over one of EBK slices of the
+// axis (the same number of MFMAs and R registers per wave, 1/EBK of the operand reads).  The partial sums
+// go through LDS; wave w then runs the point-wise function of block w.
+// Global traffic moves as 16-byte chunks through LDS images, off the chain: the inputs of step t-2 are
+// fetched while step t's MFMAs run, by loads that write their image in LDS directly (no registers are
+// held across the HBM latency), and are read into registers during step t-1's MFMAs; dWx_t leaves
+// during step t's MFMAs.
+template <int CELL, int KTW, int EBK, int BT, int MAXW>
+__global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams p) {
+    using CT = CellTraits<CELL>;
+    using OP = Operand<true>;
+    constexpr int G = CT::G, S = CT::S, NC = CT::NC;
+    constexpr int PP = BT / 4;
+    constexpr int ESZ = 2;
+    constexpr int KT = KTW * EBK, DK = KT * 32;
+    constexpr int NSB = CELL == CELL_SLSTM ? 2 : 1;   // state rows the Jacobian needs per time level ...
+    constexpr int SB0 = CELL == CELL_GRU ? 0 : 1;     // ... starting at this state
+    constexpr int GO = CELL == CELL_GRU ? G + 1 : G;  // output rows per batch row: dWx (+ the recurrent-side candidate gradient)
+    constexpr int NA = EBK == 1 ? 4 : (EBK == 2 ? 2 : 1);   // accumulators per block: independent MFMAs in flight
+    constexpr uint32_t kDrop = 0x80000000u;
+    constexpr uint32_t REC = kCacheSlots * ESZ;
+    static_assert(BT == 4 || BT == 8, "batch tiles of 4 or 8 rows");
+    static_assert(BT * NSB <= 16 && BT * GO <= 32, "one chunk per thread and image");
+
+    extern __shared__ __align__(16) char smem[];
+    const int gid = blockIdx.x;
+    if (gid >= p.NG) return;
+    const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), tid = threadIdx.x;
+    const int tg = w / EBK, ks = w % EBK;
+    const LaneMap<BT> lm(lane);
+    const int T = p.T, B = p.B, NH = p.NH, D = p.D;
+    const int NT = 4 * D;
+    const int n = gid % NH, q = gid / NH;
+    const int e0 = w * 16 + lm.uoff;                 // this lane's units in the point-wise phase: block w
+
+    const uint32_t HD = (uint32_t)NH * D;
+    const size_t wx_step = (size_t)B * G * HD * ESZ, st_step = (size_t)S * B * HD * 4, c_step = (size_t)B * HD * REC;
+    const size_t dh_step = (size_t)B * HD * ESZ;
+    const uint32_t st_state = (uint32_t)B * HD * 4;
+    const TileLdsBwd L = tile_lds_bwd(BT, GO, NSB, D, DK * 2, EBK);
+    const uint32_t BUF = BT * L.hp;
+    char* gbuf = smem;
+    float* red = (float*)(smem + L.red_off);
+    char* in_img = smem + L.in_off;
+    char* out_img = smem + L.out_off;
+
+    // ---- R fragments: blocks tg*EBK + j, contraction slice ks
+    bf16x8 Rf[EBK][KTW];
+#pragma unroll
+    for (int j = 0; j < EBK; ++j) {
+        const size_t rrow = ((size_t)n * D + (tg * EBK + j) * 16 + lm.c) * DK + (size_t)ks * KTW * 32;
+#pragma unroll
+        for (int kt = 0; kt < KTW; ++kt) Rf[j][kt] = *(const bf16x8*)((const uint16_t*)p.R + rrow + kt * 32 + lm.quad * 8);
+    }
+
+    const int bb_raw = q * BT + lm.bslot;
+    const bool row_valid = bb_raw < B;
+    const int bb = row_valid ? bb_raw : B - 1;
+    const char* c_g = (const char*)p.cache + (size_t)n * D * REC;
+    const char* st_g = (const char*)p.states + (size_t)n * D * 4;
+    const char* dh_g = (const char*)p.dH + (size_t)n * D * ESZ;
+    char* dwx_g = (char*)p.dWx + (size_t)n * D * ESZ;
+    char* dgn_g = (char*)p.dgn + (size_t)n * D * ESZ;
+    const uint32_t voff_st = ((uint32_t)bb * HD + e0) * 4;
+
+    // ---- chunk roles: global byte offsets (out of range = nothing to move)
+    uint32_t cc_g[PP], cst_g, cdh_g, cout_g, cout_n, cout_l;
+    bool out_real;
+    const uint32_t cpr_io = (uint32_t)D / 8;
+    const bool st_wave = (uint32_t)w * 64 < (uint32_t)BT * NSB * (D / 4), dh_wave = (uint32_t)w * 64 < (uint32_t)BT * cpr_io;
+    {
+#pragma unroll
+        for (int k2 = 0; k2 < PP; ++k2) {   // records: chunk idx = slot * D + unit
+            const uint32_t idx = tid + k2 * NT, row = idx / (uint32_t)D, u = idx % (uint32_t)D, brow = q * BT + row;
+            cc_g[k2] = brow < (uint32_t)B ? (brow * HD + u) * REC : kDrop;
+        }
+        {   // state rows: row = state * BT + slot
+            const uint32_t cpr_st = (uint32_t)D / 4;
+            const uint32_t row = tid / cpr_st, ch = tid % cpr_st, sidx = row / BT, brow = q * BT + row % BT;
+            cst_g = (row < (uint32_t)BT * NSB && brow < (uint32_t)B) ? (SB0 + sidx) * st_state + (brow * HD) * 4 + ch * 16 : kDrop;
+        }
+        {   // dh rows: row = slot
+            const uint32_t row = tid / cpr_io, ch = tid % cpr_io, brow = q * BT + row;
+            cdh_g = (row < (uint32_t)BT && brow < (uint32_t)B) ? (brow * HD) * ESZ + ch * 16 : kDrop;
+        }
+        {   // output rows: row = slot * GO + g; g < G goes to dWx, g == G to the candidate-gradient buffer
+            const uint32_t row = tid / cpr_io, ch = tid % cpr_io, g = row % GO, brow = q * BT + row / GO;
+            const bool in = row < (uint32_t)BT * GO && brow < (uint32_t)B;
+            cout_g = (in && g < (uint32_t)G) ? ((brow * G + g) * HD) * ESZ + ch * 16 : kDrop;
+            cout_n = (in && g == (uint32_t)G) ? (brow * HD) * ESZ + ch * 16 : kDrop;
+            cout_l = row * L.rp_io + ch * 16;
+            out_real = row < (uint32_t)BT * GO;
+        }
+    }
+    // this lane's places in the images
+    const uint32_t l_c = ((uint32_t)lm.bslot * D + e0) * REC;
+    const uint32_t l_st = L.st_off + ((uint32_t)lm.bslot * D + e0) * 4;
+    const uint32_t l_dh = L.dh_off + ((uint32_t)lm.bslot * D + e0) * ESZ;
+    const uint32_t l_out = (uint32_t)lm.bslot * GO * L.rp_io + e0 * ESZ;
+    const uint32_t lds_row = (uint32_t)lm.bslot * L.hp;
+
+    // carried state gradients; ds[0] is the part of dh_t that came through R and the direct path
+    float ds[S][PP];
+    float* dbs = (float*)(smem + L.db_off) + (size_t)e0 * BT + lm.bslot;   // this lane's bias-gradient sums: [g][unit][slot]
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+        if (p.dlast != nullptr && !(CELL == CELL_SLSTM && s == 3))
+            load_io_r<false, PP>(make_rsrc((const char*)p.dlast + (size_t)n * D * 4), voff_st, s * st_state, ds[s]);
+        else
+#pragma unroll
+            for (int i = 0; i < PP; ++i) ds[s][i] = 0.0f;
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int i = 0; i < PP; ++i) dbs[((size_t)g * D + i) * BT] = 0.0f;
+
+    for (uint32_t j = tid; j < 2 * BUF / 4; j += NT) ((uint32_t*)gbuf)[j] = 0u;
+
+    // the image of the inputs of step j: global -> LDS (each wave's 64 chunks back to back), LDS -> this lane's values
+    auto fetch = [&](int j) {
+        j = __builtin_amdgcn_readfirstlane(j);   // keeps the clamped time index (a saturating subtract) on the scalar unit
+        const rsrc_t rc = make_rsrc(c_g + (size_t)(j - 1) * c_step), rst = make_rsrc(st_g + (size_t)(j - 1) * st_step),
+                     rdh = make_rsrc(dh_g + (size_t)(j - 1) * dh_step);
+        char* img = in_img + (j & 1) * L.in_pitch + (uint32_t)w * 1024;
+#pragma unroll
+        for (int k2 = 0; k2 < PP; ++k2) load_chunk_to_lds(rc, img + (uint32_t)k2 * NT * 16, cc_g[k2]);
+        if (st_wave) load_chunk_to_lds(rst, img + L.st_off, cst_g);
+        if (dh_wave) load_chunk_to_lds(rdh, img + L.dh_off, cdh_g);
+    };
+    float cv[NC][PP], sc[S][PP], sp[S][PP], dh_ext[PP];
+    auto take = [&](int j) {
+        const char* img = in_img + (j & 1) * L.in_pitch;
+#pragma unroll
+        for (int i = 0; i < PP; ++i) {
+            float rec[NC];
+            const i32x4 r = *(const i32x4*)(img + l_c + i * REC);
+            unpack_record<true, NC>(r, r, rec);
+#pragma unroll
+            for (int c2 = 0; c2 < NC; ++c2) cv[c2][i] = rec[c2];
+        }
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            if (s >= SB0 && s < SB0 + NSB) load_io<false, PP>(img + l_st + (uint32_t)(s - SB0) * BT * D * 4, 0, sp[s]);
+            else
+#pragma unroll
+                for (int i = 0; i < PP; ++i) sp[s][i] = 1.0f;
+        }
+        load_io<true, PP>(img + l_dh, 0, dh_ext);
+    };
+
+    // ---- prologue: images of steps T and T-1, this lane's inputs of step T, the states after step T
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+        if (CELL != CELL_GRU && s >= SB0 && s < SB0 + NSB && T > 0)
+            load_io_r<false, PP>(make_rsrc(st_g + (size_t)T * st_step), voff_st, s * st_state, sc[s]);
+        else
+#pragma unroll
+            for (int i = 0; i < PP; ++i) sc[s][i] = 1.0f;
+    }
+    if (T > 0) {
+        fetch(T);
+        if (T > 1) fetch(T - 1);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    __syncthreads();
+    if (T > 0) take(T);
+
+    for (int t = T; t >= 1; --t) {
+        // ---- point-wise Jacobians of step t
+        {
+            float dwx[G][PP], dg[G][PP];
+#pragma unroll
+            for (int i = 0; i < PP; ++i) {
+                float cvi[NC], sci[S], spi[S], dsi[S], dwxi[G], dgi[G];
+#pragma unroll
+                for (int c2 = 0; c2 < NC; ++c2) cvi[c2] = cv[c2][i];
+#pragma unroll
+                for (int s = 0; s < S; ++s) { sci[s] = sc[s][i]; spi[s] = sp[s][i]; dsi[s] = ds[s][i]; }
+                dsi[0] += dh_ext[i];
+                Cell<CELL, true>::bwd(cvi, sci, spi, dsi, dwxi, dgi);
+#pragma unroll
+                for (int s = 0; s < S; ++s) ds[s][i] = dsi[s];
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    dwx[g][i] = dwxi[g];
+                    dg[g][i] = dgi[g];
+                    // db sums live in LDS (each lane owns its slots): registers are what this kernel is short of
+                    dbs[((size_t)g * D + i) * BT] += dgi[g];
+                }
+            }
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                write_operand_lds<true, PP>(gbuf + (t & 1) * BUF + lds_row, g * D + e0, dg[g]);
+                store_io<true, PP>(out_img + (t & 1) * L.out_pitch + l_out + (uint32_t)g * L.rp_io, 0, dwx[g]);
+            }
+            if constexpr (CELL == CELL_GRU) store_io<true, PP>(out_img + (t & 1) * L.out_pitch + l_out + (uint32_t)G * L.rp_io, 0, dg[2]);
+            if constexpr (CELL != CELL_GRU) {
+#pragma unroll
+                for (int s = SB0; s < SB0 + NSB; ++s)
+#pragma unroll
+                    for (int i = 0; i < PP; ++i) sc[s][i] = sp[s][i];
+            }
+        }
+        // the chunks fetched during the previous step are in LDS once only that step's stores are younger;
+        // they are read after this barrier
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(CELL == CELL_GRU ? 2 : 1) : "memory");
+        __syncthreads();
+        // ---- dh_{t-1} += R dg_t; in the shadow of the chain: fetch step t-2, dWx_t out, step t-1's values
+        // The operand is read in chunks of KC k-steps, one chunk ahead of the MFMAs that use it.
+        constexpr int KC = 4, NCK = (KTW + KC - 1) / KC;
+        bf16x8 gB[NCK][KC];
+        const char* grow = gbuf + (t & 1) * BUF + lds_row + (size_t)(ks * KTW * 32 + lm.quad * 8) * 2;
+        auto read_chunk = [&](int c) {
+#pragma unroll
+            for (int k = 0; k < KC; ++k)
+                if (c * KC + k < KTW) gB[c][k] = *(const bf16x8*)(grow + (size_t)(c * KC + k) * 64);
+        };
+        read_chunk(0);
+        if (t > 2) fetch(t - 2);
+        pin_order();
+        f32x4 acc[EBK][NA];
+#pragma unroll
+        for (int j = 0; j < EBK; ++j)
+#pragma unroll
+            for (int a = 0; a < NA; ++a) acc[j][a] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < NCK; ++c) {
+#pragma unroll
+            for (int k = 0; k < KC; ++k)
+                if (c * KC + k < KTW) {
+#pragma unroll
+                    for (int j = 0; j < EBK; ++j) acc[j][(c * KC + k) % NA] = OP::mfma(Rf[j][c * KC + k], gB[c][k], acc[j][(c * KC + k) % NA]);
+                }
+            pin_order();
+            if (c + 1 < NCK) read_chunk(c + 1);
+            if (c == 0) {   // dWx_t out of its image and on its way, step t-1's values out of theirs
+                i32x4 o = i32x4{0, 0, 0, 0};
+                if (out_real) o = *(const i32x4*)(out_img + (t & 1) * L.out_pitch + cout_l);
+                if (t > 1) take(t - 1);
+                pin_order();
+                __builtin_amdgcn_raw_buffer_store_b128(o, make_rsrc(dwx_g + (size_t)(t - 1) * wx_step), cout_g, 0, 0);
+                if constexpr (CELL == CELL_GRU)
+                    __builtin_amdgcn_raw_buffer_store_b128(o, make_rsrc(dgn_g + (size_t)(t - 1) * dh_step), cout_n, 0, 0);
+            }
+            pin_order();
+        }
+        float part[EBK][PP];
+#pragma unroll
+        for (int j = 0; j < EBK; ++j) {
+            f32x4 a = acc[j][0];
+#pragma unroll
+            for (int x = 1; x < NA; ++x) a += acc[j][x];
+            compact_tile<BT>(a);
+#pragma unroll
+            for (int i = 0; i < PP; ++i) part[j][i] = a[i];
+        }
+        if constexpr (EBK > 1) {
+#pragma unroll
+            for (int j = 0; j < EBK; ++j)   // partial sum of block tg*EBK + j from slice ks
+                store_io<false, PP>(red, ((size_t)((tg * EBK + j) * EBK + ks) * 64 + lane) * PP, part[j]);
+            __syncthreads();
+#pragma unroll
+            for (int x = 0; x < EBK; ++x) {
+                float v[PP];
+                load_io<false, PP>(red, ((size_t)(w * EBK + x) * 64 + lane) * PP, v);
+#pragma unroll
+                for (int i = 0; i < PP; ++i) ds[0][i] += v[i];
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < PP; ++i) ds[0][i] += part[0][i];
+        }
+    }
+    // ---- gradients w.r.t. the initial states, per-row partial sums of db
+    if (row_valid) {
+#pragma unroll
+        for (int s = 0; s < S; ++s)
+            store_io_r<false, PP>(make_rsrc((char*)p.dstates0 + (size_t)n * D * 4), voff_st, s * st_state, ds[s]);
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            float dbv[PP];
+#pragma unroll
+            for (int i = 0; i < PP; ++i) dbv[i] = dbs[((size_t)g * D + i) * BT];
+            store_f32<PP>(p.db_part, (((size_t)bb * NH + n) * G + g) * D + e0, dbv);
+        }
+    }
+}
+
 }  // namespace flashrnn
