@@ -6,6 +6,10 @@ configuration the headline metric is quoted on (sLSTM, B=16, T=256, NH=4, D=192,
 states).  Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload IDX] [--no-cpu-baseline]
+    python bench.py --copy-calibration     # a plain copy of known size, for scaling rocprofv3's HBM counters
+
+roofline.traffic is the measured HBM traffic per launch of the dominant kernel, taken from the summary
+of the two rocprofv3 --pmc runs under profiles/ (hbm_traffic_<workload>.txt) when that file is there.
 """
 import argparse
 import json
@@ -29,6 +33,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=25)
     ap.add_argument("--workload", type=int, default=1, help="index into the benchmark configurations (default 1: the headline one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a plain elementwise copy of 256 MiB (reads 256 MiB, writes 256 MiB) five times and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the time loop never crosses GPUs); use --gpus 1", file=sys.stderr)
@@ -42,6 +48,15 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        n = 64 * 1024 * 1024
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": True, "bytes_read": 4 * n, "bytes_written": 4 * n, "launches": 5}))
+        return
     w = synth.CONFIGS[args.workload]
     bf16 = w.dtype == "bf16"
     inp = synth.make_inputs(w)
@@ -105,9 +120,16 @@ def main():
         bytes_launch = B * T * H * (nc * esz + esz + G * esz) + B * T * H * 4 * (2 if w.cell != synth.CELL_GRU else 1) * (2 if w.cell == synth.CELL_SLSTM else 1)
     else:         # reads Wx; writes states and saved values
         bytes_launch = B * T * H * (G * esz + S * 4 + (nc * esz if w.backward else 0))
+    traffic = None   # measured HBM bytes per launch of the dominant kernel (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled)
+    tf = os.path.join(ROOT, "profiles", f"hbm_traffic_{w.name}.txt")
+    if os.path.exists(tf):
+        for ln in open(tf):
+            key = "bwd_bytes_per_launch:" if dom_bwd else "fwd_bytes_per_launch:"
+            if ln.startswith(key):
+                traffic = float(ln.split(":")[1])
     roofline = {
         "bound": "mfma", "kernel": ("bwd_kernel" if dom_bwd else "fwd_kernel"), "achieved": round(achieved, 4), "peak": peak,
-        "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
+        "unit": "TFLOP/s", "frac": achieved / peak, "traffic": traffic,
         "launch_ms": round(dom_ms, 5), "launches_timed": nb if dom_bwd else nf,
         "flops_per_launch": flops_launch,
         "workgroups": wgs, "frac_of_occupied_cus": achieved / (peak * wgs / DEVICE_CUS),
