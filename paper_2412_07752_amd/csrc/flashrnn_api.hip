@@ -307,8 +307,9 @@ int flashrnn_fwd(const flashrnn_desc_t* d, const void* Wx, const void* R, const 
     hipStream_t stream = (hipStream_t)hip_stream;
     char* ws = (char*)workspace;
     const int G = num_gates(d->cell);
-    if (launch_fill_zero(ws + w.err_off, kAlign + align_up(pf.exch_bytes), stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
-    if (launch_pack_r(d->io_dtype == FLASHRNN_BF16, false, R, ws + w.rpack_off, d->NH, d->D, G, pf.DK, stream) != hipSuccess)
+    // the exchange words start from zero stamps; the error word is cleared by the packing kernel
+    if (pf.exch_bytes && launch_fill_zero(ws + w.exch_off, align_up(pf.exch_bytes), stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
+    if (launch_pack_r(d->io_dtype == FLASHRNN_BF16, false, R, ws + w.rpack_off, d->NH, d->D, G, pf.DK, (int*)(ws + w.err_off), stream) != hipSuccess)
         return FLASHRNN_ERR_LAUNCH;
     KernelParams kp;
     memset(&kp, 0, sizeof(kp));
@@ -339,8 +340,8 @@ int flashrnn_bwd(const flashrnn_desc_t* d, const void* R, const void* b, const v
     char* ws = (char*)workspace;
     const int G = num_gates(d->cell), S = num_states(d->cell);
     const bool bf = d->io_dtype == FLASHRNN_BF16;
-    if (launch_fill_zero(ws + w.err_off, kAlign + align_up(pb.exch_bytes), stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
-    if (launch_pack_r(bf, true, R, ws + w.rpack_off, d->NH, d->D, G, pb.DK, stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
+    if (pb.exch_bytes && launch_fill_zero(ws + w.exch_off, align_up(pb.exch_bytes), stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
+    if (launch_pack_r(bf, true, R, ws + w.rpack_off, d->NH, d->D, G, pb.DK, (int*)(ws + w.err_off), stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
     KernelParams kp;
     memset(&kp, 0, sizeof(kp));
     kp.R = ws + w.rpack_off; kp.states = (float*)const_cast<void*>(states); kp.cache = const_cast<void*>(gate_cache);
@@ -353,13 +354,13 @@ int flashrnn_bwd(const flashrnn_desc_t* d, const void* R, const void* b, const v
     if (rc != FLASHRNN_OK) return rc;
     // db: sum of the per-row partial sums in row order; dR: GEMM over (t, b)
     const size_t nb = (size_t)d->NH * G * d->D;
-    if (launch_sum_slices((const float*)(ws + w.dbpart_off), (float*)db, nb, d->B, nb, stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
     if (d->T == 0) {
+        if (launch_sum_slices((const float*)(ws + w.dbpart_off), (float*)db, nb, d->B, nb, stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
         if (launch_fill_zero(dR, (size_t)d->NH * d->D * G * d->D * 4, stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
         return FLASHRNN_OK;
     }
     if (launch_dr_gemm(bf, (const float*)states, dWx, ws + w.dgn_off, (float*)(ws + w.drpart_off), (float*)dR, d->T, d->B, d->NH, d->D,
-                       G, S, d->cell == FLASHRNN_GRU, stream) != hipSuccess)
+                       G, S, d->cell == FLASHRNN_GRU, (const float*)(ws + w.dbpart_off), (float*)db, stream) != hipSuccess)
         return FLASHRNN_ERR_LAUNCH;
     return FLASHRNN_OK;
 }

@@ -35,9 +35,9 @@ KernelTable table_slstm_f32();
 
 int dr_split_k(int T, int B, int NH, int D, int G);
 hipError_t launch_dr_gemm(bool bf16, const float* states, const void* dWx, const void* dgn, float* part, float* dR, int T, int B,
-                          int NH, int D, int G, int S, bool gru, hipStream_t stream);
+                          int NH, int D, int G, int S, bool gru, const float* db_part, float* db, hipStream_t stream);
 hipError_t launch_sum_slices(const float* part, float* out, size_t count, int NS, size_t stride, hipStream_t stream);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t stream);
-hipError_t launch_pack_r(bool bf16, bool bwd, const void* R, void* out, int NH, int D, int G, int DK, hipStream_t stream);
+hipError_t launch_pack_r(bool bf16, bool bwd, const void* R, void* out, int NH, int D, int G, int DK, int* err, hipStream_t stream);
 
 }  // namespace flashrnn

@@ -24,11 +24,14 @@ __global__ __launch_bounds__(256) void dr_gemm_kernel(const float* __restrict__ 
     __shared__ __align__(16) char ldsB[TN * PITCH * ESZ];
     const int GD = G * D;
     const int tiles_n = (GD + TN - 1) / TN, tiles_m = (D + TM - 1) / TM;
-    int bid = blockIdx.x;
-    const int tn = bid % tiles_n; bid /= tiles_n;
-    const int tm = bid % tiles_m; bid /= tiles_m;
-    const int sk = bid % SK;
-    const int n = bid / SK;
+    // Workgroup i runs on XCD i % 8.  All tiles of one (head, K slice) share their operand rows, so they
+    // get block indices that are equal modulo 8 and re-read those rows from one L2.
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, tiles = tiles_n * tiles_m;
+    const int combo = (slot / tiles) * 8 + xcd, tile = slot % tiles;
+    if (combo >= SK * NH) return;
+    const int tn = tile % tiles_n, tm = tile / tiles_n;
+    const int sk = combo % SK;
+    const int n = combo / SK;
     const int K = T * B;
     const int kchunk = ((K + SK - 1) / SK + TK - 1) / TK * TK;
     const int kbeg = sk * kchunk, kend = min(K, kbeg + kchunk);
@@ -51,50 +54,63 @@ __global__ __launch_bounds__(256) void dr_gemm_kernel(const float* __restrict__ 
     const int bg = b_ok ? j_glob / D : 0, be = b_ok ? j_glob % D : 0;
     const bool b_from_dgn = gru && bg == 2;
 
-    for (int kb = kbeg; kb < kend; kb += TK) {
-        // ---- global loads (rows k = (tt, b)): A row = h_{tt}, tt = 0..T-1 is the state before step tt+1
-        float av[2][4];
-        float bv[2][8];
+    // Raw tile rows in registers (unconditional loads from clamped addresses, zeroed when they are used),
+    // so that the loads of round i+1 are in flight while round i's tiles go through LDS and the matrix cores.
+    constexpr int BW = BF16 ? 1 : 2;   // 16-byte words of a B row segment of 8 elements
+    const char* b_base = (const char*)(b_from_dgn ? dgn : dWx);
+    const size_t b_row = b_from_dgn ? (size_t)NH * D : (size_t)G * NH * D;
+    const size_t b_off = b_from_dgn ? (size_t)n * D + be : ((size_t)bg * NH + n) * D + be;
+    f32x4 ra[2];
+    i32x4 rb[2][BW];
+    bool oka[2], okb[2];
+    auto load_tiles = [&](int kb) __attribute__((always_inline)) {
+        // rows k = (tt, b): A row = h_{tt}, tt = 0..T-1 is the state before step tt+1
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
             const int k = kb + a_kp * 2 + r;
-            if (a_ok && k < kend) {
-                const int tt = k / B, b = k % B;
-                load_f32<4>(states, ((((size_t)tt * S + 0) * B + b) * NH + n) * D + d_glob, av[r]);
-            } else {
-                av[r][0] = av[r][1] = av[r][2] = av[r][3] = 0.f;
-            }
-            const int k2 = kb + b_kp * 2 + r;
-            if (b_ok && k2 < kend) {
-                const int tt = k2 / B, b = k2 % B;
-                const size_t idx = b_from_dgn ? (((size_t)tt * B + b) * NH + n) * D + be
-                                              : ((((size_t)tt * B + b) * G + bg) * NH + n) * D + be;
-                const void* src = b_from_dgn ? dgn : dWx;
-                float lo[4], hi[4];
-                load_io<BF16, 4>(src, idx, lo);
-                load_io<BF16, 4>(src, idx + 4, hi);
+            const int tt = k / B, b = k % B;
+            oka[r] = a_ok && k < kend;
+            okb[r] = b_ok && k < kend;
+            ra[r] = *(const f32x4*)(states + (oka[r] ? ((((size_t)tt * S + 0) * B + b) * NH + n) * D + d_glob : 0));
+            const char* src = b_base + (okb[r] ? (size_t)k * b_row + b_off : 0) * ESZ;   // row k = (tt, b) of dWx or of the candidate-gradient buffer
 #pragma unroll
-                for (int i = 0; i < 4; ++i) { bv[r][i] = lo[i]; bv[r][4 + i] = hi[i]; }
-            } else {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) bv[r][i] = 0.f;
-            }
+            for (int x = 0; x < BW; ++x) rb[r][x] = *(const i32x4*)(src + 16 * x);
         }
+    };
+    load_tiles(kbeg);
+    for (int kb = kbeg; kb < kend; kb += TK) {
         __syncthreads();  // previous round's reads are done
-        if constexpr (BF16) {
+        {
+            f32x4 a0 = ra[0], a1 = ra[1];
+            if (!oka[0]) a0 = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (!oka[1]) a1 = f32x4{0.f, 0.f, 0.f, 0.f};
+            i32x4 b0[BW], b1[BW];
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                *(uint32_t*)(ldsA + ((a_d + i) * PITCH + a_kp * 2) * 2) = pack_bf16x2(av[0][i], av[1][i]);
+            for (int x = 0; x < BW; ++x) {
+                b0[x] = okb[0] ? rb[0][x] : i32x4{0, 0, 0, 0};
+                b1[x] = okb[1] ? rb[1][x] : i32x4{0, 0, 0, 0};
+            }
+            if constexpr (BF16) {   // pairs along k: low half from row 2*kp, high half from row 2*kp + 1
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
-                *(uint32_t*)(ldsB + ((b_j + i) * PITCH + b_kp * 2) * 2) = pack_bf16x2(bv[0][i], bv[1][i]);
-        } else {
+                for (int i = 0; i < 4; ++i) *(uint32_t*)(ldsA + ((a_d + i) * PITCH + a_kp * 2) * 2) = pack_bf16x2(a0[i], a1[i]);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) *(float2*)(ldsA + ((a_d + i) * PITCH + a_kp * 2) * 4) = make_float2(av[0][i], av[1][i]);
+                for (int i = 0; i < 8; ++i) {
+                    const uint32_t x0 = (uint32_t)b0[0][i >> 1], x1 = (uint32_t)b1[0][i >> 1];
+                    const uint32_t v = (i & 1) ? ((x1 & 0xFFFF0000u) | (x0 >> 16)) : ((x1 << 16) | (x0 & 0xFFFFu));
+                    *(uint32_t*)(ldsB + ((b_j + i) * PITCH + b_kp * 2) * 2) = v;
+                }
+            } else {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) *(float2*)(ldsB + ((b_j + i) * PITCH + b_kp * 2) * 4) = make_float2(bv[0][i], bv[1][i]);
+                for (int i = 0; i < 4; ++i) *(float2*)(ldsA + ((a_d + i) * PITCH + a_kp * 2) * 4) = make_float2(a0[i], a1[i]);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const f32x4 y0 = __builtin_bit_cast(f32x4, b0[i >> 2]), y1 = __builtin_bit_cast(f32x4, b1[i >> 2]);
+                    *(float2*)(ldsB + ((b_j + i) * PITCH + b_kp * 2) * 4) = make_float2(y0[i & 3], y1[i & 3]);
+                }
+            }
         }
         __syncthreads();
+        if (kb + TK < kend) load_tiles(kb + TK);
         if constexpr (BF16) {
             bf16x8 af[2], bf[4];
 #pragma unroll
@@ -144,6 +160,24 @@ __global__ void sum_slices_kernel(const float* __restrict__ part, float* __restr
     out[j] = a;
 }
 
+// the two reductions that end the backward pass, in one launch: elements [0, count1) and [count1, count1 + count2)
+__global__ void sum_slices2_kernel(const float* __restrict__ part1, float* __restrict__ out1, size_t count1, int NS1, size_t stride1,
+                                   const float* __restrict__ part2, float* __restrict__ out2, size_t count2, int NS2, size_t stride2) {
+    size_t j = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const float* part = part1;
+    float* out = out1;
+    int NS = NS1;
+    size_t stride = stride1;
+    if (j >= count1) {
+        j -= count1;
+        if (j >= count2) return;
+        part = part2; out = out2; NS = NS2; stride = stride2;
+    }
+    float a = 0.f;
+    for (int s = 0; s < NS; ++s) a += part[(size_t)s * stride + j];
+    out[j] = a;
+}
+
 __global__ void fill_zero_kernel(uint32_t* __restrict__ p, size_t count) {
     const size_t j = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (j < count) p[j] = 0u;
@@ -152,9 +186,11 @@ __global__ void fill_zero_kernel(uint32_t* __restrict__ p, size_t count) {
 // Packed copies of R for the persistent kernels (made once per call, R is read once per launch):
 //   forward   Rt[n][g][e][k] = R[n][k][g][e]   (k = previous-state index, padded with zeros to DK)
 //   backward  Rb[n][d][k]    = R[n][d][k]       (k = gate * D + unit,    padded with zeros to DK)
+// The same launch clears the error word of the persistent kernel that follows.
 template <typename T>
-__global__ void pack_r_fwd_kernel(const T* __restrict__ R, T* __restrict__ out, int NH, int D, int G, int DK) {
+__global__ void pack_r_fwd_kernel(const T* __restrict__ R, T* __restrict__ out, int NH, int D, int G, int DK, int* __restrict__ err) {
     const size_t j = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j == 0) *err = 0;
     const size_t total = (size_t)NH * G * D * DK;
     if (j >= total) return;
     const int k = (int)(j % DK);
@@ -165,8 +201,9 @@ __global__ void pack_r_fwd_kernel(const T* __restrict__ R, T* __restrict__ out, 
     out[j] = k < D ? R[(((size_t)n * D + k) * G + g) * D + e] : T(0);
 }
 template <typename T>
-__global__ void pack_r_bwd_kernel(const T* __restrict__ R, T* __restrict__ out, int NH, int D, int G, int DK) {
+__global__ void pack_r_bwd_kernel(const T* __restrict__ R, T* __restrict__ out, int NH, int D, int G, int DK, int* __restrict__ err) {
     const size_t j = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (j == 0) *err = 0;
     const size_t total = (size_t)NH * D * DK;
     if (j >= total) return;
     const int k = (int)(j % DK);
@@ -174,15 +211,15 @@ __global__ void pack_r_bwd_kernel(const T* __restrict__ R, T* __restrict__ out, 
     out[j] = k < G * D ? R[row * (size_t)(G * D) + k] : T(0);
 }
 
-hipError_t launch_pack_r(bool bf16, bool bwd, const void* R, void* out, int NH, int D, int G, int DK, hipStream_t stream) {
+hipError_t launch_pack_r(bool bf16, bool bwd, const void* R, void* out, int NH, int D, int G, int DK, int* err, hipStream_t stream) {
     const size_t total = bwd ? (size_t)NH * D * DK : (size_t)NH * G * D * DK;
     const dim3 grid((unsigned)((total + 255) / 256)), block(256);
     if (bf16) {
-        if (bwd) hipLaunchKernelGGL(pack_r_bwd_kernel<uint16_t>, grid, block, 0, stream, (const uint16_t*)R, (uint16_t*)out, NH, D, G, DK);
-        else hipLaunchKernelGGL(pack_r_fwd_kernel<uint16_t>, grid, block, 0, stream, (const uint16_t*)R, (uint16_t*)out, NH, D, G, DK);
+        if (bwd) hipLaunchKernelGGL(pack_r_bwd_kernel<uint16_t>, grid, block, 0, stream, (const uint16_t*)R, (uint16_t*)out, NH, D, G, DK, err);
+        else hipLaunchKernelGGL(pack_r_fwd_kernel<uint16_t>, grid, block, 0, stream, (const uint16_t*)R, (uint16_t*)out, NH, D, G, DK, err);
     } else {
-        if (bwd) hipLaunchKernelGGL(pack_r_bwd_kernel<float>, grid, block, 0, stream, (const float*)R, (float*)out, NH, D, G, DK);
-        else hipLaunchKernelGGL(pack_r_fwd_kernel<float>, grid, block, 0, stream, (const float*)R, (float*)out, NH, D, G, DK);
+        if (bwd) hipLaunchKernelGGL(pack_r_bwd_kernel<float>, grid, block, 0, stream, (const float*)R, (float*)out, NH, D, G, DK, err);
+        else hipLaunchKernelGGL(pack_r_fwd_kernel<float>, grid, block, 0, stream, (const float*)R, (float*)out, NH, D, G, DK, err);
     }
     return hipGetLastError();
 }
@@ -196,20 +233,20 @@ int dr_split_k(int T, int B, int NH, int D, int G) {
 }
 
 hipError_t launch_dr_gemm(bool bf16, const float* states, const void* dWx, const void* dgn, float* part, float* dR, int T, int B,
-                          int NH, int D, int G, int S, bool gru, hipStream_t stream) {
+                          int NH, int D, int G, int S, bool gru, const float* db_part, float* db, hipStream_t stream) {
     const int SK = dr_split_k(T, B, NH, D, G);
     const int GD = G * D;
-    const int grid = NH * SK * ((D + TM - 1) / TM) * ((GD + TN - 1) / TN);
+    const int grid = (NH * SK + 7) / 8 * 8 * ((D + TM - 1) / TM) * ((GD + TN - 1) / TN);   // (head, K slice) padded to the 8 XCDs
     float* target = SK == 1 ? dR : part;
     if (bf16) hipLaunchKernelGGL(dr_gemm_kernel<true>, dim3(grid), dim3(256), 0, stream, states, dWx, dgn, target, T, B, NH, D, G, S, SK, gru ? 1 : 0);
     else hipLaunchKernelGGL(dr_gemm_kernel<false>, dim3(grid), dim3(256), 0, stream, states, dWx, dgn, target, T, B, NH, D, G, S, SK, gru ? 1 : 0);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (SK > 1) {
-        const size_t count = (size_t)NH * D * GD;
-        hipLaunchKernelGGL(sum_slices_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, stream, part, dR, count, SK, count);
-        e = hipGetLastError();
-    }
+    // split-K partial sums of dR (if any) and the per-row partial sums of db, each added in index order
+    const size_t count = SK > 1 ? (size_t)NH * D * GD : 0, nb = (size_t)NH * GD;
+    hipLaunchKernelGGL(sum_slices2_kernel, dim3((unsigned)((count + nb + 255) / 256)), dim3(256), 0, stream, part, dR, count, SK, (size_t)NH * D * GD,
+                       db_part, db, nb, B, nb);
+    e = hipGetLastError();
     return e;
 }
 
