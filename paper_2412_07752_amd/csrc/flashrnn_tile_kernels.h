@@ -77,7 +77,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
     const uint32_t voff_st = ((uint32_t)bb * HD + e0) * 4;
 
     // ---- chunk roles: global byte offset (out of range = nothing to move) and LDS offset inside the image
-    uint32_t cin_g[NCH_IN], cin_l[NCH_IN], cst_g[NCH_ST], cst_l[NCH_ST], cc_g[NCH_C];
+    uint32_t cin_g[NCH_IN], cin_l[NCH_IN], cst_g[NCH_ST], cst_l[NCH_ST], cc_g[NCH_C], cc_l[NCH_C];
     {
         const uint32_t cpr_io = (uint32_t)D / 8, cpr_st = (uint32_t)D / 4;
 #pragma unroll
@@ -95,15 +95,16 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
             cst_l[k2] = in ? row * L.rp_st + ch * 16 : L.st_bytes + tid16 + k2 * NT16;
         }
 #pragma unroll
-        for (int k2 = 0; k2 < NCH_C; ++k2) {  // records: chunk idx = slot * D + unit, LDS offset idx * 16
+        for (int k2 = 0; k2 < NCH_C; ++k2) {  // records: chunk idx = slot * D + unit
             const uint32_t idx = tid + k2 * NT, row = idx / (uint32_t)D, u = idx % (uint32_t)D, brow = q * BT + row;
             cc_g[k2] = (row < (uint32_t)BT && brow < (uint32_t)B && p.cache != nullptr) ? (brow * HD + u) * REC : kDrop;
+            cc_l[k2] = L.st_pitch + row * L.rec_pitch + u * REC;
         }
     }
-    // this lane's places: inputs row = slot*G + g, states row = s*BT + slot, records slot*D + unit
+    // this lane's places: inputs row = slot*G + g, states row = s*BT + slot, records row = slot
     const uint32_t l_in = (uint32_t)lm.bslot * G * L.rp_io + e0 * ESZ;
     const uint32_t l_st = (uint32_t)lm.bslot * L.rp_st + e0 * 4;
-    const uint32_t l_c = L.st_pitch + ((uint32_t)lm.bslot * D + e0) * REC;
+    const uint32_t l_c = L.st_pitch + (uint32_t)lm.bslot * L.rec_pitch + e0 * REC;
     const uint32_t lds_row = (uint32_t)lm.bslot * L.hp;
 
     // ---- initial states: slot 0 is written directly (once)
@@ -126,19 +127,13 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
     }
     __syncthreads();
 
-    float cvs[NC][PP];
-#pragma unroll
-    for (int c2 = 0; c2 < NC; ++c2)
-#pragma unroll
-        for (int i = 0; i < PP; ++i) cvs[c2][i] = 0.0f;
-
     // move the image of the outputs of step j to HBM: states slot j, saved values slot j - 1
     auto copy_out_load = [&](int j, i32x4 (&vs)[NCH_ST], i32x4 (&vc)[NCH_C]) {
         const char* img = out_img + (j & 1) * OUT_PITCH;
 #pragma unroll
         for (int k2 = 0; k2 < NCH_ST; ++k2) vs[k2] = *(const i32x4*)(img + cst_l[k2]);
 #pragma unroll
-        for (int k2 = 0; k2 < NCH_C; ++k2) vc[k2] = *(const i32x4*)(img + L.st_pitch + tid16 + k2 * NT16);
+        for (int k2 = 0; k2 < NCH_C; ++k2) vc[k2] = *(const i32x4*)(img + cc_l[k2]);
     };
     auto copy_out_store = [&](int j, const i32x4 (&vs)[NCH_ST], const i32x4 (&vc)[NCH_C]) {
         const uint32_t none = j < 1 ? kDrop : 0u;
@@ -149,20 +144,6 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
 #pragma unroll
         for (int k2 = 0; k2 < NCH_C; ++k2) __builtin_amdgcn_raw_buffer_store_b128(vc[k2], rs_c, cc_g[k2] | none, 0, 0);
     };
-    auto write_image = [&](int j) {  // outputs of step j (current st, cvs) into their image
-        char* img = out_img + (j & 1) * OUT_PITCH;
-#pragma unroll
-        for (int s = 0; s < S; ++s) store_io<false, PP>(img + l_st + (uint32_t)s * BT * L.rp_st, 0, st[s]);
-#pragma unroll
-        for (int i = 0; i < PP; ++i) {
-            float wv[kCacheSlots];
-#pragma unroll
-            for (int c2 = 0; c2 < kCacheSlots; ++c2) wv[c2] = c2 < NC ? cvs[c2 < NC ? c2 : 0][i] : 0.0f;
-            *(i32x4*)(img + l_c + i * REC) = i32x4{(int)pack_bf16x2(wv[0], wv[1]), (int)pack_bf16x2(wv[2], wv[3]),
-                                                   (int)pack_bf16x2(wv[4], wv[5]), (int)pack_bf16x2(wv[6], wv[7])};
-        }
-    };
-
     for (int t = 1; t <= T; ++t) {
         // The MFMA chain of the step, k-step by k-step, with the work that is off the dependency chain
         // issued in between (the sched barriers keep the compiler from bunching it up in front).
@@ -182,7 +163,6 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
 #pragma unroll
         for (int g = 0; g < G; ++g) acc[g] = OP::mfma(Rf[g][0], hB[0], f32x4{0.f, 0.f, 0.f, 0.f});
         pin_order();
-        write_image(t - 1);                    // outputs of step t-1 into their image
 #pragma unroll
         for (int kt = H1; kt < KT; ++kt) hB[kt] = *(const bf16x8*)(hrow + (size_t)(kt * 32 + lm.quad * 8) * 2);
         pin_order();
@@ -191,7 +171,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
             for (int g = 0; g < G; ++g) acc[g] = OP::mfma(Rf[g][1], hB[1], acc[g]);
         }
         pin_order();
-        copy_out_load(t - 2, vs, vc);          // outputs of step t-2: image -> registers
+        copy_out_load(t - 1, vs, vc);          // outputs of step t-1: image -> registers
         float wx[G][PP];
         {
             const char* im = in_img + (t & 1) * L.in_pitch + l_in;   // this step's inputs from their image
@@ -204,15 +184,16 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
             for (int g = 0; g < G; ++g) acc[g] = OP::mfma(Rf[g][2], hB[2], acc[g]);
         }
         pin_order();
-        copy_out_store(t - 2, vs, vc);         // ... -> HBM
+        copy_out_store(t - 1, vs, vc);         // ... -> HBM
         pin_order();
 #pragma unroll
         for (int kt = 3; kt < KT; ++kt)
 #pragma unroll
             for (int g = 0; g < G; ++g) acc[g] = OP::mfma(Rf[g][kt], hB[kt], acc[g]);
-        // ---- point-wise function
+        // ---- point-wise function; the step's outputs go to their image (they leave for HBM during the next step)
 #pragma unroll
         for (int g = 0; g < G; ++g) compact_tile<BT>(acc[g]);
+        char* oimg = out_img + (t & 1) * OUT_PITCH;
 #pragma unroll
         for (int i = 0; i < PP; ++i) {
             float wxi[G], ybi[G], sti[S], cvi[NC];
@@ -223,10 +204,15 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
             Cell<CELL, true>::fwd(wxi, ybi, sti, cvi);
 #pragma unroll
             for (int s = 0; s < S; ++s) st[s][i] = sti[s];
+            float wv[kCacheSlots];
 #pragma unroll
-            for (int c2 = 0; c2 < NC; ++c2) cvs[c2][i] = cvi[c2];
+            for (int c2 = 0; c2 < kCacheSlots; ++c2) wv[c2] = c2 < NC ? cvi[c2 < NC ? c2 : 0] : 0.0f;
+            *(i32x4*)(oimg + l_c + i * REC) = i32x4{(int)pack_bf16x2(wv[0], wv[1]), (int)pack_bf16x2(wv[2], wv[3]),
+                                                    (int)pack_bf16x2(wv[4], wv[5]), (int)pack_bf16x2(wv[6], wv[7])};
         }
         write_operand_lds<true, PP>(hbuf + (t & 1) * BUF + lds_row, e0, st[0]);
+#pragma unroll
+        for (int s = 0; s < S; ++s) store_io<false, PP>(oimg + l_st + (uint32_t)s * BT * L.rp_st, 0, st[s]);
         {
             char* im = in_img + ((t + 1) & 1) * L.in_pitch;
 #pragma unroll
@@ -234,18 +220,13 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
         }
         __syncthreads();
     }
-    // ---- drain: outputs of step T-1 (image written during step T) and of step T
+    // ---- drain: outputs of step T
     if (T > 0) {
         i32x4 vs[NCH_ST], vc[NCH_C];
-        copy_out_load(T - 1, vs, vc);
-        copy_out_store(T - 1, vs, vc);
-        write_image(T);
-        __syncthreads();
         copy_out_load(T, vs, vc);
         copy_out_store(T, vs, vc);
     }
 }
-
 
 // =============================================================================================
 // backward, one block of 16 units per wave, contraction split over EBK waves
