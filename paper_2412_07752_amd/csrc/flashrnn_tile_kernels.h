@@ -1,16 +1,15 @@
 // Persistent kernels for the case that carries the headline workload: bf16 I/O, one workgroup per
 // group, batch tiles of 4 or 8 rows (BT < 16), one block of 16 units per wave.
 //
-// What bounds a step here (measured with per-phase cycle stamps on MI355X) is the matrix pipe of each
-// SIMD: three waves share it and their MFMA chains fill about 1150 cycles per step, while the
-// point-wise function takes about 100.  Everything that is not on the dependency chain
+// The matrix pipe of each SIMD is busy for about 1150 cycles per step here (three waves share it), the
+// point-wise function of a wave takes a few hundred.  Everything that is not on the dependency chain
 //     h_{t-1} in LDS -> MFMA chain -> point-wise -> h_t in LDS -> barrier
-// is therefore issued between the MFMAs of the chain, where it costs nothing:
-//   - global traffic goes through LDS row images and moves as one 16-byte chunk per thread (a lane
-//     holds only one or two values per row, and the CU's memory pipeline needs about 16 cycles per
-//     narrow scattered instruction: 13 of them per wave and step would cost more than the MFMAs);
-//   - the outputs of step t-1 are written to their image during the chain of step t and leave for HBM
-//     during the chain of step t+1; the inputs of step t+1 are fetched during the chain of step t.
+// is issued between the MFMAs of a wave's chain:
+//   - global traffic goes through LDS images and moves as one 16-byte chunk per thread (a lane holds
+//     only one or two values per row, and the CU's memory pipeline needs about 16 cycles per narrow
+//     scattered instruction: 13 of them per wave and step would cost more than the MFMAs);
+//   - forward: the point-wise phase writes the outputs of step t to their image, from where they leave
+//     for HBM during the chain of step t+1; the inputs of step t+1 are fetched during the chain of step t.
 // Image rows are padded (lds_row_pitch) so that a wave's 4-rows x 16-units accesses hit 64 distinct banks.
 #pragma once
 #include "flashrnn_kernels.h"
