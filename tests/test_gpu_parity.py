@@ -13,7 +13,8 @@ from paper_2412_07752_amd.synth import CELL_GRU, CELL_LSTM, CELL_SLSTM, Workload
 
 pytestmark = pytest.mark.gpu
 CELLS = [CELL_LSTM, CELL_GRU, CELL_SLSTM]
-PLAN_ENV = ("FLASHRNN_MULTI", "FLASHRNN_BT", "FLASHRNN_NWU", "FLASHRNN_KS", "FLASHRNN_GPAR", "FLASHRNN_SPIN_LIMIT")
+PLAN_ENV = ("FLASHRNN_MULTI", "FLASHRNN_BT", "FLASHRNN_NWU", "FLASHRNN_KS", "FLASHRNN_GPAR", "FLASHRNN_SPIN_LIMIT", "FLASHRNN_EBK",
+            "FLASHRNN_KIND")
 
 
 @pytest.fixture(autouse=True)
@@ -77,6 +78,29 @@ def test_groups_split_over_workgroups(cell, dtype, D, env):
 
 
 @pytest.mark.parametrize("cell", CELLS)
+@pytest.mark.parametrize("D,ebk", [(64, 1), (64, 2), (128, 1), (128, 2), (128, 4), (192, 1), (192, 3)])
+def test_backward_contraction_split_over_waves(cell, D, ebk):
+    """Backward tile kernel with the gate-gradient contraction in one piece per wave or split over 2, 3, 4 waves."""
+    w = Workload(f"ebk{ebk}_{cell}_D{D}", cell, 8, 10, 2, D, "bf16", True, bias="uniform0.1", init="uniform0.1", seed=D + ebk)
+    _check(w, {"FLASHRNN_EBK": str(ebk)}, with_dlast=True)
+
+
+@pytest.mark.parametrize("cell", CELLS)
+@pytest.mark.parametrize("bt", [8, 4])
+def test_generic_kernels_on_small_batch_tiles(cell, bt):
+    """The generic persistent kernels (lane-wise global accesses) on the shapes the staged tile kernels normally take."""
+    w = Workload(f"generic_bt{bt}_{cell}", cell, 7, 11, 2, 96, "bf16", True, bias="uniform0.1", init="uniform0.1", seed=bt + 40)
+    _check(w, {"FLASHRNN_KIND": "0", "FLASHRNN_BT": str(bt)}, with_dlast=True)
+
+
+@pytest.mark.parametrize("cell", CELLS)
+def test_forward_only_small_batch_tile(cell):
+    """No gate cache: the staged forward kernel moves states only."""
+    w = Workload(f"fwdonly_{cell}", cell, 6, 7, 2, 128, "bf16", False, bias="uniform0.1", init="uniform0.1", seed=77)
+    _check(w)
+
+
+@pytest.mark.parametrize("cell", CELLS)
 def test_group_loop_when_groups_do_not_fit(cell):
     """More groups than run at once: workgroups loop over groups and reload R per head."""
     w = Workload(f"loop_{cell}", cell, 7, 40, 3, 64, "bf16", True, bias="uniform0.1", init="uniform0.1", seed=5)
@@ -84,8 +108,9 @@ def test_group_loop_when_groups_do_not_fit(cell):
 
 
 @pytest.mark.parametrize("cell", CELLS)
-@pytest.mark.parametrize("T", [0, 1])
+@pytest.mark.parametrize("T", [0, 1, 2, 3])
 def test_degenerate_lengths(cell, T):
+    """The staged kernels look two steps ahead: the shortest sequences take every clamped branch of that."""
     w = Workload(f"T{T}_{cell}", cell, T, 5, 2, 32, "bf16", True, bias="uniform0.1", init="uniform0.1")
     gpu = _check(w, with_dlast=True)
     if T == 0:
