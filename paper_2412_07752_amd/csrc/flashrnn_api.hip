@@ -6,6 +6,7 @@
 #include <string.h>
 
 #include <mutex>
+#include <map>
 #include <set>
 
 #include "flashrnn_common.h"
@@ -62,6 +63,23 @@ int validate(const flashrnn_desc_t* d) {
     return FLASHRNN_OK;
 }
 
+constexpr size_t kLdsBytes = 160 * 1024;   // LDS of one CU
+
+// true if the kernel keeps part of its registers in scratch memory (known once a device is there)
+bool kernel_spills(const void* fn) {
+    static std::mutex mu;
+    static std::map<const void*, bool> seen;
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = seen.find(fn);
+    if (it != seen.end()) return it->second;
+    hipFuncAttributes attr;
+    bool spills = false;
+    if (hipFuncGetAttributes(&attr, fn) == hipSuccess) spills = attr.localSizeBytes > 0;
+    else (void)hipGetLastError();
+    seen[fn] = spills;
+    return spills;
+}
+
 // Launch plan.  One workgroup per group whenever the head's R fits one CU's registers with 16 units
 // per wave (no cross-CU traffic at all); then small batch tiles spread the point-wise work over more
 // CUs.  Otherwise a group is split over P workgroups of one XCD that exchange h / dg every step.
@@ -84,52 +102,54 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
     Plan pl;
 
     if (force_multi != 1) {
-        int bt_pref[3] = {16, 8, 4};
-        int nbt = 1;
-        if (bf) {
-            // smallest batch tile whose groups still fit the chip once
-            if (d->NH * ((d->B + 3) / 4) <= cus) { bt_pref[0] = 4; bt_pref[1] = 8; bt_pref[2] = 16; }
-            else if (d->NH * ((d->B + 7) / 8) <= cus) { bt_pref[0] = 8; bt_pref[1] = 16; bt_pref[2] = 4; }
-            nbt = 3;
+        // Every (batch tile, kernel) pair that can run the shape gets a cost: rounds of workgroups over the CUs
+        // times a relative time per step.  The relative times are measured ones (D = 192 and 128, MI355X): the
+        // staged tile kernels run a step of 4 rows in 1.0, of 8 rows in about 1.5; the generic kernels, whose
+        // lanes access global memory themselves, need about 1.8 / 3.0 / 6.0 for 4 / 8 / 16 rows.  A kernel that
+        // spills registers or whose images do not fit the LDS is not a candidate.
+        const KernelEntry* best = nullptr;
+        double best_cost = 0.0;
+        size_t best_smem = 0;
+        for (int i = 0; i < tab.count; ++i) {
+            const KernelEntry& e = tab.entries[i];
+            if (e.bwd != bwd || e.multi || e.KS != 1) continue;
+            if (force_bt && e.BT != force_bt) continue;
+            if (e.KT * kstep < kdim || units16 % e.eb != 0 || e.maxw * (e.tile == 1 ? 1 : e.eb) < units16) continue;
+            if (force_eb ? e.eb != force_eb : false) continue;
+            if (force_kind >= 0 && e.tile != force_kind) continue;
+            if (force_ebk && bwd && e.tile == 1 && e.eb != force_ebk) continue;
+            const int dk = e.KT * kstep, nw = e.tile == 1 ? units16 : units16 / e.eb;
+            size_t smem = (size_t)2 * e.BT * (dk + (bf ? 8 : 4)) * (bf ? 2 : 4);
+            if (e.tile == 1 && bwd) {
+                const int nsb = d->cell == FLASHRNN_SLSTM ? 2 : 1, go = d->cell == FLASHRNN_GRU ? G + 1 : G;
+                smem = tile_lds_bwd(e.BT, go, nsb, d->D, dk * 2, e.eb).total;
+            } else if (e.tile == 1) {
+                smem = tile_lds(e.BT, G, num_states(d->cell), d->D, 64 * nw, dk * 2, 0, 0, 0).total_fwd;
+            }
+            if (smem > kLdsBytes) continue;
+            if (e.tile == 1 && kernel_spills(e.fn)) continue;
+            const int ng = d->NH * ((d->B + e.BT - 1) / e.BT);
+            const int rounds = (ng + cus - 1) / cus;
+            double rel = e.tile == 1 ? (e.BT == 4 ? 1.0 : 1.5) : (e.BT == 4 ? 1.8 : e.BT == 8 ? 3.0 : 6.0);
+            // the backward tile kernel splits the contraction over its waves only when the operand reads are
+            // many (k-steps x waves); otherwise the second barrier costs more than it saves
+            if (e.tile == 1 && bwd && ((e.eb > 1) != (e.KT * units16 >= 256))) rel *= 1.05;
+            if (e.tile == 0) rel *= 1.0 + 0.05 * (e.eb - 1);       // thin waves overlap better
+            rel *= 1.0 + 0.02 * (dk - kdim) / (double)kstep;       // padded k-steps are wasted MFMAs
+            const double cost = rounds * rel;
+            if (!best || cost < best_cost) { best = &e; best_cost = cost; best_smem = smem; }
         }
-        if (force_bt) { bt_pref[0] = force_bt; nbt = 1; }
-        for (int b = 0; b < nbt && !pl.e; ++b) {
-            const KernelEntry* best = nullptr;
-            for (int i = 0; i < tab.count; ++i) {
-                const KernelEntry& e = tab.entries[i];
-                if (e.bwd != bwd || e.multi || e.KS != 1 || e.BT != bt_pref[b]) continue;
-                if (e.KT * kstep < kdim || units16 % e.eb != 0 || e.maxw * (e.tile == 1 ? 1 : e.eb) < units16) continue;
-                if (force_eb ? e.eb != force_eb : false) continue;
-                if (force_kind >= 0 && e.tile != force_kind) continue;
-                if (force_ebk && bwd && e.tile == 1 && e.eb != force_ebk) continue;
-                // smallest contraction padding first; then the staged tile kernels before the generic one,
-                // there the thinnest waves
-                // the backward tile kernel splits the contraction over its waves only when the operand
-                // reads are many (k-steps x waves); otherwise the second barrier costs more than it saves
-                const bool split = bwd && e.KT * units16 >= 256;
-                auto rank_of = [&](const KernelEntry& x) { return x.tile == 1 ? ((x.eb > 1) == split ? 0 : 1) : 1 + x.eb; };
-                if (!best || e.KT < best->KT || (e.KT == best->KT && rank_of(e) < rank_of(*best))) best = &e;
-            }
-            if (best) {
-                pl.e = best;
-                pl.NWU = best->tile == 1 ? units16 : units16 / best->eb;   // the tile kernels run one wave per block of 16 units
-                pl.P = 1;
-                pl.NG = d->NH * ((d->B + best->BT - 1) / best->BT);
-                pl.GPAR = pl.NG;
-                pl.grid = pl.NG;
-                pl.block = 64 * pl.NWU;
-                pl.DK = best->KT * kstep;
-                const int hp = pl.DK + (bf ? 8 : 4);
-                pl.smem = (size_t)2 * best->BT * hp * (bf ? 2 : 4);
-                if (best->tile == 1 && bwd) {
-                    const int nsb = d->cell == FLASHRNN_SLSTM ? 2 : 1, go = d->cell == FLASHRNN_GRU ? G + 1 : G;
-                    pl.smem = tile_lds_bwd(best->BT, go, nsb, d->D, pl.DK * 2, best->eb).total;
-                } else if (best->tile != 0 && !bwd) {
-                    // tile kernel: operand rows + LDS row images of one step's inputs and outputs
-                    pl.smem = tile_lds(best->BT, G, num_states(d->cell), d->D, pl.block, pl.DK * 2, 0, 0, 0).total_fwd;
-                }
-                pl.exch_bytes = 0;
-            }
+        if (best) {
+            pl.e = best;
+            pl.NWU = best->tile == 1 ? units16 : units16 / best->eb;   // the tile kernels run one wave per block of 16 units
+            pl.P = 1;
+            pl.NG = d->NH * ((d->B + best->BT - 1) / best->BT);
+            pl.GPAR = pl.NG;
+            pl.grid = pl.NG;
+            pl.block = 64 * pl.NWU;
+            pl.DK = best->KT * kstep;
+            pl.smem = best_smem;
+            pl.exch_bytes = 0;
         }
     }
     if (!pl.e && force_multi != 0) {
