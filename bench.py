@@ -9,7 +9,9 @@ states).  Inputs are resident in HBM before the timed region.  Prints ONE JSON l
     python bench.py --copy-calibration     # a plain copy of known size, for scaling rocprofv3's HBM counters
 
 roofline.traffic is the measured HBM traffic per launch of the dominant kernel, taken from the summary
-of the two rocprofv3 --pmc runs under profiles/ (hbm_traffic_<workload>.txt) when that file is there.
+of the two rocprofv3 --pmc runs under profiles/ (hbm_traffic_<workload>.txt) when that file is there;
+roofline.mfma_busy_frac_of_occupied_cus likewise from sq_counters_<workload>.txt.  frac_of_occupied_cus
+counts the useful flops only (4 of the 16 batch columns of an MFMA tile carry data with 4-row batch tiles).
 """
 import argparse
 import json
@@ -127,12 +129,19 @@ def main():
             key = "bwd_bytes_per_launch:" if dom_bwd else "fwd_bytes_per_launch:"
             if ln.startswith(key):
                 traffic = float(ln.split(":")[1])
+    busy = None      # measured share of the kernel's duration in which a SIMD's matrix pipe is busy (SQ_VALU_MFMA_BUSY_CYCLES)
+    sf = os.path.join(ROOT, "profiles", f"sq_counters_{w.name}.txt")
+    if os.path.exists(sf):
+        for ln in open(sf):
+            if ln.startswith("bwd_mfma_busy_frac:" if dom_bwd else "fwd_mfma_busy_frac:"):
+                busy = float(ln.split(":")[1])
     roofline = {
         "bound": "mfma", "kernel": ("bwd_kernel" if dom_bwd else "fwd_kernel"), "achieved": round(achieved, 4), "peak": peak,
         "unit": "TFLOP/s", "frac": achieved / peak, "traffic": traffic,
         "launch_ms": round(dom_ms, 5), "launches_timed": nb if dom_bwd else nf,
         "flops_per_launch": flops_launch,
         "workgroups": wgs, "frac_of_occupied_cus": achieved / (peak * wgs / DEVICE_CUS),
+        "mfma_busy_frac_of_occupied_cus": busy,
         "hbm_stream_GBs": round(bytes_launch / (dom_ms * 1e-3) / 1e9, 2) if dom_ms > 0 else None,
         "hbm_frac": (bytes_launch / (dom_ms * 1e-3) / 1e9) / PEAK_HBM_GBS if dom_ms > 0 else None,
         "fwd_kernel_ms": round(fwd_ms, 5), "bwd_kernel_ms": round(bwd_ms, 5),
