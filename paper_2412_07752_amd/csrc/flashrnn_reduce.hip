@@ -46,8 +46,9 @@ __global__ __launch_bounds__(256) void dr_gemm_kernel(const float* __restrict__ 
         for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // loader roles: A: thread -> k pair (2 rows) x 4 consecutive d;  B: thread -> k pair x 8 consecutive columns
-    const int a_kp = tid >> 4, a_d = (tid & 15) * 4;        // 16 k pairs x 16 column groups
-    const int b_kp = tid >> 4, b_j = (tid & 15) * 8;        // 16 k pairs x 16 column groups of 8
+    // (the 16 k pairs run over the lanes of a 16-lane group: their transposed LDS writes then fall into 16 consecutive banks)
+    const int a_kp = tid & 15, a_d = (tid >> 4) * 4;        // 16 k pairs x 16 column groups
+    const int b_kp = tid & 15, b_j = (tid >> 4) * 8;        // 16 k pairs x 16 column groups of 8
     const int d_glob = tm * TM + a_d;
     const int j_glob = tn * TN + b_j;
     const bool a_ok = d_glob < D, b_ok = j_glob < GD;
