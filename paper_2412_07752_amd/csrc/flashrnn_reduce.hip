@@ -161,10 +161,11 @@ __global__ void sum_slices_kernel(const float* __restrict__ part, float* __restr
     out[j] = a;
 }
 
-// the two reductions that end the backward pass, in one launch: elements [0, count1) and [count1, count1 + count2)
+// the two reductions that end the backward pass, in one launch: elements [0, count1) and [count1, count1 + count2);
+// four consecutive elements per thread (all counts and strides here are multiples of 4: D is a multiple of 16)
 __global__ void sum_slices2_kernel(const float* __restrict__ part1, float* __restrict__ out1, size_t count1, int NS1, size_t stride1,
                                    const float* __restrict__ part2, float* __restrict__ out2, size_t count2, int NS2, size_t stride2) {
-    size_t j = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t j = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
     const float* part = part1;
     float* out = out1;
     int NS = NS1;
@@ -174,9 +175,9 @@ __global__ void sum_slices2_kernel(const float* __restrict__ part1, float* __res
         if (j >= count2) return;
         part = part2; out = out2; NS = NS2; stride = stride2;
     }
-    float a = 0.f;
-    for (int s = 0; s < NS; ++s) a += part[(size_t)s * stride + j];
-    out[j] = a;
+    f32x4 a = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < NS; ++s) a += *(const f32x4*)(part + (size_t)s * stride + j);
+    *(f32x4*)(out + j) = a;
 }
 
 __global__ void fill_zero_kernel(uint32_t* __restrict__ p, size_t count) {
@@ -245,7 +246,7 @@ hipError_t launch_dr_gemm(bool bf16, const float* states, const void* dWx, const
     if (e != hipSuccess) return e;
     // split-K partial sums of dR (if any) and the per-row partial sums of db, each added in index order
     const size_t count = SK > 1 ? (size_t)NH * D * GD : 0, nb = (size_t)NH * GD;
-    hipLaunchKernelGGL(sum_slices2_kernel, dim3((unsigned)((count + nb + 255) / 256)), dim3(256), 0, stream, part, dR, count, SK, (size_t)NH * D * GD,
+    hipLaunchKernelGGL(sum_slices2_kernel, dim3((unsigned)(((count + nb) / 4 + 255) / 256)), dim3(256), 0, stream, part, dR, count, SK, (size_t)NH * D * GD,
                        db_part, db, nb, B, nb);
     e = hipGetLastError();
     return e;
