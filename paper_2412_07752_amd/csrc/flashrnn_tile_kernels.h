@@ -185,6 +185,15 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
         pin_order();
         copy_out_store(t - 1, vs, vc);         // ... -> HBM
         pin_order();
+        // The next step's inputs go from registers to their image: with a long chain they have arrived by now and
+        // the writes stay out of the step's tail; with a short chain waiting here would stall it (measured both ways).
+        constexpr bool kParkEarly = KT >= 6;
+        if constexpr (kParkEarly) {
+            char* im = in_img + ((t + 1) & 1) * L.in_pitch;
+#pragma unroll
+            for (int k2 = 0; k2 < NCH_IN; ++k2) *(i32x4*)(im + cin_l[k2]) = pre[k2];
+        }
+        pin_order();
 #pragma unroll
         for (int kt = 3; kt < KT; ++kt)
 #pragma unroll
@@ -212,7 +221,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
         write_operand_lds<true, PP>(hbuf + (t & 1) * BUF + lds_row, e0, st[0]);
 #pragma unroll
         for (int s = 0; s < S; ++s) store_io<false, PP>(oimg + l_st + (uint32_t)s * BT * L.rp_st, 0, st[s]);
-        {
+        if constexpr (!kParkEarly) {
             char* im = in_img + ((t + 1) & 1) * L.in_pitch;
 #pragma unroll
             for (int k2 = 0; k2 < NCH_IN; ++k2) *(i32x4*)(im + cin_l[k2]) = pre[k2];
