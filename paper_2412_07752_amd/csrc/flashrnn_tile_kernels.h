@@ -411,6 +411,11 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
     __syncthreads();
     if (T > 0) take(T);
 
+    float dbv[G][PP];   // the db sums, read back ahead of each point-wise phase
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int i = 0; i < PP; ++i) dbv[g][i] = 0.0f;
     for (int t = T; t >= 1; --t) {
         // ---- point-wise Jacobians of step t
         {
@@ -430,8 +435,10 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
                 for (int g = 0; g < G; ++g) {
                     dwx[g][i] = dwxi[g];
                     dg[g][i] = dgi[g];
-                    // db sums live in LDS (each lane owns its slots): registers are what this kernel is short of
-                    dbs[((size_t)g * D + i) * BT] += dgi[g];
+                    // db sums live in LDS between the point-wise phases (each lane owns its slots): registers are
+                    // what this kernel is short of while the MFMAs run
+                    dbv[g][i] += dgi[g];
+                    dbs[((size_t)g * D + i) * BT] = dbv[g][i];
                 }
             }
 #pragma unroll
@@ -504,6 +511,10 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
 #pragma unroll
             for (int j = 0; j < EBK; ++j)   // partial sum of block tg*EBK + j from slice ks
                 store_io<false, PP>(red, ((size_t)((tg * EBK + j) * EBK + ks) * 64 + lane) * PP, part[j]);
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int i = 0; i < PP; ++i) dbv[g][i] = dbs[((size_t)g * D + i) * BT];
             __syncthreads();
 #pragma unroll
             for (int x = 0; x < EBK; ++x) {
@@ -515,6 +526,10 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
         } else {
 #pragma unroll
             for (int i = 0; i < PP; ++i) ds[0][i] += part[0][i];
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+#pragma unroll
+                for (int i = 0; i < PP; ++i) dbv[g][i] = dbs[((size_t)g * D + i) * BT];
         }
     }
     // ---- gradients w.r.t. the initial states, per-row partial sums of db
