@@ -438,7 +438,6 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
                     // db sums live in LDS between the point-wise phases (each lane owns its slots): registers are
                     // what this kernel is short of while the MFMAs run
                     dbv[g][i] += dgi[g];
-                    dbs[((size_t)g * D + i) * BT] = dbv[g][i];
                 }
             }
 #pragma unroll
@@ -458,6 +457,10 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
         // they are read after this barrier
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(CELL == CELL_GRU ? 2 : 1) : "memory");
         __syncthreads();
+#pragma unroll
+        for (int g = 0; g < G; ++g)   // (behind the barrier: nobody else reads them)
+#pragma unroll
+            for (int i = 0; i < PP; ++i) dbs[((size_t)g * D + i) * BT] = dbv[g][i];
         // ---- dh_{t-1} += R dg_t; in the shadow of the chain: fetch step t-2, dWx_t out, step t-1's values
         // The operand is read in chunks of KC k-steps, one chunk ahead of the MFMAs that use it.
         constexpr int KC = 4, NCK = (KTW + KC - 1) / KC;
