@@ -7,6 +7,7 @@ states).  Inputs are resident in HBM before the timed region.  Prints ONE JSON l
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload IDX] [--no-cpu-baseline]
     python bench.py --copy-calibration     # a plain copy of known size, for scaling rocprofv3's HBM counters
+    python bench.py --shape slstm,1024,16,4,192   # any (cell, T, B, NH, D) of the paper's sweeps; add ",fwd" for forward only
 
 roofline.traffic is the measured HBM traffic per launch of the dominant kernel, taken from the summary
 of the two rocprofv3 --pmc runs under profiles/ (hbm_traffic_<workload>.txt) when that file is there;
@@ -35,6 +36,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=25)
     ap.add_argument("--workload", type=int, default=1, help="index into the benchmark configurations (default 1: the headline one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--shape", type=str, default=None,
+                    help="cell,T,B,NH,D[,fwd]: bf16 workload with the paper's recipe (Wx, dH ~ N(0,1), R ~ N(0,1/D), forget bias 3), "
+                         "drawn on the GPU; no oracle timing")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain elementwise copy of 256 MiB (reads 256 MiB, writes 256 MiB) five times and exit")
     args = ap.parse_args()
@@ -59,10 +63,6 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration": True, "bytes_read": 4 * n, "bytes_written": 4 * n, "launches": 5}))
         return
-    w = synth.CONFIGS[args.workload]
-    bf16 = w.dtype == "bf16"
-    inp = synth.make_inputs(w)
-
     def dev(a, dt):
         if a is None:
             return None
@@ -70,9 +70,29 @@ def main():
             return torch.from_numpy(synth.bf16_bits(a).view(np.int16)).cuda().view(torch.bfloat16)
         return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
 
-    Wx, R, b = dev(inp["Wx"], w.dtype), dev(inp["R"], w.dtype), dev(inp["b"], w.dtype)
-    s0 = dev(inp["states0"], "f32")
-    dH = dev(inp["dH"], w.dtype)
+    if args.shape:
+        f = args.shape.split(",")
+        cell = {v: k for k, v in synth.CELL_NAMES.items()}[f[0]]
+        w = synth.Workload("sweep_" + "_".join(f), cell, int(f[1]), int(f[2]), int(f[3]), int(f[4]), "bf16", len(f) < 6 or f[5] != "fwd")
+        args.no_cpu_baseline = True
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(0)
+        Wx = torch.randn((w.T, w.B, w.G, w.NH, w.D), device="cuda", generator=gen).bfloat16()
+        R = (torch.randn((w.NH, w.D, w.G, w.D), device="cuda", generator=gen) / w.D ** 0.5).bfloat16()
+        b = torch.zeros((w.NH, w.G, w.D), device="cuda")
+        if cell != synth.CELL_GRU:
+            b[:, synth.FORGET_GATE] = 3.0
+        b = b.bfloat16()
+        s0 = None
+        dH = torch.randn((w.T, w.B, w.NH, w.D), device="cuda", generator=gen).bfloat16() if w.backward else None
+        inp = None
+    else:
+        w = synth.CONFIGS[args.workload]
+        inp = synth.make_inputs(w)
+        Wx, R, b = dev(inp["Wx"], w.dtype), dev(inp["R"], w.dtype), dev(inp["b"], w.dtype)
+        s0 = dev(inp["states0"], "f32")
+        dH = dev(inp["dH"], w.dtype)
+    bf16 = w.dtype == "bf16"
     T, B, NH, D, G, S = w.T, w.B, w.NH, w.D, w.G, w.S
     desc = api.make_desc(w.cell, T, B, NH, D, api.FLASHRNN_BF16 if bf16 else api.FLASHRNN_F32)
     ws = api.alloc_workspace(desc, "cuda")
@@ -170,7 +190,7 @@ def main():
                          f"{'fwd+bwd' if w.backward else 'fwd'}, fp64, {reps} passes in {c1 - c0:.2f} s"}
 
     line = {
-        "metric": "fwd+bwd B*T steps/sec per RNN layer (sLSTM); recurrent-GEMM MFMA utilisation" if args.workload == 1
+        "metric": "fwd+bwd B*T steps/sec per RNN layer (sLSTM); recurrent-GEMM MFMA utilisation" if (args.workload == 1 and not args.shape)
                   else "B*T steps/sec per RNN layer",
         "value": value, "unit": "B*T steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
