@@ -124,7 +124,7 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
                 const int nsb = d->cell == FLASHRNN_SLSTM ? 2 : 1, go = d->cell == FLASHRNN_GRU ? G + 1 : G;
                 smem = tile_lds_bwd(e.BT, go, nsb, d->D, dk * 2, e.eb).total;
             } else if (e.tile == 1) {
-                smem = tile_lds(e.BT, G, num_states(d->cell), d->D, 64 * nw, dk * 2, 0, 0, 0).total_fwd;
+                smem = tile_lds(e.BT, G, num_states(d->cell), d->D, 64 * nw, dk * 2).total_fwd;
             }
             if (smem > kLdsBytes) continue;
             if (e.tile == 1 && kernel_spills(e.fn)) continue;
@@ -171,11 +171,15 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
             // every group run at once; fall back to looping over groups
             const int slots = (NG + kXcds - 1) / kXcds;       // groups per XCD if all run at once
             int chosen = 0;
-            for (int nwu = 1; nwu <= nwu_max; ++nwu) {
-                if (units16 % nwu) continue;
-                const int P = units16 / nwu;
-                if (force_nwu ? nwu == force_nwu : P * slots <= cap) { chosen = nwu; break; }
-            }
+            // (at least four waves per workgroup where the shape allows: the workgroup polls the group's rows
+            // together, and with fewer threads that takes more rounds - measured on D = 256 and 768)
+            const int nwu_min = 4 / best->KS > 1 ? 4 / best->KS : 1;
+            for (int pass = 0; pass < 2 && !chosen; ++pass)
+                for (int nwu = pass == 0 ? nwu_min : 1; nwu <= nwu_max; ++nwu) {
+                    if (units16 % nwu) continue;
+                    const int P = units16 / nwu;
+                    if (force_nwu ? nwu == force_nwu : P * slots <= cap) { chosen = nwu; break; }
+                }
             int gpar = NG;
             if (!chosen) {
                 // even the fewest workgroups per group do not fit all groups: loop over groups
@@ -195,7 +199,8 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
                 pl.block = 64 * chosen * best->KS;
                 pl.DK = best->KT * best->KS * kstep;
                 const int nt = bwd ? 1 : G;
-                pl.smem = best->KS > 1 ? (size_t)2 * (best->KS - 1) * chosen * nt * 4 * 64 * 4 : 16;
+                // one buffer of 16 operand rows (polled once per workgroup and step), then the partial sums of the slices
+                pl.smem = (size_t)16 * (pl.DK + (bf ? 8 : 4)) * (bf ? 2 : 4) + (best->KS > 1 ? (size_t)2 * (best->KS - 1) * chosen * nt * 4 * 64 * 4 : 16);
                 pl.exch_bytes = (size_t)2 * gpar * 16 * pl.DK * (bf ? 4 : 8);
             }
         }

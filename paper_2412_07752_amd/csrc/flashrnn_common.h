@@ -44,20 +44,19 @@ __host__ __device__ inline uint32_t lds_row_pitch(uint32_t row_bytes) {
     return (dw + (16u + 64u - dw % 64u) % 64u) * 4u;
 }
 
-// LDS layout of the tile kernels (bf16 I/O, one workgroup per group, BT < 16), shared by the kernels
+// LDS layout of the forward tile kernel (bf16 I/O, one workgroup per group, BT < 16), shared by the kernel
 // and by the host code that sizes the dynamic LDS.  NT threads; every thread moves NCH 16-byte chunks
 // of each image per step, threads without a real chunk own a private pad chunk behind the image.
 struct TileLds {
     uint32_t hp;                              // operand row pitch (bytes), buf = BT * hp
     uint32_t rp_io, rp_st;                    // image row pitches: bf16 rows, f32 rows
-    uint32_t in_bytes, in_pitch;              // forward inputs Wx (BT*G rows) / backward outputs dWx (+dgn)
+    uint32_t in_bytes, in_pitch;              // inputs Wx (BT*G rows)
     uint32_t st_bytes, st_pitch;              // f32 state rows
     uint32_t c_bytes, c_pitch, rec_pitch;     // saved-values records: BT rows of D records of 16 bytes, rows rec_pitch apart
-    uint32_t dh_bytes, dh_pitch;              // backward: external dh rows (BT rows)
-    uint32_t total_fwd, total_bwd;
+    uint32_t total_fwd;
 };
 __host__ __device__ inline uint32_t div_up(uint32_t a, uint32_t b) { return (a + b - 1) / b; }
-__host__ __device__ inline TileLds tile_lds(int BT, int G, int S, int D, int NT, int k_bytes_fwd, int k_bytes_bwd, int st_rows_bwd, int out_rows_bwd) {
+__host__ __device__ inline TileLds tile_lds(int BT, int G, int S, int D, int NT, int k_bytes_fwd) {
     TileLds L;
     const uint32_t nt16 = (uint32_t)NT * 16;
     L.rp_io = lds_row_pitch((uint32_t)D * 2);
@@ -69,16 +68,8 @@ __host__ __device__ inline TileLds tile_lds(int BT, int G, int S, int D, int NT,
     L.rec_pitch = lds_row_pitch((uint32_t)D * 16);
     L.c_bytes = (uint32_t)BT * L.rec_pitch;
     L.c_pitch = div_up(div_up((uint32_t)BT * D, NT) * NT, D) * L.rec_pitch;   // rows that the copy-out chunks of all threads touch
-    L.dh_bytes = (uint32_t)BT * L.rp_io;
-    L.dh_pitch = L.dh_bytes + div_up((uint32_t)BT * (D / 8), NT) * nt16;
     L.hp = lds_row_pitch((uint32_t)k_bytes_fwd);
     L.total_fwd = 2 * BT * L.hp + 2 * L.in_pitch + 2 * (L.st_pitch + L.c_pitch);
-    // backward: operand rows of k_bytes_bwd; images: saved values, st_rows_bwd state rows per batch row
-    // (at two time levels they are loaded as one image per step), dh, and out_rows_bwd bf16 output rows
-    const uint32_t hpb = lds_row_pitch((uint32_t)k_bytes_bwd);
-    const uint32_t stb = (uint32_t)BT * st_rows_bwd * L.rp_st, stbp = stb + div_up((uint32_t)BT * st_rows_bwd * (D / 4), NT) * nt16;
-    const uint32_t ob = (uint32_t)BT * out_rows_bwd * L.rp_io, obp = ob + div_up((uint32_t)BT * out_rows_bwd * (D / 8), NT) * nt16;
-    L.total_bwd = 2 * BT * hpb + 2 * L.c_pitch + 3 * stbp + 2 * L.dh_pitch + 2 * obp;
     return L;
 }
 

@@ -167,10 +167,10 @@ struct BlockMap {
     }
 };
 
-// Waves that share a SIMD (wave w runs on SIMD w % 4) get different issue priorities.  After the
-// per-step barrier all of them want the matrix pipe; with equal priorities they take turns and all
-// finish their MFMA chains late and together, then fight for the VALU.  With distinct priorities the
-// first wave finishes its chain early and its point-wise phase overlaps the next wave's MFMA chain.
+// Waves that share a SIMD (wave w runs on SIMD w % 4) get different issue priorities, so that after the
+// per-step barrier the first wave of a SIMD takes the matrix pipe first and its point-wise phase overlaps the
+// next wave's MFMA chain.  (The hardware already tends to serve the oldest wave first: measured, the
+// priorities change the step time by less than 1 %; they are kept because they make that order explicit.)
 __device__ __forceinline__ void stagger_waves(int w) {
     const int slot = w >> 2;
     if (slot == 0) __builtin_amdgcn_s_setprio(3);
@@ -187,53 +187,49 @@ __device__ __forceinline__ void stagger_waves(int w) {
 // 8- or 16-byte store, so payload and stamp always arrive together and no fence is needed.  Stores and
 // loads carry the agent-scope cache policy.  Two buffers alternate; writing round r+1 requires having
 // read round r from every member, which implies every member has finished reading round r-1.
-// Polls KC k-steps of one operand row (first k-step kt0 of the wave's KT) and returns them in hB.
-// The loads are marked volatile: every round of the loop must go to memory again.
-template <bool BF16, int KT, int KC>
-__device__ __forceinline__ bool poll_operand(__amdgpu_buffer_rsrc_t rs, uint32_t row_off, int k0, int kt0, int quad, uint32_t stamp,
-                                             int spin_limit, int* err, typename Operand<BF16>::type* hB) {
-    constexpr int NL = BF16 ? 2 * KC : KC / 2;   // 16-byte loads per lane and round (two stamped words each)
-    static_assert(BF16 || (KC % 2 == 0 && KT % 2 == 0), "f32 operand rows are read two words at a time");
+// The 16 operand rows of a group (cpr chunks of 16 bytes = two stamped
+// words per row, rows xrow bytes apart from byte offset goff of rs) are polled once, NT threads taking consecutive
+// chunks, and their payloads go to LDS rows (lds_pitch bytes apart, plain element order).  The waves then read
+// their MFMA operands from LDS like the one-workgroup kernels do (every wave polling every row in L2 itself
+// measured 1.2x to 1.5x slower at D = 256 and 768).  The loads are marked volatile: every round goes to memory again.
+// Returns false on a timeout (the error word is set; the caller stops waiting from then on).
+__device__ __forceinline__ bool poll_rows_to_lds(__amdgpu_buffer_rsrc_t rs, uint32_t goff, uint32_t xrow, uint32_t cpr, char* lds,
+                                                 uint32_t lds_pitch, uint32_t stamp, int spin_limit, int* err, uint32_t tid, uint32_t NT) {
+    constexpr int NB = 8;   // chunks per thread and round (a round costs one L2 round trip: few rounds)
     constexpr int kAuxPoll = (int)(0x80000000u | (unsigned)kAuxAgent);
-    const uint32_t base = BF16 ? row_off + (uint32_t)(k0 + kt0 * 32 + quad * 8) * 4u : row_off + (uint32_t)(k0 + quad * KT + kt0) * 8u;
-    constexpr uint32_t STEP = BF16 ? 128u : 16u;  // bytes between consecutive loads: next k-step (bf16) / next word pair (f32)
-    i32x4 raw[NL];
-    bool good = false;
-    int spins = 0;
-    if (spin_limit < 0) {  // host-forced failure (tests of the error path): give up without looking
+    constexpr uint32_t kDrop = 0x80000000u;
+    if (spin_limit < 0) {   // host-forced failure (tests of the error path): give up without looking
         __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-        for (int j = 0; j < KC; ++j) hB[j] = typename Operand<BF16>::type{};
         return false;
     }
-    while (true) {
+    const uint32_t total = 16u * cpr;
+    bool good = true;
+    for (uint32_t base = 0; base < total && good; base += NT * NB) {
+        uint32_t goffs[NB], loffs[NB];
 #pragma unroll
-        for (int j = 0; j < NL; ++j) {
-            const uint32_t off = BF16 ? base + (uint32_t)(j >> 1) * STEP + (uint32_t)(j & 1) * 16u : base + (uint32_t)j * STEP;
-            raw[j] = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, kAuxPoll);
+        for (int j = 0; j < NB; ++j) {
+            const uint32_t idx = base + tid + (uint32_t)j * NT, row = idx / cpr, c = idx % cpr;
+            goffs[j] = idx < total ? goff + row * xrow + c * 16u : kDrop;
+            loffs[j] = row * lds_pitch + c * 8u;
         }
-        bool ok = true;
+        i32x4 raw[NB];
+        for (int spins = 0;; ++spins) {
 #pragma unroll
-        for (int j = 0; j < NL; ++j) ok = ok && ((uint32_t)raw[j][1] == stamp) && ((uint32_t)raw[j][3] == stamp);
-        if (__all((int)ok)) { good = true; break; }
-        if (++spins > spin_limit) {
-            __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            break;
+            for (int j = 0; j < NB; ++j) raw[j] = __builtin_amdgcn_raw_buffer_load_b128(rs, goffs[j], 0, kAuxPoll);
+            bool ok = true;
+#pragma unroll
+            for (int j = 0; j < NB; ++j) ok = ok && (goffs[j] == kDrop || ((uint32_t)raw[j][1] == stamp && (uint32_t)raw[j][3] == stamp));
+            if (__all((int)ok)) break;
+            if (spins > spin_limit) {
+                __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                good = false;
+                break;
+            }
+            if ((spins & 255) == 255 && __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) { good = false; break; }
         }
-        if ((spins & 255) == 0 && __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) break;
-    }
-    if constexpr (BF16) {
 #pragma unroll
-        for (int j = 0; j < KC; ++j) hB[j] = __builtin_bit_cast(bf16x8, i32x4{raw[2 * j][0], raw[2 * j][2], raw[2 * j + 1][0], raw[2 * j + 1][2]});
-    } else {
-#pragma unroll
-        for (int j = 0; j < KC / 2; ++j) {
-            // (cast the whole vector, then index: a bit cast of a single vector element reads element 0
-            // with this compiler)
-            const f32x4 f = __builtin_bit_cast(f32x4, raw[j]);
-            hB[2 * j] = f[0];
-            hB[2 * j + 1] = f[2];
-        }
+        for (int j = 0; j < NB; ++j)
+            if (goffs[j] != kDrop) *(i32x2*)(lds + loffs[j]) = i32x2{raw[j][0], raw[j][2]};
     }
     return good;
 }
@@ -351,7 +347,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
     const int k0 = ks * KT * OP::KSTEP;
 
     char* hbuf = smem;                                          // !MULTI: [2][BT][HP] operand rows
-    float* red = (float*)smem;                                  // MULTI, KS > 1: partial sums
+    float* red = (float*)(smem + (MULTI ? 16 * HP * ESZ : 0));  // MULTI: one operand buffer [16][HP], then (KS > 1) the partial sums
     __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(p.exch, 0, 0x7FFFFFFF, 0x00020000);
     constexpr uint32_t XROW = DK * (BF16 ? 4 : 8);             // bytes per exchange row
     const uint32_t xgroup = (uint32_t)bm.gpar * 16u * XROW;    // this group's rows inside one buffer
@@ -466,15 +462,20 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
 #pragma unroll
                     for (int g = 0; g < G; ++g) accs[eb][g] = OP::mfma(Rf[eb][g][kt], hB[kt], accs[eb][g]);
             } else {
+                // h_{t-1} of the whole group: polled once per workgroup into LDS, then read like in the one-workgroup case
                 const uint32_t cnt = (uint32_t)iter * (uint32_t)T + (uint32_t)(t - 1);
-                const uint32_t row_off = (cnt & 1u) * xbuf + xgroup + (uint32_t)lm.c * XROW;
+                __syncthreads();   // every wave has read the previous step's rows
+                if (!failed)
+                    failed = !poll_rows_to_lds(xr, (cnt & 1u) * xbuf + xgroup, XROW, XROW / 16, hbuf, HP * ESZ, cnt + 1u, p.spin_limit, p.err,
+                                               threadIdx.x, blockDim.x);
+                __syncthreads();
 #pragma unroll
                 for (int kc = 0; kc < KT; kc += KC) {
                     op_t hB[KC];
-                    if (!failed) failed = !poll_operand<BF16, KT, KC>(xr, row_off, k0, kc, lm.quad, cnt + 1u, p.spin_limit, p.err, hB);
-                    if (failed) {
 #pragma unroll
-                        for (int j = 0; j < KC; ++j) hB[j] = op_t{};
+                    for (int j = 0; j < KC; ++j) {
+                        if constexpr (BF16) hB[j] = *(const bf16x8*)(hbuf + lds_rd + (size_t)(k0 + (kc + j) * 32 + lm.quad * 8) * 2);
+                        else hB[j] = *(const float*)(hbuf + lds_rd + (size_t)(k0 + lm.quad * KT + kc + j) * 4);
                     }
 #pragma unroll
                     for (int j = 0; j < KC; ++j)
@@ -581,7 +582,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
     const int k0 = ks * KT * OP::KSTEP;
 
     char* gbuf = smem;          // !MULTI: [2][BT][HP] gate-gradient rows
-    float* red = (float*)smem;  // MULTI, KS > 1
+    float* red = (float*)(smem + (MULTI ? BUF : 0));  // MULTI: one operand buffer [16][HP], then (KS > 1) the partial sums
     __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(p.exch, 0, 0x7FFFFFFF, 0x00020000);
     constexpr uint32_t XROW = DK * (BF16 ? 4 : 8);
     const uint32_t xgroup = (uint32_t)bm.gpar * 16u * XROW;
@@ -742,15 +743,20 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
 #pragma unroll
                     for (int eb = 0; eb < EB; ++eb) a4[eb][kt % NA] = OP::mfma(Rf[eb][kt], gB[kt], a4[eb][kt % NA]);
             } else {
+                // dg_t of the whole group: polled once per workgroup into LDS, then read like in the one-workgroup case
                 const uint32_t cnt = (uint32_t)iter * (uint32_t)T + (uint32_t)(T - t);
-                const uint32_t row_off = (cnt & 1u) * xbuf + xgroup + (uint32_t)lm.c * XROW;
+                __syncthreads();   // every wave has read the previous step's rows
+                if (!failed)
+                    failed = !poll_rows_to_lds(xr, (cnt & 1u) * xbuf + xgroup, XROW, XROW / 16, gbuf, HP * ESZ, cnt + 1u, p.spin_limit, p.err,
+                                               threadIdx.x, blockDim.x);
+                __syncthreads();
 #pragma unroll
                 for (int kc = 0; kc < KT; kc += KC) {
                     op_t gB[KC];
-                    if (!failed) failed = !poll_operand<BF16, KT, KC>(xr, row_off, k0, kc, lm.quad, cnt + 1u, p.spin_limit, p.err, gB);
-                    if (failed) {
 #pragma unroll
-                        for (int j = 0; j < KC; ++j) gB[j] = op_t{};
+                    for (int j = 0; j < KC; ++j) {
+                        if constexpr (BF16) gB[j] = *(const bf16x8*)(gbuf + lds_row + (size_t)(k0 + (kc + j) * 32 + lm.quad * 8) * 2);
+                        else gB[j] = *(const float*)(gbuf + lds_row + (size_t)(k0 + lm.quad * KT + kc + j) * 4);
                     }
 #pragma unroll
                     for (int j = 0; j < KC; ++j) a4[0][(kc + j) % NA] = OP::mfma(Rf[0][kc + j], gB[j], a4[0][(kc + j) % NA]);

@@ -49,7 +49,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
     const uint32_t HD = (uint32_t)NH * D;
     const size_t wx_step = (size_t)B * G * HD * ESZ, st_step = (size_t)S * B * HD * 4, c_step = (size_t)B * HD * REC;
     const uint32_t st_state = (uint32_t)B * HD * 4;
-    const TileLds L = tile_lds(BT, G, S, D, NT, DK * 2, 0, 0, 0);
+    const TileLds L = tile_lds(BT, G, S, D, NT, DK * 2);
     const uint32_t BUF = BT * L.hp, OUT_PITCH = L.st_pitch + L.c_pitch;
     const uint32_t tid16 = (uint32_t)tid * 16, NT16 = (uint32_t)NT * 16;
     char* hbuf = smem;
