@@ -13,12 +13,13 @@
  *                                                                          [Sec. 4, eq. (3),(4)]
  *             dx_t = dg_t ; db = sum_t dg_t ; dR = sum_t dg_t s0_{t-1}^T    [Sec. 4, eq. (5)-(7)]
  *   heads     R is block diagonal: NH independent heads of size D          [Sec. 4.2]
- *   cells     LSTM, GRU, sLSTM point-wise functions P                       [App. A]
+ *   cells     LSTM, GRU, sLSTM, Elman point-wise functions P                [App. A]
  *
  * Readings of the paper taken here (each one is listed again in the design notes):
  *   - eq. (4) and (7) are printed with the time index of dg / s0 shifted by one; because g_t depends
  *     on s0_{t-1} (eq. (1)) the chain rule gives  ds0_{t-1} += R^T dg_t  and  dR = sum_t dg_t s0_{t-1}^T.
  *   - gate order on the G axis: LSTM and sLSTM  i, f, z, o ; GRU  r, z, n.   State order h, c, n, m.
+ *   - Elman network (App. A): one state, one gate, h_t = tanh(x_t + R h_{t-1} + b).
  *   - sLSTM equations (App. A) have unbalanced parentheses; read as
  *       m_t = max(log sig(f) + m_{t-1}, i)
  *       c_t = exp(log sig(f) + m_{t-1} - m_t) c_{t-1} + exp(i - m_t) tanh(z)
@@ -44,10 +45,10 @@
 #include <omp.h>
 #endif
 
-enum { CELL_LSTM = 0, CELL_GRU = 1, CELL_SLSTM = 2 };
+enum { CELL_LSTM = 0, CELL_GRU = 1, CELL_SLSTM = 2, CELL_ELMAN = 3 };
 
-static int n_states(int cell) { return cell == CELL_LSTM ? 2 : cell == CELL_GRU ? 1 : cell == CELL_SLSTM ? 4 : -1; }
-static int n_gates(int cell) { return cell == CELL_LSTM ? 4 : cell == CELL_GRU ? 3 : cell == CELL_SLSTM ? 4 : -1; }
+static int n_states(int cell) { return cell == CELL_LSTM ? 2 : cell == CELL_GRU ? 1 : cell == CELL_SLSTM ? 4 : cell == CELL_ELMAN ? 1 : -1; }
+static int n_gates(int cell) { return cell == CELL_LSTM ? 4 : cell == CELL_GRU ? 3 : cell == CELL_SLSTM ? 4 : cell == CELL_ELMAN ? 1 : -1; }
 
 int oracle_num_states(int cell) { return n_states(cell); }
 int oracle_num_gates(int cell) { return n_gates(cell); }
@@ -125,6 +126,8 @@ int oracle_fwd(int cell, int T, int B, int NH, int D, const double* Wx, const do
                             ST(t, 2, bb, n, e) = nn;
                             ST(t, 3, bb, n, e) = m;
                             ST(t, 0, bb, n, e) = sigm(po) * c / nn;
+                        } else if (cell == CELL_ELMAN) {
+                            ST(t, 0, bb, n, e) = tanh(WX(t - 1, bb, 0, n, e) + y[e] + BI(n, 0, e));
                         } else { /* GRU */
                             const double pr = WX(t - 1, bb, 0, n, e) + y[0 * D + e] + BI(n, 0, e);
                             const double pz = WX(t - 1, bb, 1, n, e) + y[1 * D + e] + BI(n, 1, e);
@@ -216,6 +219,12 @@ int oracle_bwd(int cell, int T, int B, int NH, int D, const double* Wx, const do
                             DS(1, bb, n, e) = dc * fg;
                             DS(2, bb, n, e) = dn * fg;
                             DS(0, bb, n, e) = 0.0;
+                        } else if (cell == CELL_ELMAN) {
+                            const double h = tanh(WX(t - 1, bb, 0, n, e) + y[e] + BI(n, 0, e));
+                            const double dpre = dh * (1.0 - h * h);
+                            DWX(t - 1, bb, 0, n, e) = dpre;
+                            DG(bb, 0, n, e) = dpre;
+                            DS(0, bb, n, e) = 0.0; /* h_{t-1} enters step t only through R */
                         } else { /* GRU */
                             const double r = sigm(WX(t - 1, bb, 0, n, e) + y[0 * D + e] + BI(n, 0, e));
                             const double z = sigm(WX(t - 1, bb, 1, n, e) + y[1 * D + e] + BI(n, 1, e));

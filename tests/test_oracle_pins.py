@@ -13,10 +13,10 @@ import pytest
 import torch
 
 import oracle
-from oracle import CELL_GRU, CELL_LSTM, CELL_SLSTM
+from oracle import CELL_ELMAN, CELL_GRU, CELL_LSTM, CELL_SLSTM
 
 GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
-CELLS = [CELL_LSTM, CELL_GRU, CELL_SLSTM]
+CELLS = [CELL_LSTM, CELL_GRU, CELL_SLSTM, CELL_ELMAN]
 
 
 def _rand(cell, T, B, NH, D, seed, rscale=0.6, with_s0=True):
@@ -47,7 +47,7 @@ def _read_golden(name):
 
 
 # ----------------------------------------------------------------------------------------------
-# library special cases: NH = 1 reduces LSTM / GRU to the textbook cells (Sec. 3, App. A)
+# library special cases: NH = 1 reduces LSTM / GRU / Elman to the textbook cells (Sec. 3, App. A)
 # ----------------------------------------------------------------------------------------------
 def _torch_rnn_reference(kind, Wx, R, b, s0, dH):
     """Run torch's CPU nn.LSTM / nn.GRU in float64 with W_ih = identity so that its input is the
@@ -55,7 +55,7 @@ def _torch_rnn_reference(kind, Wx, R, b, s0, dH):
     gradients (dWx, dR, db, dh0, dc0)."""
     T, B, G, NH, D = Wx.shape
     assert NH == 1
-    mod = (torch.nn.LSTM if kind == "lstm" else torch.nn.GRU)(G * D, D, bias=True).double()
+    mod = {"lstm": torch.nn.LSTM, "gru": torch.nn.GRU, "elman": torch.nn.RNN}[kind](G * D, D, bias=True).double()   # nn.RNN: tanh
     x = torch.tensor(Wx.reshape(T, B, G * D), requires_grad=True)
     # torch: weight_hh[g*D + e, d] multiplies h[d] into gate g of unit e;  ours: R[0, d, g, e]
     w_hh = torch.tensor(np.ascontiguousarray(R[0].transpose(1, 2, 0)).reshape(G * D, D), requires_grad=True)
@@ -81,7 +81,7 @@ def _torch_rnn_reference(kind, Wx, R, b, s0, dH):
         dWx, dR, db, dh0, dc0
 
 
-@pytest.mark.parametrize("kind,cell", [("lstm", CELL_LSTM), ("gru", CELL_GRU)])
+@pytest.mark.parametrize("kind,cell", [("lstm", CELL_LSTM), ("gru", CELL_GRU), ("elman", CELL_ELMAN)])
 def test_matches_torch_cpu_library_cell_fp64(kind, cell):
     """Catches: wrong gate order, transposed R, GRU bias outside the r-product, z applied to the wrong
     term, any wrong Jacobian term, the time index of dR / R^T dg."""
