@@ -27,7 +27,7 @@
 extern "C" {
 #endif
 
-typedef enum { FLASHRNN_LSTM = 0, FLASHRNN_GRU = 1, FLASHRNN_SLSTM = 2 } flashrnn_cell_t;
+typedef enum { FLASHRNN_LSTM = 0, FLASHRNN_GRU = 1, FLASHRNN_SLSTM = 2, FLASHRNN_ELMAN = 3 } flashrnn_cell_t;
 typedef enum { FLASHRNN_F32 = 0, FLASHRNN_BF16 = 1 } flashrnn_dtype_t;
 
 typedef enum {

@@ -20,8 +20,8 @@ constexpr int kXcds = 8;            // accelerator dies a workgroup index cycles
 constexpr size_t kAlign = 256;
 
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
-inline int num_states(int cell) { return cell == FLASHRNN_LSTM ? 2 : cell == FLASHRNN_GRU ? 1 : cell == FLASHRNN_SLSTM ? 4 : -1; }
-inline int num_gates(int cell) { return cell == FLASHRNN_LSTM ? 4 : cell == FLASHRNN_GRU ? 3 : cell == FLASHRNN_SLSTM ? 4 : -1; }
+inline int num_states(int cell) { return cell == FLASHRNN_LSTM ? 2 : cell == FLASHRNN_GRU ? 1 : cell == FLASHRNN_SLSTM ? 4 : cell == FLASHRNN_ELMAN ? 1 : -1; }
+inline int num_gates(int cell) { return cell == FLASHRNN_LSTM ? 4 : cell == FLASHRNN_GRU ? 3 : cell == FLASHRNN_SLSTM ? 4 : cell == FLASHRNN_ELMAN ? 1 : -1; }
 inline int num_cached(int cell) { return cell == FLASHRNN_SLSTM ? 5 : 4; }
 inline size_t io_size(int dt) { return dt == FLASHRNN_BF16 ? 2 : 4; }
 
@@ -45,6 +45,7 @@ KernelTable table_for(int cell, int dt) {
     switch (cell) {
         case FLASHRNN_LSTM: return bf ? table_lstm_bf16() : table_lstm_f32();
         case FLASHRNN_GRU: return bf ? table_gru_bf16() : table_gru_f32();
+        case FLASHRNN_ELMAN: return bf ? table_elman_bf16() : table_elman_f32();
         default: return bf ? table_slstm_bf16() : table_slstm_f32();
     }
 }
@@ -121,7 +122,7 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
             const int dk = e.KT * kstep, nw = e.tile == 1 ? units16 : units16 / e.eb;
             size_t smem = (size_t)2 * e.BT * (dk + (bf ? 8 : 4)) * (bf ? 2 : 4);
             if (e.tile == 1 && bwd) {
-                const int nsb = d->cell == FLASHRNN_SLSTM ? 2 : 1, go = d->cell == FLASHRNN_GRU ? G + 1 : G;
+                const int nsb = d->cell == FLASHRNN_SLSTM ? 2 : d->cell == FLASHRNN_ELMAN ? 0 : 1, go = d->cell == FLASHRNN_GRU ? G + 1 : G;
                 smem = tile_lds_bwd(e.BT, go, nsb, d->D, dk * 2, e.eb).total;
             } else if (e.tile == 1) {
                 smem = tile_lds(e.BT, G, num_states(d->cell), d->D, 64 * nw, dk * 2).total_fwd;

@@ -1,0 +1,9 @@
+// Persistent-kernel instantiations: elman, bf16 I/O.
+#define FRNN_CELL flashrnn::CELL_ELMAN
+#define FRNN_G 1
+#define FRNN_BF16 1
+#include "flashrnn_inst.h"
+
+namespace flashrnn {
+KernelTable table_elman_bf16() { return KernelTable{kEntries, (int)(sizeof(kEntries) / sizeof(kEntries[0]))}; }
+}  // namespace flashrnn

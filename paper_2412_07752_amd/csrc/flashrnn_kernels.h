@@ -13,7 +13,7 @@
 namespace flashrnn {
 
 // ---------------------------------------------------------------------------------------------
-// point-wise functions (paper App. A); gate order i,f,z,o (LSTM, sLSTM) and r,z,n (GRU)
+// point-wise functions (paper App. A); gate order i,f,z,o (LSTM, sLSTM) and r,z,n (GRU); Elman has one gate
 // ---------------------------------------------------------------------------------------------
 template <int CELL, bool FAST> struct Cell;
 
@@ -115,6 +115,21 @@ template <bool FAST> struct Cell<CELL_GRU, FAST> {
         dg[0] = dr; dg[1] = dz; dg[2] = dpre * r;
         ds[0] = dh * z;  // direct path h_{t-1} -> h_t
         (void)sc;
+    }
+};
+
+template <bool FAST> struct Cell<CELL_ELMAN, FAST> {
+    // st = {h}: h_t = tanh(x_t + R h_{t-1} + b)
+    static __device__ __forceinline__ void fwd(const float (&wx)[1], const float (&yb)[1], float (&st)[1], float (&cv)[1]) {
+        st[0] = tanh_<FAST>(wx[0] + yb[0]);
+        cv[0] = st[0];
+    }
+    static __device__ __forceinline__ void bwd(const float (&cv)[1], const float (&sc)[1], const float (&sp)[1], float (&ds)[1],
+                                               float (&dwx)[1], float (&dg)[1]) {
+        dg[0] = ds[0] * (1.0f - cv[0] * cv[0]);
+        dwx[0] = dg[0];
+        ds[0] = 0.0f;   // h_{t-1} enters the step only through R
+        (void)sc; (void)sp;
     }
 };
 

@@ -258,7 +258,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
     constexpr int PP = BT / 4;
     constexpr int ESZ = 2;
     constexpr int KT = KTW * EBK, DK = KT * 32;
-    constexpr int NSB = CELL == CELL_SLSTM ? 2 : 1;   // state rows the Jacobian needs per time level ...
+    constexpr int NSB = CELL == CELL_SLSTM ? 2 : CELL == CELL_ELMAN ? 0 : 1;   // state rows the Jacobian needs per time level ...
     constexpr int SB0 = CELL == CELL_GRU ? 0 : 1;     // ... starting at this state
     constexpr int GO = CELL == CELL_GRU ? G + 1 : G;  // output rows per batch row: dWx (+ the recurrent-side candidate gradient)
     constexpr int NA = EBK == 1 ? 4 : (EBK == 2 ? 2 : 1);   // accumulators per block: independent MFMAs in flight

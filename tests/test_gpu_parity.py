@@ -9,10 +9,10 @@ import torch
 
 import parity_util as pu
 from paper_2412_07752_amd import api, synth
-from paper_2412_07752_amd.synth import CELL_GRU, CELL_LSTM, CELL_SLSTM, Workload
+from paper_2412_07752_amd.synth import CELL_ELMAN, CELL_GRU, CELL_LSTM, CELL_SLSTM, Workload
 
 pytestmark = pytest.mark.gpu
-CELLS = [CELL_LSTM, CELL_GRU, CELL_SLSTM]
+CELLS = [CELL_LSTM, CELL_GRU, CELL_SLSTM, CELL_ELMAN]
 PLAN_ENV = ("FLASHRNN_MULTI", "FLASHRNN_BT", "FLASHRNN_NWU", "FLASHRNN_KS", "FLASHRNN_GPAR", "FLASHRNN_SPIN_LIMIT", "FLASHRNN_EBK",
             "FLASHRNN_KIND")
 
@@ -58,7 +58,7 @@ def test_one_workgroup_per_group(cell, dtype, D):
 @pytest.mark.parametrize("bt", [16, 8, 4])
 def test_batch_tiles(cell, bt):
     """Batch tiles of 16, 8 and 4 rows (idle MFMA lanes take over point-wise work); 21 rows = ragged last tile."""
-    w = Workload(f"bt{bt}_{cell}", cell, 11, 21, 3, 64, "bf16", True, bias="forget3" if cell != CELL_GRU else "uniform0.1",
+    w = Workload(f"bt{bt}_{cell}", cell, 11, 21, 3, 64, "bf16", True, bias="forget3" if cell in (CELL_LSTM, CELL_SLSTM) else "uniform0.1",
                  init="uniform0.1", seed=bt)
     _check(w, {"FLASHRNN_BT": str(bt)}, with_dlast=True)
 
