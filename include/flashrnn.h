@@ -15,8 +15,8 @@
  *   - Calls that share a workspace must not overlap in time.
  *
  * Index names:  T time steps, B batch, NH heads, D units per head, G gates, S states.
- *   Gate order on the G axis:  LSTM, sLSTM: i, f, z, o     GRU: r, z, n
- *   State order on the S axis: LSTM: h, c     GRU: h     sLSTM: h, c, n, m   (paper App. A)
+ *   Gate order on the G axis:  LSTM, sLSTM: i, f, z, o     GRU: r, z, n     Elman: one gate
+ *   State order on the S axis: LSTM: h, c     GRU: h     sLSTM: h, c, n, m     Elman: h   (paper App. A)
  */
 #ifndef FLASHRNN_H
 #define FLASHRNN_H
