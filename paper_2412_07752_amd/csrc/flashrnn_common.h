@@ -54,7 +54,6 @@ struct TileLds {
     uint32_t rp_io, rp_st;                    // image row pitches: bf16 rows, f32 rows
     uint32_t in_bytes, in_pitch;              // inputs Wx (BT*G rows)
     uint32_t st_bytes, st_pitch;              // f32 state rows
-    uint32_t c_bytes, c_pitch, rec_pitch;     // saved-values records: BT rows of D records of 16 bytes, rows rec_pitch apart
     uint32_t total_fwd;
 };
 __host__ __device__ inline uint32_t div_up(uint32_t a, uint32_t b) { return (a + b - 1) / b; }
@@ -67,11 +66,8 @@ __host__ __device__ inline TileLds tile_lds(int BT, int G, int S, int D, int NT,
     L.in_pitch = L.in_bytes + div_up((uint32_t)BT * G * (D / 8), NT) * nt16;
     L.st_bytes = (uint32_t)BT * S * L.rp_st;
     L.st_pitch = L.st_bytes + div_up((uint32_t)BT * S * (D / 4), NT) * nt16;
-    L.rec_pitch = lds_row_pitch((uint32_t)D * 16);
-    L.c_bytes = (uint32_t)BT * L.rec_pitch;
-    L.c_pitch = div_up(div_up((uint32_t)BT * D, NT) * NT, D) * L.rec_pitch;   // rows that the copy-out chunks of all threads touch
     L.hp = lds_row_pitch((uint32_t)k_bytes_fwd);
-    L.total_fwd = 2 * BT * L.hp + 2 * L.in_pitch + 2 * (L.st_pitch + L.c_pitch);
+    L.total_fwd = 2 * BT * L.hp + 2 * L.in_pitch + 2 * L.st_pitch;
     return L;
 }
 

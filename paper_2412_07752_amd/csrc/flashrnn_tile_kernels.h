@@ -31,7 +31,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
     constexpr int PP = BT / 4;
     constexpr int ESZ = 2;
     constexpr int DK = KT * 32;
-    constexpr int NCH_IN = (BT * G + 31) / 32, NCH_ST = (BT * S + 15) / 16, NCH_C = (BT + 3) / 4;
+    constexpr int NCH_IN = (BT * G + 31) / 32, NCH_ST = (BT * S + 15) / 16;
     constexpr uint32_t kDrop = 0x80000000u;
     constexpr uint32_t REC = kCacheSlots * ESZ;
     static_assert(BT == 4 || BT == 8, "batch tiles of 4 or 8 rows");
@@ -50,7 +50,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
     const size_t wx_step = (size_t)B * G * HD * ESZ, st_step = (size_t)S * B * HD * 4, c_step = (size_t)B * HD * REC;
     const uint32_t st_state = (uint32_t)B * HD * 4;
     const TileLds L = tile_lds(BT, G, S, D, NT, DK * 2);
-    const uint32_t BUF = BT * L.hp, OUT_PITCH = L.st_pitch + L.c_pitch;
+    const uint32_t BUF = BT * L.hp, OUT_PITCH = L.st_pitch;
     const uint32_t tid16 = (uint32_t)tid * 16, NT16 = (uint32_t)NT * 16;
     char* hbuf = smem;
     char* in_img = smem + 2 * BUF;
@@ -76,7 +76,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
     const uint32_t voff_st = ((uint32_t)bb * HD + e0) * 4;
 
     // ---- chunk roles: global byte offset (out of range = nothing to move) and LDS offset inside the image
-    uint32_t cin_g[NCH_IN], cin_l[NCH_IN], cst_g[NCH_ST], cst_l[NCH_ST], cc_g[NCH_C], cc_l[NCH_C];
+    uint32_t cin_g[NCH_IN], cin_l[NCH_IN], cst_g[NCH_ST], cst_l[NCH_ST];
     {
         const uint32_t cpr_io = (uint32_t)D / 8, cpr_st = (uint32_t)D / 4;
 #pragma unroll
@@ -93,17 +93,12 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
             cst_g[k2] = (in && brow < (uint32_t)B) ? s * st_state + (brow * HD) * 4 + ch * 16 : kDrop;
             cst_l[k2] = in ? row * L.rp_st + ch * 16 : L.st_bytes + tid16 + k2 * NT16;
         }
-#pragma unroll
-        for (int k2 = 0; k2 < NCH_C; ++k2) {  // records: chunk idx = slot * D + unit
-            const uint32_t idx = tid + k2 * NT, row = idx / (uint32_t)D, u = idx % (uint32_t)D, brow = q * BT + row;
-            cc_g[k2] = (row < (uint32_t)BT && brow < (uint32_t)B && p.cache != nullptr) ? (brow * HD + u) * REC : kDrop;
-            cc_l[k2] = L.st_pitch + row * L.rec_pitch + u * REC;
-        }
     }
-    // this lane's places: inputs row = slot*G + g, states row = s*BT + slot, records row = slot
+    // this lane's places: inputs row = slot*G + g, states row = s*BT + slot; the saved-values records (16 bytes per
+    // lane, 256 contiguous bytes per batch row and wave) go to HBM straight from the lanes
     const uint32_t l_in = (uint32_t)lm.bslot * G * L.rp_io + e0 * ESZ;
     const uint32_t l_st = (uint32_t)lm.bslot * L.rp_st + e0 * 4;
-    const uint32_t l_c = L.st_pitch + (uint32_t)lm.bslot * L.rec_pitch + e0 * REC;
+    const uint32_t voff_c = (row_valid && p.cache != nullptr) ? ((uint32_t)bb * HD + e0) * REC : kDrop;
     const uint32_t lds_row = (uint32_t)lm.bslot * L.hp;
 
     // ---- initial states: slot 0 is written directly (once)
@@ -126,22 +121,17 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
     }
     __syncthreads();
 
-    // move the image of the outputs of step j to HBM: states slot j, saved values slot j - 1
-    auto copy_out_load = [&](int j, i32x4 (&vs)[NCH_ST], i32x4 (&vc)[NCH_C]) {
+    // move the image of the states after step j to HBM (slot j)
+    auto copy_out_load = [&](int j, i32x4 (&vs)[NCH_ST]) {
         const char* img = out_img + (j & 1) * OUT_PITCH;
 #pragma unroll
         for (int k2 = 0; k2 < NCH_ST; ++k2) vs[k2] = *(const i32x4*)(img + cst_l[k2]);
-#pragma unroll
-        for (int k2 = 0; k2 < NCH_C; ++k2) vc[k2] = *(const i32x4*)(img + cc_l[k2]);
     };
-    auto copy_out_store = [&](int j, const i32x4 (&vs)[NCH_ST], const i32x4 (&vc)[NCH_C]) {
+    auto copy_out_store = [&](int j, const i32x4 (&vs)[NCH_ST]) {
         const uint32_t none = j < 1 ? kDrop : 0u;
         const rsrc_t rs_st = make_rsrc(st_g + (size_t)(j < 1 ? 0 : j) * st_step);
-        const rsrc_t rs_c = make_rsrc(c_g + (size_t)(j < 1 ? 0 : j - 1) * c_step);
 #pragma unroll
         for (int k2 = 0; k2 < NCH_ST; ++k2) __builtin_amdgcn_raw_buffer_store_b128(vs[k2], rs_st, cst_g[k2] | none, 0, 0);
-#pragma unroll
-        for (int k2 = 0; k2 < NCH_C; ++k2) __builtin_amdgcn_raw_buffer_store_b128(vc[k2], rs_c, cc_g[k2] | none, 0, 0);
     };
     for (int t = 1; t <= T; ++t) {
         // The MFMA chain of the step, k-step by k-step, with the work that is off the dependency chain
@@ -151,7 +141,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
         const char* hrow = hbuf + ((t - 1) & 1) * BUF + lds_row;
 #pragma unroll
         for (int kt = 0; kt < H1; ++kt) hB[kt] = *(const bf16x8*)(hrow + (size_t)(kt * 32 + lm.quad * 8) * 2);
-        i32x4 pre[NCH_IN], vs[NCH_ST], vc[NCH_C];
+        i32x4 pre[NCH_IN], vs[NCH_ST];
         {
             const rsrc_t rsn = make_rsrc(wx_g + (size_t)(t < T ? t : T - 1) * wx_step);
 #pragma unroll
@@ -170,7 +160,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
             for (int g = 0; g < G; ++g) acc[g] = OP::mfma(Rf[g][1], hB[1], acc[g]);
         }
         pin_order();
-        copy_out_load(t - 1, vs, vc);          // outputs of step t-1: image -> registers
+        copy_out_load(t - 1, vs);          // outputs of step t-1: image -> registers
         float wx[G][PP];
         {
             const char* im = in_img + (t & 1) * L.in_pitch + l_in;   // this step's inputs from their image
@@ -183,7 +173,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
             for (int g = 0; g < G; ++g) acc[g] = OP::mfma(Rf[g][2], hB[2], acc[g]);
         }
         pin_order();
-        copy_out_store(t - 1, vs, vc);         // ... -> HBM
+        copy_out_store(t - 1, vs);         // ... -> HBM
         pin_order();
         // The next step's inputs go from registers to their image: with a long chain they have arrived by now and
         // the writes stay out of the step's tail; with a short chain waiting here would stall it (measured both ways).
@@ -202,6 +192,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
 #pragma unroll
         for (int g = 0; g < G; ++g) compact_tile<BT>(acc[g]);
         char* oimg = out_img + (t & 1) * OUT_PITCH;
+        const rsrc_t rs_c = make_rsrc(c_g + (size_t)(t - 1) * c_step);
 #pragma unroll
         for (int i = 0; i < PP; ++i) {
             float wxi[G], ybi[G], sti[S], cvi[NC];
@@ -212,11 +203,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
             Cell<CELL, true>::fwd(wxi, ybi, sti, cvi);
 #pragma unroll
             for (int s = 0; s < S; ++s) st[s][i] = sti[s];
-            float wv[kCacheSlots];
-#pragma unroll
-            for (int c2 = 0; c2 < kCacheSlots; ++c2) wv[c2] = c2 < NC ? cvi[c2 < NC ? c2 : 0] : 0.0f;
-            *(i32x4*)(oimg + l_c + i * REC) = i32x4{(int)pack_bf16x2(wv[0], wv[1]), (int)pack_bf16x2(wv[2], wv[3]),
-                                                    (int)pack_bf16x2(wv[4], wv[5]), (int)pack_bf16x2(wv[6], wv[7])};
+            store_record<true, NC>(rs_c, voff_c + i * REC, 0, cvi);
         }
         write_operand_lds<true, PP>(hbuf + (t & 1) * BUF + lds_row, e0, st[0]);
 #pragma unroll
@@ -230,9 +217,9 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
     }
     // ---- drain: outputs of step T
     if (T > 0) {
-        i32x4 vs[NCH_ST], vc[NCH_C];
-        copy_out_load(T, vs, vc);
-        copy_out_store(T, vs, vc);
+        i32x4 vs[NCH_ST];
+        copy_out_load(T, vs);
+        copy_out_store(T, vs);
     }
 }
 
