@@ -134,14 +134,25 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
         for (int k2 = 0; k2 < NCH_ST; ++k2) __builtin_amdgcn_raw_buffer_store_b128(vs[k2], rs_st, cst_g[k2] | none, 0, 0);
     };
     for (int t = 1; t <= T; ++t) {
-        // The MFMA chain of the step, k-step by k-step, with the work that is off the dependency chain
-        // issued in between (the sched barriers keep the compiler from bunching it up in front).
-        constexpr int H1 = KT < 3 ? KT : 3;   // operand k-steps fetched up front
+        // The MFMA chain of the step, k-step by k-step, and the work off the dependency chain: this step's inputs out of
+        // their image, the state rows of the previous step on their way to HBM, the next step's inputs into their image
+        // (the sched barriers keep the compiler from bunching it all up in front).  With a long chain (KT >= 6) that
+        // work sits between the k-steps; with a short one all LDS reads go out together at the top of the step (one
+        // latency) and the next inputs are parked at its end, where they have had time to arrive (measured both ways).
+        constexpr bool kLongChain = KT >= 6;
         bf16x8 hB[KT];
         const char* hrow = hbuf + ((t - 1) & 1) * BUF + lds_row;
 #pragma unroll
-        for (int kt = 0; kt < H1; ++kt) hB[kt] = *(const bf16x8*)(hrow + (size_t)(kt * 32 + lm.quad * 8) * 2);
+        for (int kt = 0; kt < KT; ++kt) hB[kt] = *(const bf16x8*)(hrow + (size_t)(kt * 32 + lm.quad * 8) * 2);
         i32x4 pre[NCH_IN], vs[NCH_ST];
+        float wx[G][PP];
+        auto side_reads = [&]() {
+            const char* im = in_img + (t & 1) * L.in_pitch + l_in;
+#pragma unroll
+            for (int g = 0; g < G; ++g) load_io<true, PP>(im + (uint32_t)g * L.rp_io, 0, wx[g]);
+            copy_out_load(t - 1, vs);
+        };
+        if constexpr (!kLongChain) side_reads();
         {
             const rsrc_t rsn = make_rsrc(wx_g + (size_t)(t < T ? t : T - 1) * wx_step);
 #pragma unroll
@@ -152,33 +163,24 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
 #pragma unroll
         for (int g = 0; g < G; ++g) acc[g] = OP::mfma(Rf[g][0], hB[0], f32x4{0.f, 0.f, 0.f, 0.f});
         pin_order();
+        if constexpr (!kLongChain) {
+            copy_out_store(t - 1, vs);
+            pin_order();
 #pragma unroll
-        for (int kt = H1; kt < KT; ++kt) hB[kt] = *(const bf16x8*)(hrow + (size_t)(kt * 32 + lm.quad * 8) * 2);
-        pin_order();
-        if constexpr (KT > 1) {
+            for (int kt = 1; kt < (KT < 3 ? KT : 3); ++kt)
+#pragma unroll
+                for (int g = 0; g < G; ++g) acc[g] = OP::mfma(Rf[g][kt], hB[kt], acc[g]);
+        } else {
 #pragma unroll
             for (int g = 0; g < G; ++g) acc[g] = OP::mfma(Rf[g][1], hB[1], acc[g]);
-        }
-        pin_order();
-        copy_out_load(t - 1, vs);          // outputs of step t-1: image -> registers
-        float wx[G][PP];
-        {
-            const char* im = in_img + (t & 1) * L.in_pitch + l_in;   // this step's inputs from their image
-#pragma unroll
-            for (int g = 0; g < G; ++g) load_io<true, PP>(im + (uint32_t)g * L.rp_io, 0, wx[g]);
-        }
-        pin_order();
-        if constexpr (KT > 2) {
+            pin_order();
+            side_reads();
+            pin_order();
 #pragma unroll
             for (int g = 0; g < G; ++g) acc[g] = OP::mfma(Rf[g][2], hB[2], acc[g]);
-        }
-        pin_order();
-        copy_out_store(t - 1, vs);         // ... -> HBM
-        pin_order();
-        // The next step's inputs go from registers to their image: with a long chain they have arrived by now and
-        // the writes stay out of the step's tail; with a short chain waiting here would stall it (measured both ways).
-        constexpr bool kParkEarly = KT >= 6;
-        if constexpr (kParkEarly) {
+            pin_order();
+            copy_out_store(t - 1, vs);
+            pin_order();
             char* im = in_img + ((t + 1) & 1) * L.in_pitch;
 #pragma unroll
             for (int k2 = 0; k2 < NCH_IN; ++k2) *(i32x4*)(im + cin_l[k2]) = pre[k2];
@@ -208,7 +210,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
         write_operand_lds<true, PP>(hbuf + (t & 1) * BUF + lds_row, e0, st[0]);
 #pragma unroll
         for (int s = 0; s < S; ++s) store_io<false, PP>(oimg + l_st + (uint32_t)s * BT * L.rp_st, 0, st[s]);
-        if constexpr (!kParkEarly) {
+        if constexpr (!kLongChain) {
             char* im = in_img + ((t + 1) & 1) * L.in_pitch;
 #pragma unroll
             for (int k2 = 0; k2 < NCH_IN; ++k2) *(i32x4*)(im + cin_l[k2]) = pre[k2];
