@@ -383,6 +383,24 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
         load_io<true, PP>(img + l_dh, 0, dh_ext);
     };
 
+    // sLSTM: the factors of the Jacobian that do not depend on dh_t are formed as soon as the step's saved values and
+    // states are in registers (in the shadow of the previous step's MFMAs), which leaves a dozen operations for the
+    // point-wise phase, where all waves compete for the VALU.  kc = {o/n, o c/n^2, ig (1 - z^2), fg sig(-f), (c/n) o (1 - o)}
+    constexpr bool kPre = CELL == CELL_SLSTM;
+    float kc[5][PP];
+    auto precompute = [&]() {
+        if constexpr (kPre) {
+#pragma unroll
+            for (int i = 0; i < PP; ++i) {
+                const float inv = fast_rcp(sc[2][i]), q = sc[1][i] * inv, o = cv[3][i], z = cv[2][i], oi = o * inv;
+                kc[0][i] = oi;
+                kc[1][i] = oi * q;
+                kc[2][i] = cv[0][i] * (1.0f - z * z);
+                kc[3][i] = cv[1][i] * cv[4][i];
+                kc[4][i] = q * o * (1.0f - o);
+            }
+        }
+    };
     // ---- prologue: images of steps T and T-1, this lane's inputs of step T, the states after step T
 #pragma unroll
     for (int s = 0; s < S; ++s) {
@@ -398,7 +416,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
     __syncthreads();
-    if (T > 0) take(T);
+    if (T > 0) { take(T); precompute(); }
 
     float dbv[G][PP];   // the db sums, read back ahead of each point-wise phase
 #pragma unroll
@@ -417,7 +435,19 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
 #pragma unroll
                 for (int s = 0; s < S; ++s) { sci[s] = sc[s][i]; spi[s] = sp[s][i]; dsi[s] = ds[s][i]; }
                 dsi[0] += dh_ext[i];
-                Cell<CELL, true>::bwd(cvi, sci, spi, dsi, dwxi, dgi);
+                if constexpr (kPre) {
+                    const float dh = dsi[0];
+                    const float dc = fmaf(dh, kc[0][i], dsi[1]), dn = fmaf(-dh, kc[1][i], dsi[2]);
+                    dgi[0] = fmaf(dc, cvi[2], dn) * cvi[0];
+                    dgi[1] = fmaf(dc, spi[1], dn * spi[2]) * kc[3][i];
+                    dgi[2] = dc * kc[2][i];
+                    dgi[3] = dh * kc[4][i];
+#pragma unroll
+                    for (int g = 0; g < G; ++g) dwxi[g] = dgi[g];
+                    dsi[0] = 0.0f; dsi[1] = dc * cvi[1]; dsi[2] = dn * cvi[1]; dsi[3] = 0.0f;
+                } else {
+                    Cell<CELL, true>::bwd(cvi, sci, spi, dsi, dwxi, dgi);
+                }
 #pragma unroll
                 for (int s = 0; s < S; ++s) ds[s][i] = dsi[s];
 #pragma unroll
@@ -481,7 +511,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
             if (c == 0) {   // dWx_t out of its image and on its way, step t-1's values out of theirs
                 i32x4 o = i32x4{0, 0, 0, 0};
                 if (out_real) o = *(const i32x4*)(out_img + (t & 1) * L.out_pitch + cout_l);
-                if (t > 1) take(t - 1);
+                if (t > 1) { take(t - 1); precompute(); }
                 pin_order();
                 __builtin_amdgcn_raw_buffer_store_b128(o, make_rsrc(dwx_g + (size_t)(t - 1) * wx_step), cout_g, 0, 0);
                 if constexpr (CELL == CELL_GRU)
