@@ -383,21 +383,37 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
         load_io<true, PP>(img + l_dh, 0, dh_ext);
     };
 
-    // sLSTM: the factors of the Jacobian that do not depend on dh_t are formed as soon as the step's saved values and
-    // states are in registers (in the shadow of the previous step's MFMAs), which leaves a dozen operations for the
-    // point-wise phase, where all waves compete for the VALU.  kc = {o/n, o c/n^2, ig (1 - z^2), fg sig(-f), (c/n) o (1 - o)}
-    constexpr bool kPre = CELL == CELL_SLSTM;
+    // The factors of the Jacobian that do not depend on dh_t are formed as soon as the step's saved values and states
+    // are in registers (in the shadow of the previous step's MFMAs), which leaves a few multiply-adds for the point-wise
+    // phase, where all waves compete for the VALU.
+    //   sLSTM kc = {o/n, o c/n^2, ig (1 - z^2), fg sig(-f), (c/n) o (1 - o)}
+    //   LSTM  kc = {o (1 - tanh^2 c), z i (1 - i), c_prev f (1 - f), i (1 - z^2), tanh(c) o (1 - o)}
+    //   GRU   kc = {(1 - z)(1 - cand^2), (h_prev - cand) z (1 - z), kc0 yn r (1 - r), kc0 r}
+    constexpr bool kPre = CELL != CELL_ELMAN;
     float kc[5][PP];
     auto precompute = [&]() {
-        if constexpr (kPre) {
 #pragma unroll
-            for (int i = 0; i < PP; ++i) {
+        for (int i = 0; i < PP; ++i) {
+            if constexpr (CELL == CELL_SLSTM) {
                 const float inv = fast_rcp(sc[2][i]), q = sc[1][i] * inv, o = cv[3][i], z = cv[2][i], oi = o * inv;
                 kc[0][i] = oi;
                 kc[1][i] = oi * q;
                 kc[2][i] = cv[0][i] * (1.0f - z * z);
                 kc[3][i] = cv[1][i] * cv[4][i];
                 kc[4][i] = q * o * (1.0f - o);
+            } else if constexpr (CELL == CELL_LSTM) {
+                const float ig = cv[0][i], f = cv[1][i], z = cv[2][i], o = cv[3][i], tc = tanh_<true>(sc[1][i]);
+                kc[0][i] = o * (1.0f - tc * tc);
+                kc[1][i] = z * ig * (1.0f - ig);
+                kc[2][i] = sp[1][i] * f * (1.0f - f);
+                kc[3][i] = ig * (1.0f - z * z);
+                kc[4][i] = tc * o * (1.0f - o);
+            } else if constexpr (CELL == CELL_GRU) {
+                const float r = cv[0][i], z = cv[1][i], cand = cv[2][i], yn = cv[3][i];
+                kc[0][i] = (1.0f - z) * (1.0f - cand * cand);
+                kc[1][i] = (sp[0][i] - cand) * z * (1.0f - z);
+                kc[2][i] = kc[0][i] * yn * r * (1.0f - r);
+                kc[3][i] = kc[0][i] * r;
             }
         }
     };
@@ -437,14 +453,29 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
                 dsi[0] += dh_ext[i];
                 if constexpr (kPre) {
                     const float dh = dsi[0];
-                    const float dc = fmaf(dh, kc[0][i], dsi[1]), dn = fmaf(-dh, kc[1][i], dsi[2]);
-                    dgi[0] = fmaf(dc, cvi[2], dn) * cvi[0];
-                    dgi[1] = fmaf(dc, spi[1], dn * spi[2]) * kc[3][i];
-                    dgi[2] = dc * kc[2][i];
-                    dgi[3] = dh * kc[4][i];
+                    if constexpr (CELL == CELL_SLSTM) {
+                        const float dc = fmaf(dh, kc[0][i], dsi[1]), dn = fmaf(-dh, kc[1][i], dsi[2]);
+                        dgi[0] = fmaf(dc, cvi[2], dn) * cvi[0];
+                        dgi[1] = fmaf(dc, spi[1], dn * spi[2]) * kc[3][i];
+                        dgi[2] = dc * kc[2][i];
+                        dgi[3] = dh * kc[4][i];
+                        dsi[0] = 0.0f; dsi[1] = dc * cvi[1]; dsi[2] = dn * cvi[1]; dsi[3] = 0.0f;
+                    } else if constexpr (CELL == CELL_LSTM) {
+                        const float dc = fmaf(dh, kc[0][i], dsi[1]);
+                        dgi[0] = dc * kc[1][i];
+                        dgi[1] = dc * kc[2][i];
+                        dgi[2] = dc * kc[3][i];
+                        dgi[3] = dh * kc[4][i];
+                        dsi[0] = 0.0f; dsi[1] = dc * cvi[1];
+                    } else {   // GRU: the input side sees d(pre-tanh) in gate n, the recurrent side d(yn)
+                        dgi[0] = dh * kc[2][i];
+                        dgi[1] = dh * kc[1][i];
+                        dgi[2] = dh * kc[3][i];
+                        dsi[0] = dh * cvi[1];   // direct path h_{t-1} -> h_t
+                    }
 #pragma unroll
                     for (int g = 0; g < G; ++g) dwxi[g] = dgi[g];
-                    dsi[0] = 0.0f; dsi[1] = dc * cvi[1]; dsi[2] = dn * cvi[1]; dsi[3] = 0.0f;
+                    if constexpr (CELL == CELL_GRU) dwxi[2] = dh * kc[0][i];
                 } else {
                     Cell<CELL, true>::bwd(cvi, sci, spi, dsi, dwxi, dgi);
                 }
