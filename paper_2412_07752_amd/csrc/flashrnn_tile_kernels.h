@@ -151,6 +151,11 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
 #pragma unroll
             for (int g = 0; g < G; ++g) load_io<true, PP>(im + (uint32_t)g * L.rp_io, 0, wx[g]);
             copy_out_load(t - 1, vs);
+#pragma unroll
+            for (int g = 0; g < G; ++g)     // the bias joins the inputs here, off the step's tail (GRU's candidate bias
+#pragma unroll                      // belongs to the recurrent term that sig(r) multiplies: it stays with y)
+                for (int i = 0; i < PP; ++i)
+                    if (!(CELL == CELL_GRU && g == 2)) wx[g][i] += bias[g][i];
         };
         if constexpr (!kLongChain) side_reads();
         {
@@ -199,7 +204,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
         for (int i = 0; i < PP; ++i) {
             float wxi[G], ybi[G], sti[S], cvi[NC];
 #pragma unroll
-            for (int g = 0; g < G; ++g) { wxi[g] = wx[g][i]; ybi[g] = acc[g][i] + bias[g][i]; }
+            for (int g = 0; g < G; ++g) { wxi[g] = wx[g][i]; ybi[g] = (CELL == CELL_GRU && g == 2) ? acc[g][i] + bias[g][i] : acc[g][i]; }
 #pragma unroll
             for (int s = 0; s < S; ++s) sti[s] = st[s][i];
             Cell<CELL, true>::fwd(wxi, ybi, sti, cvi);
