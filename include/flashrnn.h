@@ -52,7 +52,7 @@ typedef struct {
     int io_dtype; /* flashrnn_dtype_t */
 } flashrnn_desc_t;
 
-/* Number of states / gates of a cell (paper App. A): LSTM 2 / 4, GRU 1 / 3, sLSTM 4 / 4; -1 if unknown. */
+/* Number of states / gates of a cell (paper App. A): LSTM 2 / 4, GRU 1 / 3, sLSTM 4 / 4, Elman 1 / 1; -1 if unknown. */
 int flashrnn_num_states(int cell);
 int flashrnn_num_gates(int cell);
 
@@ -107,7 +107,9 @@ int flashrnn_bwd(const flashrnn_desc_t* desc, const void* R, const void* b, cons
  * Reads the error word the kernels of the last call on this workspace left behind (synchronizes
  * the stream).  The spin limit of the cross-CU waits is 2^21 polls; the environment variable
  * FLASHRNN_SPIN_LIMIT overrides it (a negative value makes every wait give up at once, which
- * exercises this error path without hanging anything).  Returns FLASHRNN_OK, FLASHRNN_ERR_TIMEOUT
+ * exercises this error path without hanging anything).  The environment variables FLASHRNN_MULTI, _BT, _NWU,
+ * _KS, _GPAR, _EB, _EBK and _KIND override single choices of the launch planner; they exist for the tests that
+ * force every kernel family onto small shapes.  Returns FLASHRNN_OK, FLASHRNN_ERR_TIMEOUT
  * if a cross-CU wait ran into its spin limit (results are then invalid), or FLASHRNN_ERR_LAUNCH.
  * workspace may be NULL (returns OK).
  */
