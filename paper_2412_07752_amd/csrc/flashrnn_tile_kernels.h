@@ -12,6 +12,8 @@
 //     for HBM during the chain of step t+1; the inputs of step t+1 are fetched during the chain of step t.
 // Image rows are padded (lds_row_pitch) so that a wave's 4-rows x 16-units accesses hit 64 distinct banks.
 #pragma once
+#include <type_traits>
+
 #include "flashrnn_kernels.h"
 
 namespace flashrnn {
@@ -120,6 +122,19 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
         for (int k2 = 0; k2 < NCH_IN; ++k2) *(i32x4*)(in_img + L.in_pitch + cin_l[k2]) = __builtin_amdgcn_raw_buffer_load_b128(rs1, cin_g[k2], 0, 0);
     }
     __syncthreads();
+    // With a short chain a step is shorter than the HBM latency under load: the inputs are fetched two steps ahead
+    // there (two register sets in flight), one step ahead with a long chain.
+    constexpr bool kLongChain = KT >= 6;
+    i32x4 preA[NCH_IN], preB[NCH_IN];   // short chain: step t fetches into the set t & 1 and parks the other one
+    if constexpr (!kLongChain) {
+#pragma unroll
+        for (int k2 = 0; k2 < NCH_IN; ++k2) preA[k2] = preB[k2] = i32x4{0, 0, 0, 0};
+        if (T > 0) {   // (with T = 0 there is no Wx to touch)
+            const rsrc_t rs2 = make_rsrc(wx_g + (size_t)(T > 1 ? 1 : 0) * wx_step);
+#pragma unroll
+            for (int k2 = 0; k2 < NCH_IN; ++k2) preA[k2] = __builtin_amdgcn_raw_buffer_load_b128(rs2, cin_g[k2], 0, 0);   // Wx_2, parked at the end of step 1
+        }
+    }
 
     // move the image of the states after step j to HBM (slot j)
     auto copy_out_load = [&](int j, i32x4 (&vs)[NCH_ST]) {
@@ -133,13 +148,14 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
 #pragma unroll
         for (int k2 = 0; k2 < NCH_ST; ++k2) __builtin_amdgcn_raw_buffer_store_b128(vs[k2], rs_st, cst_g[k2] | none, 0, 0);
     };
-    for (int t = 1; t <= T; ++t) {
+    // one time step; PAR = t & 1 as a compile-time constant where it selects a register set
+    auto step = [&](auto par_c, const int t) {
+        constexpr int PAR = decltype(par_c)::value;
         // The MFMA chain of the step, k-step by k-step, and the work off the dependency chain: this step's inputs out of
         // their image, the state rows of the previous step on their way to HBM, the next step's inputs into their image
         // (the sched barriers keep the compiler from bunching it all up in front).  With a long chain (KT >= 6) that
         // work sits between the k-steps; with a short one all LDS reads go out together at the top of the step (one
         // latency) and the next inputs are parked at its end, where they have had time to arrive (measured both ways).
-        constexpr bool kLongChain = KT >= 6;
         bf16x8 hB[KT];
         const char* hrow = hbuf + ((t - 1) & 1) * BUF + lds_row;
 #pragma unroll
@@ -159,9 +175,18 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
         };
         if constexpr (!kLongChain) side_reads();
         {
-            const rsrc_t rsn = make_rsrc(wx_g + (size_t)(t < T ? t : T - 1) * wx_step);
+            const int ahead = kLongChain ? t : t + 1;   // slot of Wx_{t+1} / Wx_{t+2}
+            const rsrc_t rsn = make_rsrc(wx_g + (size_t)(ahead < T ? ahead : T - 1) * wx_step);
+            if constexpr (kLongChain) {
 #pragma unroll
-            for (int k2 = 0; k2 < NCH_IN; ++k2) pre[k2] = __builtin_amdgcn_raw_buffer_load_b128(rsn, cin_g[k2], 0, 0);
+                for (int k2 = 0; k2 < NCH_IN; ++k2) pre[k2] = __builtin_amdgcn_raw_buffer_load_b128(rsn, cin_g[k2], 0, 0);
+            } else if constexpr (PAR == 1) {
+#pragma unroll
+                for (int k2 = 0; k2 < NCH_IN; ++k2) preB[k2] = __builtin_amdgcn_raw_buffer_load_b128(rsn, cin_g[k2], 0, 0);
+            } else {
+#pragma unroll
+                for (int k2 = 0; k2 < NCH_IN; ++k2) preA[k2] = __builtin_amdgcn_raw_buffer_load_b128(rsn, cin_g[k2], 0, 0);
+            }
         }
         pin_order();
         f32x4 acc[G];
@@ -215,12 +240,27 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
         write_operand_lds<true, PP>(hbuf + (t & 1) * BUF + lds_row, e0, st[0]);
 #pragma unroll
         for (int s = 0; s < S; ++s) store_io<false, PP>(oimg + l_st + (uint32_t)s * BT * L.rp_st, 0, st[s]);
-        if constexpr (!kLongChain) {
+        if constexpr (!kLongChain) {   // park Wx_{t+1} (fetched during the previous step); Wx_{t+2} stays in flight
             char* im = in_img + ((t + 1) & 1) * L.in_pitch;
 #pragma unroll
-            for (int k2 = 0; k2 < NCH_IN; ++k2) *(i32x4*)(im + cin_l[k2]) = pre[k2];
+            for (int k2 = 0; k2 < NCH_IN; ++k2) {
+                if constexpr (PAR == 1) *(i32x4*)(im + cin_l[k2]) = preA[k2];
+                else *(i32x4*)(im + cin_l[k2]) = preB[k2];
+            }
         }
         __syncthreads();
+    };
+    using par0 = std::integral_constant<int, 0>;
+    using par1 = std::integral_constant<int, 1>;
+    if constexpr (kLongChain) {
+        for (int t = 1; t <= T; ++t) step(par0{}, t);
+    } else {
+        int t = 1;
+        for (; t + 1 <= T; t += 2) {
+            step(par1{}, t);
+            step(par0{}, t + 1);
+        }
+        if (t <= T) step(par1{}, t);
     }
     // ---- drain: outputs of step T
     if (T > 0) {
