@@ -12,6 +12,7 @@
  *   backward  dg_t = dP/dg * ds_t ; ds_{t-1} = dP/ds * ds_t (+ R^T dg_t for the hidden state)
  *                                                                          [Sec. 4, eq. (3),(4)]
  *             dx_t = dg_t ; db = sum_t dg_t ; dR = sum_t dg_t s0_{t-1}^T    [Sec. 4, eq. (5)-(7)]
+ *             optional value-wise clipping of the R^T dg_t term per step    [Sec. 4.1]
  *   heads     R is block diagonal: NH independent heads of size D          [Sec. 4.2]
  *   cells     LSTM, GRU, sLSTM, Elman point-wise functions P                [App. A]
  *
@@ -151,9 +152,9 @@ int oracle_fwd(int cell, int T, int B, int NH, int D, const double* Wx, const do
  * (t = 1..T).  dstates_last (may be NULL) is an extra gradient on the final states [S,B,NH,D]
  * (its stabilizer slot is ignored).  Outputs: dWx, dR, db, dstates0.
  */
-int oracle_bwd(int cell, int T, int B, int NH, int D, const double* Wx, const double* R, const double* bias,
-               const double* states, const double* dH, const double* dstates_last, double* dWx, double* dR,
-               double* db, double* dstates0) {
+int oracle_bwd_clipped(int cell, int T, int B, int NH, int D, const double* Wx, const double* R, const double* bias,
+                       const double* states, const double* dH, const double* dstates_last, double recurrent_clip,
+                       double* dWx, double* dR, double* db, double* dstates0) {
     const int S = n_states(cell), G = n_gates(cell);
     if (S < 0 || T < 0 || B <= 0 || NH <= 0 || D <= 0) return -1;
     if (!Wx || !R || !bias || !states || !dH || !dWx || !dR || !db || !dstates0) return -1;
@@ -257,7 +258,9 @@ int oracle_bwd(int cell, int T, int B, int NH, int D, const double* Wx, const do
                             acc += Rrow[g * D + e] * v;
                             dRrow[g * D + e] += hp * v;
                         }
-                    dh_prev[((size_t)bb * NH + n) * D + d] = acc;
+                    /* Sec. 4.1: the term that contains the recurrent matrix may be clipped, value by value, after
+                       each time step (recurrent_clip < 0: not clipped; 0 cuts it to zero) */
+                    dh_prev[((size_t)bb * NH + n) * D + d] = recurrent_clip >= 0.0 ? fmin(fmax(acc, -recurrent_clip), recurrent_clip) : acc;
                 }
             }
         }
@@ -275,4 +278,10 @@ int oracle_bwd(int cell, int T, int B, int NH, int D, const double* Wx, const do
     if (cell == CELL_SLSTM) memset(dstates0 + 3 * BHD, 0, BHD * sizeof(double));
     free(ds); free(dg); free(dh_prev);
     return 0;
+}
+
+int oracle_bwd(int cell, int T, int B, int NH, int D, const double* Wx, const double* R, const double* bias,
+               const double* states, const double* dH, const double* dstates_last, double* dWx, double* dR,
+               double* db, double* dstates0) {
+    return oracle_bwd_clipped(cell, T, B, NH, D, Wx, R, bias, states, dH, dstates_last, -1.0, dWx, dR, db, dstates0);
 }

@@ -37,6 +37,8 @@ def _load():
         lib.oracle_fwd.restype = ctypes.c_int
         lib.oracle_bwd.argtypes = [ctypes.c_int] * 5 + [dp] * 10
         lib.oracle_bwd.restype = ctypes.c_int
+        lib.oracle_bwd_clipped.argtypes = [ctypes.c_int] * 5 + [dp] * 6 + [ctypes.c_double] + [dp] * 4
+        lib.oracle_bwd_clipped.restype = ctypes.c_int
         for f in (lib.oracle_num_states, lib.oracle_num_gates):
             f.argtypes = [ctypes.c_int]
             f.restype = ctypes.c_int
@@ -86,8 +88,9 @@ def fwd(cell, Wx, R, b, states0=None):
     return states
 
 
-def bwd(cell, Wx, R, b, states, dH, dstates_last=None):
-    """BPTT; returns (dWx, dR, db, dstates0)."""
+def bwd(cell, Wx, R, b, states, dH, dstates_last=None, recurrent_clip=None):
+    """BPTT; returns (dWx, dR, db, dstates0).  recurrent_clip (Sec. 4.1): None = off, c >= 0 clips every value of the
+    recurrent term R^T dg_t to [-c, c] after each step (0 cuts it)."""
     T, B, G, NH, D = Wx.shape
     S = num_states(cell)
     Wx = _c(Wx, (T, B, G, NH, D), "Wx")
@@ -101,8 +104,11 @@ def bwd(cell, Wx, R, b, states, dH, dstates_last=None):
     dR = np.empty_like(R)
     db = np.empty_like(b)
     ds0 = np.empty((S, B, NH, D), dtype=np.float64)
-    rc = _load().oracle_bwd(int(cell), T, B, NH, D, _p(Wx), _p(R), _p(b), _p(states), _p(dH), _p(dstates_last),
-                            _p(dWx), _p(dR), _p(db), _p(ds0))
+    clip = -1.0 if recurrent_clip is None else float(recurrent_clip)
+    if recurrent_clip is not None and not clip >= 0.0:
+        raise ValueError("recurrent_clip must be >= 0 or None")
+    rc = _load().oracle_bwd_clipped(int(cell), T, B, NH, D, _p(Wx), _p(R), _p(b), _p(states), _p(dH), _p(dstates_last),
+                                    ctypes.c_double(clip), _p(dWx), _p(dR), _p(db), _p(ds0))
     if rc != 0:
         raise RuntimeError(f"oracle_bwd failed ({rc})")
     return dWx, dR, db, ds0

@@ -351,3 +351,80 @@ def test_zero_initial_state_is_default_and_T0():
         assert np.all(np.isfinite(a))
         e = oracle.fwd(cell, Wx[:0], R, b, None)
         assert e.shape == (1, S, 2, 1, 4) and np.all(e == 0)
+
+
+# ----------------------------------------------------------------------------------------------
+# clipping of the recurrent gradient term (Sec. 4.1)
+# ----------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("cell", CELLS)
+def test_recurrent_clip_single_step_is_clamp_of_unclipped(cell):
+    """T = 1: nothing upstream is affected by the clip, so dstates0[h] = direct path + clamp(R^T dg_1) with the
+    unclipped dg_1.  Catches: clip applied to the wrong term (direct path, dH, dWx), wrong bounds, clip ignored."""
+    T, B, NH, D = 1, 3, 2, 6
+    Wx, R, b, s0, dH = _rand(cell, T, B, NH, D, seed=21, rscale=3.0)
+    st = oracle.fwd(cell, Wx, R, b, s0)
+    dWx0, dR0, db0, ds0_0 = oracle.bwd(cell, Wx, R, b, st, dH)
+    # recurrent term alone: R^T dg_1 = dstates0[h] of the unclipped run minus the direct path, which is what a run
+    # with the recurrent term cut (clip 0) returns
+    _, _, _, ds0_cut = oracle.bwd(cell, Wx, R, b, st, dH, recurrent_clip=0.0)
+    rec = ds0_0[0] - ds0_cut[0]
+    assert np.abs(rec).max() > 0.2
+    c = 0.1
+    dWx, dR, db, ds0 = oracle.bwd(cell, Wx, R, b, st, dH, recurrent_clip=c)
+    np.testing.assert_allclose(ds0[0], ds0_cut[0] + np.clip(rec, -c, c), rtol=1e-12, atol=1e-14)
+    for a, ref in ((dWx, dWx0), (dR, dR0), (db, db0), (ds0[1:], ds0_0[1:])):
+        np.testing.assert_array_equal(a, ref)
+    big = oracle.bwd(cell, Wx, R, b, st, dH, recurrent_clip=1e30)
+    for a, ref in zip(big, (dWx0, dR0, db0, ds0_0)):
+        np.testing.assert_array_equal(a, ref)
+
+
+@pytest.mark.parametrize("cell", CELLS)
+def test_recurrent_clip_composes_over_time(cell):
+    """BPTT over T steps with the clip == T single-step backward passes chained through dstates_last, each of
+    them clipping its own recurrent term (dR, db summed).  Catches: clip applied once at the end, or to the carried
+    gradient instead of to the recurrent term of each step."""
+    T, B, NH, D = 5, 2, 2, 4
+    Wx, R, b, s0, dH = _rand(cell, T, B, NH, D, seed=22, rscale=3.0)
+    st = oracle.fwd(cell, Wx, R, b, s0)
+    c = 0.05
+    dWx, dR, db, ds0 = oracle.bwd(cell, Wx, R, b, st, dH, recurrent_clip=c)
+    carry, dR_sum, db_sum = None, 0.0, 0.0
+    for t in range(T, 0, -1):
+        g = oracle.bwd(cell, Wx[t - 1:t], R, b, st[t - 1:t + 1], dH[t - 1:t], carry, recurrent_clip=c)
+        np.testing.assert_allclose(dWx[t - 1], g[0][0], rtol=1e-12, atol=1e-14)
+        dR_sum, db_sum, carry = dR_sum + g[1], db_sum + g[2], g[3]
+    np.testing.assert_allclose(dR, dR_sum, rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(db, db_sum, rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(ds0, carry, rtol=1e-12, atol=1e-14)
+    unclipped = oracle.bwd(cell, Wx, R, b, st, dH)
+    assert np.abs(dWx - unclipped[0]).max() > 1e-3   # the clip did bite
+
+
+def test_recurrent_cut_equals_library_lstm_cell_with_detached_h():
+    """clip = 0 removes the path through R from the backward pass: the same as autograd through torch's CPU LSTMCell
+    (float64) when the hidden state entering the cell is detached.  dR and db still see every step."""
+    T, B, NH, D = 6, 3, 1, 5
+    Wx, R, b, s0, dH = _rand(CELL_LSTM, T, B, NH, D, seed=23)
+    st = oracle.fwd(CELL_LSTM, Wx, R, b, s0)
+    dWx, dR, db, ds0 = oracle.bwd(CELL_LSTM, Wx, R, b, st, dH, recurrent_clip=0.0)
+    G = 4
+    x = torch.tensor(Wx.reshape(T, B, G * D), requires_grad=True)
+    w_hh = torch.tensor(np.ascontiguousarray(R[0].transpose(1, 2, 0)).reshape(G * D, D), requires_grad=True)
+    b_hh = torch.tensor(b[0].reshape(G * D), requires_grad=True)
+    h0 = torch.tensor(s0[0].reshape(B, D), requires_grad=True)
+    c0 = torch.tensor(s0[1].reshape(B, D), requires_grad=True)
+    cell = torch.nn.LSTMCell(G * D, D).double()
+    params = {"weight_ih": torch.eye(G * D, dtype=torch.float64), "weight_hh": w_hh,
+              "bias_ih": torch.zeros(G * D, dtype=torch.float64), "bias_hh": b_hh}
+    h, c, loss = h0, c0, 0.0
+    dHt = torch.tensor(dH.reshape(T, B, D))
+    for t in range(T):
+        h, c = torch.func.functional_call(cell, params, (x[t], (h.detach() if t > 0 else h * 0 + h.detach(), c)))
+        loss = loss + (h * dHt[t]).sum()
+    g = torch.autograd.grad(loss, [x, w_hh, b_hh, c0])
+    np.testing.assert_allclose(dWx, g[0].numpy().reshape(T, B, G, 1, D), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(dR, g[1].numpy().reshape(G, D, D).transpose(2, 0, 1)[None], rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(db, g[2].numpy().reshape(1, G, D), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(ds0[1], g[3].numpy().reshape(B, 1, D), rtol=1e-10, atol=1e-12)
+    np.testing.assert_array_equal(ds0[0], 0.0)   # h_0 reaches the loss only through R
