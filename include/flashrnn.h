@@ -50,6 +50,10 @@ typedef struct {
     int cell;     /* flashrnn_cell_t  */
     int T, B, NH, D;
     int io_dtype; /* flashrnn_dtype_t */
+    /* Backward pass only (paper Sec. 4.1): clipping of the term of dh_{t-1} that contains the recurrent matrix,
+     * R^T dg_t, value by value after each time step.  0 = off, c > 0 clips to [-c, c], any negative value cuts
+     * the term to zero (no gradient flows through R between steps; dR and db still see every step). */
+    float recurrent_grad_clip;
 } flashrnn_desc_t;
 
 /* Number of states / gates of a cell (paper App. A): LSTM 2 / 4, GRU 1 / 3, sLSTM 4 / 4, Elman 1 / 1; -1 if unknown. */

@@ -21,7 +21,7 @@ _lib = None
 
 class flashrnn_desc_t(ctypes.Structure):
     _fields_ = [("cell", ctypes.c_int), ("T", ctypes.c_int), ("B", ctypes.c_int), ("NH", ctypes.c_int), ("D", ctypes.c_int),
-                ("io_dtype", ctypes.c_int)]
+                ("io_dtype", ctypes.c_int), ("recurrent_grad_clip", ctypes.c_float)]
 
 
 class FlashRNNError(RuntimeError):
@@ -87,8 +87,9 @@ def flashrnn_num_gates(cell):
     return lib().flashrnn_num_gates(int(cell))
 
 
-def make_desc(cell, T, B, NH, D, io_dtype):
-    return flashrnn_desc_t(int(cell), int(T), int(B), int(NH), int(D), int(io_dtype))
+def make_desc(cell, T, B, NH, D, io_dtype, recurrent_grad_clip=0.0):
+    """recurrent_grad_clip: 0 = off, c > 0 clips R^T dg_t to [-c, c] per step, negative cuts it (backward only)."""
+    return flashrnn_desc_t(int(cell), int(T), int(B), int(NH), int(D), int(io_dtype), float(recurrent_grad_clip))
 
 
 def flashrnn_gate_cache_bytes(desc):
@@ -186,13 +187,15 @@ def flashrnn_fwd(cell, Wx, R, b, states0=None, save_for_backward=True, workspace
     return states, (gate_cache if save_for_backward else None), workspace
 
 
-def flashrnn_bwd(cell, R, b, states, gate_cache, dH, dstates_last=None, workspace=None, stream=None, out=None):
+def flashrnn_bwd(cell, R, b, states, gate_cache, dH, dstates_last=None, workspace=None, stream=None, out=None,
+                 recurrent_grad_clip=0.0):
     """BPTT.  dH[T,B,NH,D] (I/O dtype).  Returns (dWx[T,B,G,NH,D], dR[NH,D,G,D] f32, db[NH,G,D] f32,
-    dstates0[S,B,NH,D] f32).  `out` may pass preallocated (dWx, dR, db, dstates0)."""
+    dstates0[S,B,NH,D] f32).  `out` may pass preallocated (dWx, dR, db, dstates0).  recurrent_grad_clip as in
+    flashrnn_desc_t: 0 off, c > 0 clips R^T dg_t to [-c, c] per step, negative cuts it."""
     T, B, NH, D = dH.shape
     S, G = flashrnn_num_states(cell), flashrnn_num_gates(cell)
     dt = dH.dtype
-    desc = make_desc(cell, T, B, NH, D, _io_dtype(dH))
+    desc = make_desc(cell, T, B, NH, D, _io_dtype(dH), recurrent_grad_clip)
     _chk(R, (NH, D, G, D), dt, "R")
     _chk(b, (NH, G, D), dt, "b")
     _chk(states, (T + 1, S, B, NH, D), torch.float32, "states")

@@ -60,6 +60,7 @@ int validate(const flashrnn_desc_t* d) {
     if (!d) return FLASHRNN_ERR_NULL;
     if (num_states(d->cell) < 0 || (d->io_dtype != FLASHRNN_F32 && d->io_dtype != FLASHRNN_BF16)) return FLASHRNN_ERR_SHAPE;
     if (d->T < 0 || d->B <= 0 || d->NH <= 0 || d->D <= 0) return FLASHRNN_ERR_SHAPE;
+    if (d->recurrent_grad_clip != d->recurrent_grad_clip) return FLASHRNN_ERR_SHAPE;   // NaN
     if (d->D % 16 != 0) return FLASHRNN_ERR_UNSUPPORTED;
     return FLASHRNN_OK;
 }
@@ -372,6 +373,7 @@ int flashrnn_bwd(const flashrnn_desc_t* d, const void* R, const void* b, const v
     memset(&kp, 0, sizeof(kp));
     kp.R = ws + w.rpack_off; kp.states = (float*)const_cast<void*>(states); kp.cache = const_cast<void*>(gate_cache);
     kp.dH = dH; kp.dlast = (const float*)dstates_last; kp.dWx = dWx; kp.dgn = ws + w.dgn_off;
+    kp.clip = d->recurrent_grad_clip > 0.0f ? d->recurrent_grad_clip : d->recurrent_grad_clip < 0.0f ? 0.0f : __builtin_inff();
     kp.dstates0 = (float*)dstates0; kp.db_part = (float*)(ws + w.dbpart_off);
     kp.exch = (uint32_t*)(ws + w.exch_off);
     kp.err = (int*)(ws + w.err_off);

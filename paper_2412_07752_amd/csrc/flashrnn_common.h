@@ -130,6 +130,7 @@ struct KernelParams {
     int NG;                // groups in total: NH * batch tiles; group id = tile * NH + head
     int GPAR;              // groups processed concurrently; a workgroup set loops over NG / GPAR of them
     int spin_limit;
+    float clip;            // bwd: bound of the recurrent gradient term per value (+inf = not clipped, 0 = cut)
 };
 
 // ---------------------------------------------------------------------------------------------

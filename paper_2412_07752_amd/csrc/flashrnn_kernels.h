@@ -789,7 +789,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
                 for (int eb = 0; eb < EB; ++eb) {
                     compact_tile<BT>(accs[eb][0]);
 #pragma unroll
-                    for (int i = 0; i < PP; ++i) ds[eb][0][i] += accs[eb][0][i];
+                    for (int i = 0; i < PP; ++i) ds[eb][0][i] += fminf(fmaxf(accs[eb][0][i], -p.clip), p.clip);   // (Sec. 4.1 clip; +inf = off)
                 }
                 // wait for the prefetched inputs here, where only this step's stores are younger
 #pragma unroll

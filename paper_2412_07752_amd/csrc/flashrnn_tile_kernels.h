@@ -614,16 +614,21 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
 #pragma unroll
                 for (int i = 0; i < PP; ++i) dbv[g][i] = dbs[((size_t)g * D + i) * BT];
             __syncthreads();
+            float rec[PP];   // R dg_t of this lane's pairs, summed over the slices
+#pragma unroll
+            for (int i = 0; i < PP; ++i) rec[i] = 0.0f;
 #pragma unroll
             for (int x = 0; x < EBK; ++x) {
                 float v[PP];
                 load_io<false, PP>(red, ((size_t)(w * EBK + x) * 64 + lane) * PP, v);
 #pragma unroll
-                for (int i = 0; i < PP; ++i) ds[0][i] += v[i];
+                for (int i = 0; i < PP; ++i) rec[i] += v[i];
             }
+#pragma unroll
+            for (int i = 0; i < PP; ++i) ds[0][i] += fminf(fmaxf(rec[i], -p.clip), p.clip);   // (Sec. 4.1 clip; +inf = off)
         } else {
 #pragma unroll
-            for (int i = 0; i < PP; ++i) ds[0][i] += part[0][i];
+            for (int i = 0; i < PP; ++i) ds[0][i] += fminf(fmaxf(part[0][i], -p.clip), p.clip);
 #pragma unroll
             for (int g = 0; g < G; ++g)
 #pragma unroll

@@ -40,17 +40,19 @@ def err(gpu, ref):
     return d / max(float(np.max(np.abs(ref))), 1e-30), d
 
 
-def run_oracle(w, inp, dstates_last=None):
+def run_oracle(w, inp, dstates_last=None, clip=None):
     f64 = lambda a: None if a is None else a.astype(np.float64)
     st = oracle.fwd(w.cell, f64(inp["Wx"]), f64(inp["R"]), f64(inp["b"]), f64(inp["states0"]))
     out = {"states": st}
     if w.backward:
-        dWx, dR, db, ds0 = oracle.bwd(w.cell, f64(inp["Wx"]), f64(inp["R"]), f64(inp["b"]), st, f64(inp["dH"]), f64(dstates_last))
+        dWx, dR, db, ds0 = oracle.bwd(w.cell, f64(inp["Wx"]), f64(inp["R"]), f64(inp["b"]), st, f64(inp["dH"]), f64(dstates_last),
+                                      recurrent_clip=clip)
         out.update(dWx=dWx, dR=dR, db=db, dstates0=ds0)
     return out
 
 
-def run_gpu(w, inp, dstates_last=None, check=True):
+def run_gpu(w, inp, dstates_last=None, check=True, clip=None):
+    """clip: the oracle's convention (None off, c >= 0 bound, 0 = cut); the C ABI spells it 0 / c / negative."""
     Wx, R, b = (to_device(inp[k], w.dtype) for k in ("Wx", "R", "b"))
     s0 = to_device(inp["states0"], "f32")
     states, cache, ws = api.flashrnn_fwd(w.cell, Wx, R, b, s0, save_for_backward=w.backward)
@@ -61,7 +63,8 @@ def run_gpu(w, inp, dstates_last=None, check=True):
     if w.backward:
         dH = to_device(inp["dH"], w.dtype)
         dl = to_device(dstates_last, "f32")
-        dWx, dR, db, ds0 = api.flashrnn_bwd(w.cell, R, b, states, cache, dH, dl, workspace=ws)
+        gclip = 0.0 if clip is None else (-1.0 if clip == 0 else float(clip))
+        dWx, dR, db, ds0 = api.flashrnn_bwd(w.cell, R, b, states, cache, dH, dl, workspace=ws, recurrent_grad_clip=gclip)
         if check:
             api.flashrnn_check(desc, ws)
         out.update(dWx=to_host64(dWx), dR=to_host64(dR), db=to_host64(db), dstates0=to_host64(ds0))
@@ -69,8 +72,11 @@ def run_gpu(w, inp, dstates_last=None, check=True):
     return out
 
 
-def compare(w, gpu, ref):
-    """dict name -> (rel, abs); states are split per state so that a small state is not hidden by a large one."""
+def compare(w, gpu, ref, scale_ref=None):
+    """dict name -> (rel, abs); states are split per state so that a small state is not hidden by a large one.
+    scale_ref (another reference result): the error is taken relative to the larger of the two references' maxima.
+    A clipped gradient is compared that way, against the scale of the unclipped one: the clip shrinks the values,
+    not the rounding error of the terms below the bound."""
     res = {}
     names = "hcnm"
     for s in range(w.S):
@@ -81,6 +87,12 @@ def compare(w, gpu, ref):
     if "dstates0" in ref:
         for s in range(w.S):
             res[f"dstates0.{names[s]}"] = err(gpu["dstates0"][s], ref["dstates0"][s])
+    if scale_ref is not None:
+        for k, (r, a) in list(res.items()):
+            base, idx = (k.split(".") + [None])[:2]
+            pick = (lambda d: d[base]) if idx is None else (lambda d: d[base][:, names.index(idx)] if base == "states" else d[base][names.index(idx)])
+            m = max(np.abs(pick(ref)).max(initial=0.0), np.abs(pick(scale_ref)).max(initial=0.0))
+            res[k] = (a / m if m > 0 else r, a)
     return res
 
 

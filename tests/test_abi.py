@@ -40,7 +40,8 @@ def test_status_strings():
     assert "unknown" in api.status_string(-99)
 
 
-@pytest.mark.parametrize("bad", [dict(cell=5), dict(T=-1), dict(B=0), dict(NH=0), dict(D=0), dict(io_dtype=3)])
+@pytest.mark.parametrize("bad", [dict(cell=5), dict(T=-1), dict(B=0), dict(NH=0), dict(D=0), dict(io_dtype=3),
+                                 dict(recurrent_grad_clip=float("nan"))])
 def test_bad_descriptors_are_rejected_on_the_host(bad):
     kw = dict(cell=0, T=4, B=2, NH=1, D=16, io_dtype=api.FLASHRNN_F32)
     kw.update(bad)

@@ -32,13 +32,13 @@ def _dlast(w, seed=99):
     return rng.standard_normal((w.S, w.B, w.NH, w.D)).astype(np.float32)
 
 
-def _check(w, env=None, with_dlast=False):
+def _check(w, env=None, with_dlast=False, clip=None):
     os.environ.update(env or {})
     print(f"case {w.name} env={env}", flush=True)
     inp = synth.make_inputs(w)
     dl = _dlast(w) if (with_dlast and w.backward) else None
-    ref = pu.run_oracle(w, inp, dl)
-    gpu = pu.run_gpu(w, inp, dl)
+    ref = pu.run_oracle(w, inp, dl, clip=clip)
+    gpu = pu.run_gpu(w, inp, dl, clip=clip)
     res = pu.compare(w, gpu, ref)
     pu.assert_close(w, res)
     return gpu
@@ -98,6 +98,25 @@ def test_forward_only_small_batch_tile(cell):
     """No gate cache: the staged forward kernel moves states only."""
     w = Workload(f"fwdonly_{cell}", cell, 6, 7, 2, 128, "bf16", False, bias="uniform0.1", init="uniform0.1", seed=77)
     _check(w)
+
+
+@pytest.mark.parametrize("cell", CELLS)
+@pytest.mark.parametrize("clip", [0.0, 0.02, 1e6])
+@pytest.mark.parametrize("dtype,D,env", [("bf16", 64, {}), ("bf16", 192, {}), ("bf16", 96, {"FLASHRNN_KIND": "0"}), ("f32", 32, {}),
+                                         ("bf16", 128, {"FLASHRNN_MULTI": "1", "FLASHRNN_KS": "4"})])
+def test_recurrent_gradient_clip(cell, clip, dtype, D, env):
+    """Sec. 4.1: the R^T dg_t term clipped value by value after every step (0 cuts it; a huge bound changes nothing),
+    in the tile, generic, f32 and split-group kernels.  (The recurrent term has values of a few tenths here: 0.02 bites.)"""
+    w = Workload(f"clip{clip}_{cell}_{dtype}_D{D}", cell, 7, 6, 2, D, dtype, True, bias="uniform0.1", init="uniform0.1", seed=D + 3)
+    os.environ.update(env)
+    print(f"case {w.name} env={env}", flush=True)
+    inp, dl = synth.make_inputs(w), _dlast(w)
+    ref, ref_free = pu.run_oracle(w, inp, dl, clip=clip), pu.run_oracle(w, inp, dl)
+    gpu = pu.run_gpu(w, inp, dl, clip=clip)
+    # errors relative to the scale of the unclipped gradients (the clip shrinks values, not rounding errors)
+    pu.assert_close(w, pu.compare(w, gpu, ref, scale_ref=ref_free))
+    if clip == 0.02:   # the bound did change the result
+        assert np.abs(ref_free["dWx"] - gpu["dWx"]).max() > 1e-3
 
 
 @pytest.mark.parametrize("cell", CELLS)
