@@ -21,6 +21,10 @@
  *     on s0_{t-1} (eq. (1)) the chain rule gives  ds0_{t-1} += R^T dg_t  and  dR = sum_t dg_t s0_{t-1}^T.
  *   - gate order on the G axis: LSTM and sLSTM  i, f, z, o ; GRU  r, z, n.   State order h, c, n, m.
  *   - Elman network (App. A): one state, one gate, h_t = tanh(x_t + R h_{t-1} + b).
+ *   - GRU4: the GRU exactly as App. A prints it, four gates in the printed order z, r, n, g, every one of them a full
+ *     pre-activation x + R h_{t-1} + b:   h_t = sig(z) h_{t-1} + (1 - sig(z)) tanh(n + sig(r) tanh(g))
+ *     (the appendix remarks that n does not depend on the previous state and g not on the input; a caller models that
+ *     with a zero R slice / zero inputs for those gates).
  *   - sLSTM equations (App. A) have unbalanced parentheses; read as
  *       m_t = max(log sig(f) + m_{t-1}, i)
  *       c_t = exp(log sig(f) + m_{t-1} - m_t) c_{t-1} + exp(i - m_t) tanh(z)
@@ -46,10 +50,10 @@
 #include <omp.h>
 #endif
 
-enum { CELL_LSTM = 0, CELL_GRU = 1, CELL_SLSTM = 2, CELL_ELMAN = 3 };
+enum { CELL_LSTM = 0, CELL_GRU = 1, CELL_SLSTM = 2, CELL_ELMAN = 3, CELL_GRU4 = 4 };
 
-static int n_states(int cell) { return cell == CELL_LSTM ? 2 : cell == CELL_GRU ? 1 : cell == CELL_SLSTM ? 4 : cell == CELL_ELMAN ? 1 : -1; }
-static int n_gates(int cell) { return cell == CELL_LSTM ? 4 : cell == CELL_GRU ? 3 : cell == CELL_SLSTM ? 4 : cell == CELL_ELMAN ? 1 : -1; }
+static int n_states(int cell) { return cell == CELL_LSTM ? 2 : cell == CELL_GRU ? 1 : cell == CELL_SLSTM ? 4 : cell == CELL_ELMAN ? 1 : cell == CELL_GRU4 ? 1 : -1; }
+static int n_gates(int cell) { return cell == CELL_LSTM ? 4 : cell == CELL_GRU ? 3 : cell == CELL_SLSTM ? 4 : cell == CELL_ELMAN ? 1 : cell == CELL_GRU4 ? 4 : -1; }
 
 int oracle_num_states(int cell) { return n_states(cell); }
 int oracle_num_gates(int cell) { return n_gates(cell); }
@@ -129,6 +133,12 @@ int oracle_fwd(int cell, int T, int B, int NH, int D, const double* Wx, const do
                             ST(t, 0, bb, n, e) = sigm(po) * c / nn;
                         } else if (cell == CELL_ELMAN) {
                             ST(t, 0, bb, n, e) = tanh(WX(t - 1, bb, 0, n, e) + y[e] + BI(n, 0, e));
+                        } else if (cell == CELL_GRU4) {
+                            const double z = sigm(WX(t - 1, bb, 0, n, e) + y[0 * D + e] + BI(n, 0, e));
+                            const double r = sigm(WX(t - 1, bb, 1, n, e) + y[1 * D + e] + BI(n, 1, e));
+                            const double pn = WX(t - 1, bb, 2, n, e) + y[2 * D + e] + BI(n, 2, e);
+                            const double tg = tanh(WX(t - 1, bb, 3, n, e) + y[3 * D + e] + BI(n, 3, e));
+                            ST(t, 0, bb, n, e) = z * ST(t - 1, 0, bb, n, e) + (1.0 - z) * tanh(pn + r * tg);
                         } else { /* GRU */
                             const double pr = WX(t - 1, bb, 0, n, e) + y[0 * D + e] + BI(n, 0, e);
                             const double pz = WX(t - 1, bb, 1, n, e) + y[1 * D + e] + BI(n, 1, e);
@@ -220,6 +230,20 @@ int oracle_bwd_clipped(int cell, int T, int B, int NH, int D, const double* Wx, 
                             DS(1, bb, n, e) = dc * fg;
                             DS(2, bb, n, e) = dn * fg;
                             DS(0, bb, n, e) = 0.0;
+                        } else if (cell == CELL_GRU4) {
+                            const double z = sigm(WX(t - 1, bb, 0, n, e) + y[0 * D + e] + BI(n, 0, e));
+                            const double r = sigm(WX(t - 1, bb, 1, n, e) + y[1 * D + e] + BI(n, 1, e));
+                            const double pn = WX(t - 1, bb, 2, n, e) + y[2 * D + e] + BI(n, 2, e);
+                            const double tg = tanh(WX(t - 1, bb, 3, n, e) + y[3 * D + e] + BI(n, 3, e));
+                            const double cand = tanh(pn + r * tg);
+                            const double dpre = dh * (1.0 - z) * (1.0 - cand * cand);
+                            const double dz = dh * (ST(t - 1, 0, bb, n, e) - cand) * z * (1.0 - z);
+                            const double dr = dpre * tg * r * (1.0 - r);
+                            const double dgg = dpre * r * (1.0 - tg * tg);
+                            DG(bb, 0, n, e) = dz; DG(bb, 1, n, e) = dr; DG(bb, 2, n, e) = dpre; DG(bb, 3, n, e) = dgg;
+                            DWX(t - 1, bb, 0, n, e) = dz; DWX(t - 1, bb, 1, n, e) = dr;
+                            DWX(t - 1, bb, 2, n, e) = dpre; DWX(t - 1, bb, 3, n, e) = dgg;
+                            DS(0, bb, n, e) = dh * z; /* direct path h_{t-1} -> h_t */
                         } else if (cell == CELL_ELMAN) {
                             const double h = tanh(WX(t - 1, bb, 0, n, e) + y[e] + BI(n, 0, e));
                             const double dpre = dh * (1.0 - h * h);

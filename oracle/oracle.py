@@ -12,7 +12,7 @@ import subprocess
 
 import numpy as np
 
-CELL_LSTM, CELL_GRU, CELL_SLSTM, CELL_ELMAN = 0, 1, 2, 3
+CELL_LSTM, CELL_GRU, CELL_SLSTM, CELL_ELMAN, CELL_GRU4 = 0, 1, 2, 3, 4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "flashrnn_oracle.c")

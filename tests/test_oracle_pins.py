@@ -13,10 +13,10 @@ import pytest
 import torch
 
 import oracle
-from oracle import CELL_ELMAN, CELL_GRU, CELL_LSTM, CELL_SLSTM
+from oracle import CELL_ELMAN, CELL_GRU, CELL_GRU4, CELL_LSTM, CELL_SLSTM
 
 GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
-CELLS = [CELL_LSTM, CELL_GRU, CELL_SLSTM, CELL_ELMAN]
+CELLS = [CELL_LSTM, CELL_GRU, CELL_SLSTM, CELL_ELMAN, CELL_GRU4]
 
 
 def _rand(cell, T, B, NH, D, seed, rscale=0.6, with_s0=True):
@@ -221,6 +221,12 @@ def test_hand_worked_examples():
     Wx = np.array([[0.0, -ln3, ln2], [0.0, 0.0, ln3 - 0.45]]).reshape(2, 1, 3, 1, 1)
     R = np.array([0.0, 0.0, 2.0]).reshape(1, 1, 3, 1)
     st = oracle.fwd(CELL_GRU, Wx, R, np.zeros((1, 3, 1)))
+    np.testing.assert_allclose([st[1, 0].item(), st[2, 0].item()], [g["h_1"], g["h_2"]], rtol=1e-13)
+
+    g = _read_golden("gru4_hand_example.txt")
+    Wx = np.array([[-ln3, ln3, ln2 - 0.45, ln2], [0.0, 0.0, ln3 - 0.4, ln3 - 0.9]]).reshape(2, 1, 4, 1, 1)
+    R = np.array([0.0, 0.0, 0.0, 2.0]).reshape(1, 1, 4, 1)
+    st = oracle.fwd(CELL_GRU4, Wx, R, np.zeros((1, 4, 1)))
     np.testing.assert_allclose([st[1, 0].item(), st[2, 0].item()], [g["h_1"], g["h_2"]], rtol=1e-13)
 
     g = _read_golden("slstm_hand_example.txt")
