@@ -15,8 +15,10 @@
  *   - Calls that share a workspace must not overlap in time.
  *
  * Index names:  T time steps, B batch, NH heads, D units per head, G gates, S states.
- *   Gate order on the G axis:  LSTM, sLSTM: i, f, z, o     GRU: r, z, n     Elman: one gate
- *   State order on the S axis: LSTM: h, c     GRU: h     sLSTM: h, c, n, m     Elman: h   (paper App. A)
+ *   Gate order on the G axis:  LSTM, sLSTM: i, f, z, o     GRU: r, z, n     Elman: one gate     GRU4: z, r, n, g
+ *   State order on the S axis: LSTM: h, c     GRU, GRU4: h     sLSTM: h, c, n, m     Elman: h   (paper App. A)
+ *   GRU is the three-gate cell (candidate bias inside the r-product); GRU4 is the cell exactly as App. A prints it:
+ *   h_t = sig(z) h_{t-1} + (1 - sig(z)) tanh(n + sig(r) tanh(g)), all four gates full pre-activations.
  */
 #ifndef FLASHRNN_H
 #define FLASHRNN_H
@@ -27,7 +29,7 @@
 extern "C" {
 #endif
 
-typedef enum { FLASHRNN_LSTM = 0, FLASHRNN_GRU = 1, FLASHRNN_SLSTM = 2, FLASHRNN_ELMAN = 3 } flashrnn_cell_t;
+typedef enum { FLASHRNN_LSTM = 0, FLASHRNN_GRU = 1, FLASHRNN_SLSTM = 2, FLASHRNN_ELMAN = 3, FLASHRNN_GRU4 = 4 } flashrnn_cell_t;
 typedef enum { FLASHRNN_F32 = 0, FLASHRNN_BF16 = 1 } flashrnn_dtype_t;
 
 typedef enum {
@@ -56,7 +58,7 @@ typedef struct {
     float recurrent_grad_clip;
 } flashrnn_desc_t;
 
-/* Number of states / gates of a cell (paper App. A): LSTM 2 / 4, GRU 1 / 3, sLSTM 4 / 4, Elman 1 / 1; -1 if unknown. */
+/* Number of states / gates of a cell (paper App. A): LSTM 2 / 4, GRU 1 / 3, sLSTM 4 / 4, Elman 1 / 1, GRU4 1 / 4; -1 if unknown. */
 int flashrnn_num_states(int cell);
 int flashrnn_num_gates(int cell);
 

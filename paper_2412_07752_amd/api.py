@@ -9,7 +9,7 @@ import os
 
 import torch
 
-FLASHRNN_LSTM, FLASHRNN_GRU, FLASHRNN_SLSTM, FLASHRNN_ELMAN = 0, 1, 2, 3
+FLASHRNN_LSTM, FLASHRNN_GRU, FLASHRNN_SLSTM, FLASHRNN_ELMAN, FLASHRNN_GRU4 = 0, 1, 2, 3, 4
 FLASHRNN_F32, FLASHRNN_BF16 = 0, 1
 FLASHRNN_OK = 0
 FLASHRNN_ERR_NULL, FLASHRNN_ERR_SHAPE, FLASHRNN_ERR_UNSUPPORTED = -1, -2, -3

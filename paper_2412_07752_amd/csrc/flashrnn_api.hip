@@ -20,8 +20,8 @@ constexpr int kXcds = 8;            // accelerator dies a workgroup index cycles
 constexpr size_t kAlign = 256;
 
 inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
-inline int num_states(int cell) { return cell == FLASHRNN_LSTM ? 2 : cell == FLASHRNN_GRU ? 1 : cell == FLASHRNN_SLSTM ? 4 : cell == FLASHRNN_ELMAN ? 1 : -1; }
-inline int num_gates(int cell) { return cell == FLASHRNN_LSTM ? 4 : cell == FLASHRNN_GRU ? 3 : cell == FLASHRNN_SLSTM ? 4 : cell == FLASHRNN_ELMAN ? 1 : -1; }
+inline int num_states(int cell) { return cell == FLASHRNN_LSTM ? 2 : cell == FLASHRNN_GRU ? 1 : cell == FLASHRNN_SLSTM ? 4 : cell == FLASHRNN_ELMAN ? 1 : cell == FLASHRNN_GRU4 ? 1 : -1; }
+inline int num_gates(int cell) { return cell == FLASHRNN_LSTM ? 4 : cell == FLASHRNN_GRU ? 3 : cell == FLASHRNN_SLSTM ? 4 : cell == FLASHRNN_ELMAN ? 1 : cell == FLASHRNN_GRU4 ? 4 : -1; }
 inline int num_cached(int cell) { return cell == FLASHRNN_SLSTM ? 5 : 4; }
 inline size_t io_size(int dt) { return dt == FLASHRNN_BF16 ? 2 : 4; }
 
@@ -46,6 +46,7 @@ KernelTable table_for(int cell, int dt) {
         case FLASHRNN_LSTM: return bf ? table_lstm_bf16() : table_lstm_f32();
         case FLASHRNN_GRU: return bf ? table_gru_bf16() : table_gru_f32();
         case FLASHRNN_ELMAN: return bf ? table_elman_bf16() : table_elman_f32();
+        case FLASHRNN_GRU4: return bf ? table_gru4_bf16() : table_gru4_f32();
         default: return bf ? table_slstm_bf16() : table_slstm_f32();
     }
 }

@@ -15,7 +15,9 @@
 
 namespace flashrnn {
 
-enum : int { CELL_LSTM = 0, CELL_GRU = 1, CELL_SLSTM = 2, CELL_ELMAN = 3 };
+enum : int { CELL_LSTM = 0, CELL_GRU = 1, CELL_SLSTM = 2, CELL_ELMAN = 3, CELL_GRU4 = 4 };
+// cells whose Jacobian needs h_{t-1} itself (the z gate mixes it into h_t)
+constexpr bool cell_uses_h_prev(int cell) { return cell == CELL_GRU || cell == CELL_GRU4; }
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
@@ -27,11 +29,13 @@ template <> struct CellTraits<CELL_LSTM> { static constexpr int G = 4, S = 2, NC
 template <> struct CellTraits<CELL_GRU> { static constexpr int G = 3, S = 1, NC = 4; };
 template <> struct CellTraits<CELL_SLSTM> { static constexpr int G = 4, S = 4, NC = 5; };
 template <> struct CellTraits<CELL_ELMAN> { static constexpr int G = 1, S = 1, NC = 1; };
+template <> struct CellTraits<CELL_GRU4> { static constexpr int G = 4, S = 1, NC = 4; };
 // NC = values per (t, batch row, unit) the forward pass saves for the backward pass:
 //   LSTM  sig(i), sig(f), tanh(z), sig(o)
 //   GRU   sig(r), sig(z), tanh(candidate), yn = R_n h + b_n
 //   sLSTM input weight exp(i - m_t), forget weight exp(log sig(f) + m_{t-1} - m_t), tanh(z), sig(o), sig(-f)
 //   Elman h_t
+//   GRU4  sig(z), sig(r), tanh(n + sig(r) tanh(g)), tanh(g)
 
 // The saved values of one (t, batch row, head, unit) form one 16-byte record of kCacheSlots elements
 // (bf16 I/O; with f32 I/O the record is 32 bytes): cache[T][B][NH][D][kCacheSlots].  One record is one

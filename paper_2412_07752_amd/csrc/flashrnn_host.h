@@ -34,6 +34,8 @@ KernelTable table_slstm_bf16();
 KernelTable table_slstm_f32();
 KernelTable table_elman_bf16();
 KernelTable table_elman_f32();
+KernelTable table_gru4_bf16();
+KernelTable table_gru4_f32();
 
 int dr_split_k(int T, int B, int NH, int D, int G);
 hipError_t launch_dr_gemm(bool bf16, const float* states, const void* dWx, const void* dgn, float* part, float* dR, int T, int B,

@@ -118,6 +118,30 @@ template <bool FAST> struct Cell<CELL_GRU, FAST> {
     }
 };
 
+template <bool FAST> struct Cell<CELL_GRU4, FAST> {
+    // the GRU as App. A prints it; gates z, r, n, g (all full pre-activations); st = {h}
+    static __device__ __forceinline__ void fwd(const float (&wx)[4], const float (&yb)[4], float (&st)[1], float (&cv)[4]) {
+        const float z = sigm<FAST>(wx[0] + yb[0]), r = sigm<FAST>(wx[1] + yb[1]);
+        const float tg = tanh_<FAST>(wx[3] + yb[3]);
+        const float cand = tanh_<FAST>(wx[2] + yb[2] + r * tg);
+        st[0] = z * st[0] + (1.0f - z) * cand;
+        cv[0] = z; cv[1] = r; cv[2] = cand; cv[3] = tg;
+    }
+    static __device__ __forceinline__ void bwd(const float (&cv)[4], const float (&sc)[1], const float (&sp)[1], float (&ds)[1],
+                                               float (&dwx)[4], float (&dg)[4]) {
+        const float z = cv[0], r = cv[1], cand = cv[2], tg = cv[3];
+        const float dh = ds[0];
+        const float dpre = dh * (1.0f - z) * (1.0f - cand * cand);
+        dg[0] = dh * (sp[0] - cand) * z * (1.0f - z);
+        dg[1] = dpre * tg * r * (1.0f - r);
+        dg[2] = dpre;
+        dg[3] = dpre * r * (1.0f - tg * tg);
+        dwx[0] = dg[0]; dwx[1] = dg[1]; dwx[2] = dg[2]; dwx[3] = dg[3];
+        ds[0] = dh * z;  // direct path h_{t-1} -> h_t
+        (void)sc;
+    }
+};
+
 template <bool FAST> struct Cell<CELL_ELMAN, FAST> {
     // st = {h}: h_t = tanh(x_t + R h_{t-1} + b)
     static __device__ __forceinline__ void fwd(const float (&wx)[1], const float (&yb)[1], float (&st)[1], float (&cv)[1]) {
@@ -687,11 +711,11 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
             }
 #pragma unroll
             for (int s = 0; s < S; ++s) {
-                if (CELL != CELL_GRU && s > 0 && s < 3) load_io_r<false, PP>(st_t, voff_st + eb * 64, s * st_state, sc_[eb][s]);
+                if (!cell_uses_h_prev(CELL) && s > 0 && s < 3) load_io_r<false, PP>(st_t, voff_st + eb * 64, s * st_state, sc_[eb][s]);
                 else
 #pragma unroll
                     for (int i = 0; i < PP; ++i) sc_[eb][s][i] = 1.0f;
-                if ((CELL == CELL_GRU) ? (s == 0) : (s > 0 && s < 3)) load_io_r<false, PP>(st_p, voff_st + eb * 64, s * st_state, sp_[eb][s]);
+                if (cell_uses_h_prev(CELL) ? (s == 0) : (s > 0 && s < 3)) load_io_r<false, PP>(st_p, voff_st + eb * 64, s * st_state, sp_[eb][s]);
                 else
 #pragma unroll
                     for (int i = 0; i < PP; ++i) sp_[eb][s][i] = 1.0f;

@@ -293,7 +293,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
     constexpr int ESZ = 2;
     constexpr int KT = KTW * EBK, DK = KT * 32;
     constexpr int NSB = CELL == CELL_SLSTM ? 2 : CELL == CELL_ELMAN ? 0 : 1;   // state rows the Jacobian needs per time level ...
-    constexpr int SB0 = CELL == CELL_GRU ? 0 : 1;     // ... starting at this state
+    constexpr int SB0 = cell_uses_h_prev(CELL) ? 0 : 1;   // ... starting at this state
     constexpr int GO = CELL == CELL_GRU ? G + 1 : G;  // output rows per batch row: dWx (+ the recurrent-side candidate gradient)
     constexpr int NA = EBK == 1 ? 4 : (EBK == 2 ? 2 : 1);   // accumulators per block: independent MFMAs in flight
     constexpr uint32_t kDrop = 0x80000000u;
@@ -434,7 +434,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
     //   sLSTM kc = {o/n, o c/n^2, ig (1 - z^2), fg sig(-f), (c/n) o (1 - o)}
     //   LSTM  kc = {o (1 - tanh^2 c), z i (1 - i), c_prev f (1 - f), i (1 - z^2), tanh(c) o (1 - o)}
     //   GRU   kc = {(1 - z)(1 - cand^2), (h_prev - cand) z (1 - z), kc0 yn r (1 - r), kc0 r}
-    constexpr bool kPre = CELL != CELL_ELMAN;
+    constexpr bool kPre = CELL == CELL_LSTM || CELL == CELL_SLSTM || CELL == CELL_GRU;
     float kc[5][PP];
     auto precompute = [&]() {
 #pragma unroll
@@ -465,7 +465,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
     // ---- prologue: images of steps T and T-1, this lane's inputs of step T, the states after step T
 #pragma unroll
     for (int s = 0; s < S; ++s) {
-        if (CELL != CELL_GRU && s >= SB0 && s < SB0 + NSB && T > 0)
+        if (!cell_uses_h_prev(CELL) && s >= SB0 && s < SB0 + NSB && T > 0)
             load_io_r<false, PP>(make_rsrc(st_g + (size_t)T * st_step), voff_st, s * st_state, sc[s]);
         else
 #pragma unroll
@@ -541,7 +541,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
                 store_io<true, PP>(out_img + (t & 1) * L.out_pitch + l_out + (uint32_t)g * L.rp_io, 0, dwx[g]);
             }
             if constexpr (CELL == CELL_GRU) store_io<true, PP>(out_img + (t & 1) * L.out_pitch + l_out + (uint32_t)G * L.rp_io, 0, dg[2]);
-            if constexpr (CELL != CELL_GRU) {
+            if constexpr (!cell_uses_h_prev(CELL)) {
 #pragma unroll
                 for (int s = SB0; s < SB0 + NSB; ++s)
 #pragma unroll

@@ -9,10 +9,10 @@ from dataclasses import dataclass, field
 
 import numpy as np
 
-CELL_LSTM, CELL_GRU, CELL_SLSTM, CELL_ELMAN = 0, 1, 2, 3
-CELL_NAMES = {CELL_LSTM: "lstm", CELL_GRU: "gru", CELL_SLSTM: "slstm", CELL_ELMAN: "elman"}
-NUM_STATES = {CELL_LSTM: 2, CELL_GRU: 1, CELL_SLSTM: 4, CELL_ELMAN: 1}
-NUM_GATES = {CELL_LSTM: 4, CELL_GRU: 3, CELL_SLSTM: 4, CELL_ELMAN: 1}
+CELL_LSTM, CELL_GRU, CELL_SLSTM, CELL_ELMAN, CELL_GRU4 = 0, 1, 2, 3, 4
+CELL_NAMES = {CELL_LSTM: "lstm", CELL_GRU: "gru", CELL_SLSTM: "slstm", CELL_ELMAN: "elman", CELL_GRU4: "gru4"}
+NUM_STATES = {CELL_LSTM: 2, CELL_GRU: 1, CELL_SLSTM: 4, CELL_ELMAN: 1, CELL_GRU4: 1}
+NUM_GATES = {CELL_LSTM: 4, CELL_GRU: 3, CELL_SLSTM: 4, CELL_ELMAN: 1, CELL_GRU4: 4}
 FORGET_GATE = 1  # index of the forget gate on the G axis (order i, f, z, o)
 
 

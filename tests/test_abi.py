@@ -26,8 +26,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_cell_tables_match_paper_appendix_a():
-    assert [api.flashrnn_num_states(c) for c in (0, 1, 2, 3)] == [2, 1, 4, 1]
-    assert [api.flashrnn_num_gates(c) for c in (0, 1, 2, 3)] == [4, 3, 4, 1]
+    assert [api.flashrnn_num_states(c) for c in (0, 1, 2, 3, 4)] == [2, 1, 4, 1, 1]
+    assert [api.flashrnn_num_gates(c) for c in (0, 1, 2, 3, 4)] == [4, 3, 4, 1, 4]
     assert api.flashrnn_num_states(7) == -1 and api.flashrnn_num_gates(-1) == -1
 
 

@@ -9,10 +9,10 @@ import torch
 
 import parity_util as pu
 from paper_2412_07752_amd import api, synth
-from paper_2412_07752_amd.synth import CELL_ELMAN, CELL_GRU, CELL_LSTM, CELL_SLSTM, Workload
+from paper_2412_07752_amd.synth import CELL_ELMAN, CELL_GRU, CELL_GRU4, CELL_LSTM, CELL_SLSTM, Workload
 
 pytestmark = pytest.mark.gpu
-CELLS = [CELL_LSTM, CELL_GRU, CELL_SLSTM, CELL_ELMAN]
+CELLS = [CELL_LSTM, CELL_GRU, CELL_SLSTM, CELL_ELMAN, CELL_GRU4]
 PLAN_ENV = ("FLASHRNN_MULTI", "FLASHRNN_BT", "FLASHRNN_NWU", "FLASHRNN_KS", "FLASHRNN_GPAR", "FLASHRNN_SPIN_LIMIT", "FLASHRNN_EBK",
             "FLASHRNN_KIND")
 
