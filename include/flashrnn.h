@@ -129,6 +129,14 @@ int flashrnn_check(const flashrnn_desc_t* desc, const void* workspace, void* hip
 int flashrnn_plan(const flashrnn_desc_t* desc, int backward, int* workgroups, int* cus_per_head, int* waves_per_wg);
 
 /*
+ * Which kernel family that plan uses, for reports and regression tests: *staged = 1 for the kernels that move
+ * global traffic as 16-byte chunks through LDS images (small batch tiles, bf16), 0 for the kernels whose lanes
+ * access global memory themselves; *batch_tile = rows of a batch tile (16, 8 or 4); *split = workgroups per group
+ * (> 1: the head is split over CUs that exchange h / dg every step).  Any out pointer may be NULL.
+ */
+int flashrnn_plan_kernel(const flashrnn_desc_t* desc, int backward, int* staged, int* batch_tile, int* split);
+
+/*
  * Measurement aid (the only state the library keeps; meant for benchmarks, not thread-hot paths).
  * While enabled, every flashrnn_fwd / flashrnn_bwd call records one HIP event immediately before and
  * one immediately after its persistent time-loop kernel, on the call's stream (up to 256 calls per

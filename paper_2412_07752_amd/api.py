@@ -60,6 +60,8 @@ def lib():
         L.flashrnn_check.restype = ctypes.c_int
         L.flashrnn_plan.argtypes = [dp, ctypes.c_int] + [ctypes.POINTER(ctypes.c_int)] * 3
         L.flashrnn_plan.restype = ctypes.c_int
+        L.flashrnn_plan_kernel.argtypes = [dp, ctypes.c_int] + [ctypes.POINTER(ctypes.c_int)] * 3
+        L.flashrnn_plan_kernel.restype = ctypes.c_int
         L.flashrnn_profile_enable.argtypes = [ctypes.c_int]
         L.flashrnn_profile_enable.restype = ctypes.c_int
         L.flashrnn_profile_kernel_ms.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int)]
@@ -71,7 +73,7 @@ def lib():
 
 
 EXPORTS = ["flashrnn_num_states", "flashrnn_num_gates", "flashrnn_gate_cache_bytes", "flashrnn_workspace_bytes", "flashrnn_fwd",
-           "flashrnn_bwd", "flashrnn_check", "flashrnn_plan", "flashrnn_profile_enable", "flashrnn_profile_kernel_ms",
+           "flashrnn_bwd", "flashrnn_check", "flashrnn_plan", "flashrnn_plan_kernel", "flashrnn_profile_enable", "flashrnn_profile_kernel_ms",
            "flashrnn_status_string"]
 
 
@@ -107,6 +109,15 @@ def flashrnn_plan(desc, backward=False):
     if rc != FLASHRNN_OK:
         raise FlashRNNError(rc, "flashrnn_plan")
     return a.value, b.value, c.value
+
+
+def flashrnn_plan_kernel(desc, backward=False):
+    """(staged, batch tile rows, workgroups per group) of the kernel that plan uses."""
+    a, b, c = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    rc = lib().flashrnn_plan_kernel(ctypes.byref(desc), int(bool(backward)), ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
+    if rc != FLASHRNN_OK:
+        raise FlashRNNError(rc, "flashrnn_plan_kernel")
+    return bool(a.value), b.value, c.value
 
 
 def flashrnn_profile_enable(on):

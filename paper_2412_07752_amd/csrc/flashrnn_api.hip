@@ -320,6 +320,18 @@ int flashrnn_plan(const flashrnn_desc_t* d, int backward, int* workgroups, int* 
     return FLASHRNN_OK;
 }
 
+int flashrnn_plan_kernel(const flashrnn_desc_t* d, int backward, int* staged, int* batch_tile, int* split) {
+    int rc = validate(d);
+    if (rc != FLASHRNN_OK) return rc;
+    Plan pl;
+    rc = make_plan(d, backward ? 1 : 0, &pl);
+    if (rc != FLASHRNN_OK) return rc;
+    if (staged) *staged = pl.e->tile != 0;
+    if (batch_tile) *batch_tile = pl.e->BT;
+    if (split) *split = pl.P;
+    return FLASHRNN_OK;
+}
+
 int flashrnn_fwd(const flashrnn_desc_t* d, const void* Wx, const void* R, const void* b, const void* states0, void* states,
                  void* gate_cache, void* workspace, void* hip_stream) {
     int rc = validate(d);

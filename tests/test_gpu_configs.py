@@ -41,3 +41,15 @@ def test_config5_full_size_gpu_against_oracle_on_sampled_heads():
         res = pu.compare(sub, g, ref)
         print({k: f"{r:.2e}/{a:.2e}" for k, (r, a) in res.items()}, flush=True)
         pu.assert_close(sub, res)
+
+
+@pytest.mark.gpu
+def test_headline_workload_runs_on_the_staged_kernels():
+    """The planner refuses kernels that spill registers (known only with a device).  The staged kernels of the headline
+    workload sit a register or two below their budget: if a change makes one of them spill, the planner silently falls
+    back to the generic kernel, which is 1.5x to 2x slower.  This test makes that loud."""
+    w = synth.CONFIGS[1]
+    d = api.make_desc(w.cell, w.T, w.B, w.NH, w.D, api.FLASHRNN_BF16)
+    for bwd in (False, True):
+        staged, bt, split = api.flashrnn_plan_kernel(d, bwd)
+        assert staged and bt == 4 and split == 1, (bwd, staged, bt, split)
