@@ -136,6 +136,7 @@ def main():
     peak = PEAK_BF16_MFMA_TFLOPS if bf16 else PEAK_F32_MFMA_TFLOPS
     achieved = flops_launch / (dom_ms * 1e-3) / 1e12 if dom_ms > 0 else 0.0
     wgs, per_head, waves = api.flashrnn_plan(desc, dom_bwd)
+    staged, batch_tile, split = api.flashrnn_plan_kernel(desc, dom_bwd)
     esz = 2 if bf16 else 4
     nc = 5 if w.cell == synth.CELL_SLSTM else 4
     if dom_bwd:   # reads: saved values, states t and t-1 (what the cell needs), dH; writes dWx
@@ -160,7 +161,8 @@ def main():
         "unit": "TFLOP/s", "frac": achieved / peak, "traffic": traffic,
         "launch_ms": round(dom_ms, 5), "launches_timed": nb if dom_bwd else nf,
         "flops_per_launch": flops_launch,
-        "workgroups": wgs, "frac_of_occupied_cus": achieved / (peak * wgs / DEVICE_CUS),
+        "workgroups": wgs, "batch_tile_rows": batch_tile, "staged_kernel": staged, "workgroups_per_group": split,
+        "frac_of_occupied_cus": achieved / (peak * wgs / DEVICE_CUS),
         "mfma_busy_frac_of_occupied_cus": busy,
         "hbm_stream_GBs": round(bytes_launch / (dom_ms * 1e-3) / 1e9, 2) if dom_ms > 0 else None,
         "hbm_frac": (bytes_launch / (dom_ms * 1e-3) / 1e9) / PEAK_HBM_GBS if dom_ms > 0 else None,
