@@ -13,6 +13,9 @@
  *   - All tensors are dense, row major, in the layouts written next to each argument.
  *   - Return value: FLASHRNN_OK (0) or a negative flashrnn_status_t.  Nothing is thrown.
  *   - Calls that share a workspace must not overlap in time.
+ *   - flashrnn_fwd and flashrnn_bwd record only kernel launches on the stream (no allocation, no memset, no
+ *     synchronization): after one ordinary call with the same descriptor (kernel attributes are set on first use)
+ *     they may be captured into a HIP graph and replayed.
  *
  * Index names:  T time steps, B batch, NH heads, D units per head, G gates, S states.
  *   Gate order on the G axis:  LSTM, sLSTM: i, f, z, o     GRU: r, z, n     Elman: one gate     GRU4: z, r, n, g

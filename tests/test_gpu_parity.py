@@ -203,3 +203,50 @@ def test_binding_rejects_wrong_shapes_and_dtypes():
     rc = api.lib().flashrnn_fwd(ctypes.byref(d), Wx.data_ptr(), R.data_ptr(), b.data_ptr(), None, st.data_ptr(), None,
                                 ws.data_ptr() + 8, None)
     assert rc == api.FLASHRNN_ERR_WORKSPACE
+
+
+@pytest.mark.parametrize("D", [64, 256])
+def test_forward_backward_replay_from_a_hip_graph(D):
+    """The two entry points allocate nothing and record only kernels, so a caller may capture them.  The graph is replayed
+    several times, with eager work and synchronizations in between, on changing inputs; every replay must reproduce the eager
+    result bit for bit (one workgroup per group, and a head split over workgroups with its exchange buffers)."""
+    w = Workload(f"graph_D{D}", CELL_SLSTM, 12, 8, 2, D, "bf16", True, bias="forget3", init="uniform0.1", seed=D)
+    inp = synth.make_inputs(w)
+    Wx, R, b = (pu.to_device(inp[k], "bf16") for k in ("Wx", "R", "b"))
+    s0, dH = pu.to_device(inp["states0"], "f32"), pu.to_device(inp["dH"], "bf16")
+    desc = api.make_desc(w.cell, w.T, w.B, w.NH, w.D, api.FLASHRNN_BF16)
+    ws = api.alloc_workspace(desc, "cuda")
+    states = torch.empty((w.T + 1, w.S, w.B, w.NH, w.D), dtype=torch.float32, device="cuda")
+    cache = torch.empty(api.flashrnn_gate_cache_bytes(desc), dtype=torch.uint8, device="cuda")
+    out = (torch.empty((w.T, w.B, w.G, w.NH, w.D), dtype=torch.bfloat16, device="cuda"), torch.empty((w.NH, w.D, w.G, w.D), device="cuda"),
+           torch.empty((w.NH, w.G, w.D), device="cuda"), torch.empty((w.S, w.B, w.NH, w.D), device="cuda"))
+
+    def step():
+        api.flashrnn_fwd(w.cell, Wx, R, b, s0, workspace=ws, states=states, gate_cache=cache)
+        api.flashrnn_bwd(w.cell, R, b, states, cache, dH, None, workspace=ws, out=out)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [t.clone() for t in (states,) + out]
+
+    step()                       # warm-up outside the capture (kernel attributes are set on first use)
+    api.flashrnn_check(desc, ws)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        Wx.copy_(torch.roll(Wx, 1, dims=0))          # new inputs, same buffers
+        dH.mul_(-1.0)
+        step()
+        eager = snapshot()
+        for t in (states,) + out:
+            t.fill_(float("nan"))
+        graph.replay()
+        replayed = snapshot()
+        api.flashrnn_check(desc, ws)
+        for a, r in zip(eager, replayed):
+            assert torch.equal(a, r), f"replay {rep} differs from the eager result"
