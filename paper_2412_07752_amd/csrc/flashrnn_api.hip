@@ -156,17 +156,18 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
         }
     }
     if (!pl.e && force_multi != 0) {
-        const int cap = cus / kXcds - 2;                 // workgroups of one launch per XCD, with a margin
+        int cap = cus / kXcds - 2;                       // workgroups of one launch per XCD, with a margin
         const int NG = d->NH * ((d->B + 15) / 16);
         const int want_ks = force_ks ? force_ks : (d->D >= 512 ? 4 : 1);
         const KernelEntry* best = nullptr;
-        for (int pass = 0; pass < 2 && !best; ++pass) {
-            for (int i = 0; i < tab.count; ++i) {
-                const KernelEntry& e = tab.entries[i];
-                if (e.bwd != bwd || !e.multi || e.KT * e.KS * kstep != kdim) continue;
-                if (pass == 0 && e.KS != want_ks) continue;
-                if (!best || e.maxw > best->maxw) best = &e;
-            }
+        for (int i = 0; i < tab.count; ++i) {
+            const KernelEntry& e = tab.entries[i];
+            const int dk = e.KT * e.KS * kstep;
+            if (e.bwd != bwd || !e.multi || dk < kdim) continue;
+            // least padding of the contraction axis first, then the wanted number of slices, then the most waves
+            const int bdk = best ? best->KT * best->KS * kstep : 0;
+            const bool want = e.KS == want_ks, bwant = best && best->KS == want_ks;
+            if (!best || dk < bdk || (dk == bdk && (want > bwant || (want == bwant && e.maxw > best->maxw)))) best = &e;
         }
         if (best) {
             const int nwu_max = best->maxw / best->KS;
@@ -188,6 +189,12 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
                 // even the fewest workgroups per group do not fit all groups: loop over groups
                 for (int nwu = nwu_max; nwu >= 1 && !chosen; --nwu)
                     if (units16 % nwu == 0 && units16 / nwu <= cap) chosen = nwu;
+                if (!chosen && units16 % nwu_max == 0 && units16 / nwu_max <= cus / kXcds) {
+                    // the largest heads need every CU of an XCD for one group (no margin: should a CU be taken, the
+                    // waits run into their spin limit and the call reports a timeout)
+                    chosen = nwu_max;
+                    cap = cus / kXcds;
+                }
                 if (chosen) gpar = kXcds * (cap / (units16 / chosen));
                 if (gpar > NG) gpar = NG;
             }

@@ -347,7 +347,7 @@ __device__ __forceinline__ void reduce_slices(float* red, int parity, int ks, in
 // CELL, BF16 (I/O dtype), KT k-steps per wave, KS contraction slices, BT valid batch slots per tile,
 // MULTI several workgroups per group, MAXW launch bound in waves.
 // p.R is the packed forward copy of R: Rt[n][g][e][k], k < DK = KT*KS*KSTEP, zero beyond D.
-// The launch guarantees P * NWU * 16 == D, and with MULTI also DK == D.
+// The launch guarantees P * NWU * 16 == D and DK >= D (operand rows and packed R are zero beyond D).
 // Global addresses are formed as (uniform base advanced per step on the scalar unit) + (32-bit lane offset).
 template <bool BF16> constexpr int poll_chunk(int KT) {
     if (!BF16) return 8;
@@ -451,6 +451,10 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
                 for (int i = 0; i < PP; ++i) st[eb][s][i] = 0.0f;
             store_io_r<false, PP>(make_rsrc(st_g), soff_st + eb * 64, s * st_state, st[eb][s]);
         }
+        if constexpr (MULTI) {   // the polled rows fill the first D elements; the padding up to DK stays zero
+            __syncthreads();
+            for (int j = threadIdx.x; j < 16 * HP * ESZ / 4; j += blockDim.x) ((uint32_t*)hbuf)[j] = 0u;
+        }
         if constexpr (!MULTI) {
             __syncthreads();  // the previous group is done with the operand rows
             for (int j = threadIdx.x; j < 2 * BUF / 4; j += blockDim.x) ((uint32_t*)hbuf)[j] = 0u;
@@ -505,8 +509,8 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
                 const uint32_t cnt = (uint32_t)iter * (uint32_t)T + (uint32_t)(t - 1);
                 __syncthreads();   // every wave has read the previous step's rows
                 if (!failed)
-                    failed = !poll_rows_to_lds(xr, (cnt & 1u) * xbuf + xgroup, XROW, XROW / 16, hbuf, HP * ESZ, cnt + 1u, p.spin_limit, p.err,
-                                               threadIdx.x, blockDim.x);
+                    failed = !poll_rows_to_lds(xr, (cnt & 1u) * xbuf + xgroup, XROW, (uint32_t)D * (BF16 ? 4 : 8) / 16, hbuf, HP * ESZ, cnt + 1u,
+                                               p.spin_limit, p.err, threadIdx.x, blockDim.x);
                 __syncthreads();
 #pragma unroll
                 for (int kc = 0; kc < KT; kc += KC) {
@@ -687,9 +691,9 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
             for (int i = 0; i < PP; ++i) dbacc[eb][g][i] = 0.0f;
         }
 
-        if constexpr (!MULTI) {
+        {   // operand rows start from zero (with MULTI one buffer: the polled rows fill the first G*D elements)
             __syncthreads();
-            for (int j = threadIdx.x; j < 2 * BUF / 4; j += blockDim.x) ((uint32_t*)gbuf)[j] = 0u;
+            for (int j = threadIdx.x; j < (MULTI ? 1 : 2) * BUF / 4; j += blockDim.x) ((uint32_t*)gbuf)[j] = 0u;
             __syncthreads();
         }
 
@@ -786,8 +790,8 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
                 const uint32_t cnt = (uint32_t)iter * (uint32_t)T + (uint32_t)(T - t);
                 __syncthreads();   // every wave has read the previous step's rows
                 if (!failed)
-                    failed = !poll_rows_to_lds(xr, (cnt & 1u) * xbuf + xgroup, XROW, XROW / 16, gbuf, HP * ESZ, cnt + 1u, p.spin_limit, p.err,
-                                               threadIdx.x, blockDim.x);
+                    failed = !poll_rows_to_lds(xr, (cnt & 1u) * xbuf + xgroup, XROW, (uint32_t)(G * D) * (BF16 ? 4 : 8) / 16, gbuf, HP * ESZ, cnt + 1u,
+                                               p.spin_limit, p.err, threadIdx.x, blockDim.x);
                 __syncthreads();
 #pragma unroll
                 for (int kc = 0; kc < KT; kc += KC) {

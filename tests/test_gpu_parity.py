@@ -119,6 +119,22 @@ def test_recurrent_gradient_clip(cell, clip, dtype, D, env):
         assert np.abs(ref_free["dWx"] - gpu["dWx"]).max() > 1e-3
 
 
+@pytest.mark.parametrize("cell", [CELL_LSTM, CELL_GRU, CELL_SLSTM])
+@pytest.mark.parametrize("dtype,D", [("bf16", 208), ("bf16", 320), ("bf16", 640), ("f32", 144), ("f32", 208)])
+def test_split_groups_with_padded_contraction(cell, dtype, D):
+    """Head sizes between the instantiated contraction lengths: the exchanged rows and the packed R are zero beyond D."""
+    w = Workload(f"pad_{cell}_{dtype}_D{D}", cell, 5, 5, 1 if D > 400 else 2, D, dtype, True, bias="uniform0.1", init="uniform0.1", seed=D)
+    _check(w, with_dlast=True)
+
+
+def test_largest_head_takes_a_whole_xcd():
+    """D = 1024 in one head: 32 workgroups (every CU of one XCD) x 2 unit waves x 4 contraction slices."""
+    w = Workload("lstm_D1024", CELL_LSTM, 4, 5, 1, 1024, "bf16", True, seed=9)
+    _check(w)
+    d = api.make_desc(CELL_LSTM, 4, 5, 1, 1024, api.FLASHRNN_BF16)
+    assert api.flashrnn_plan(d)[0] == 32 and api.flashrnn_plan_kernel(d)[2] == 32
+
+
 @pytest.mark.parametrize("cell", CELLS)
 def test_group_loop_when_groups_do_not_fit(cell):
     """More groups than run at once: workgroups loop over groups and reload R per head."""
