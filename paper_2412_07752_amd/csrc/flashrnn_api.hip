@@ -156,62 +156,72 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
         }
     }
     if (!pl.e && force_multi != 0) {
-        int cap = cus / kXcds - 2;                       // workgroups of one launch per XCD, with a margin
-        const int NG = d->NH * ((d->B + 15) / 16);
+        // Batch tiles of 16, 8 or 4 rows here too.  A smaller tile means more groups (each with its own workgroups, on its
+        // own XCD when there are few) and proportionally less to exchange and less point-wise work per workgroup; the
+        // smallest tile whose groups all run at once is taken, else the largest (fewest rounds over the groups).
         const int want_ks = force_ks ? force_ks : (d->D >= 512 ? 4 : 1);
-        const KernelEntry* best = nullptr;
-        for (int i = 0; i < tab.count; ++i) {
-            const KernelEntry& e = tab.entries[i];
-            const int dk = e.KT * e.KS * kstep;
-            if (e.bwd != bwd || !e.multi || dk < kdim) continue;
-            // least padding of the contraction axis first, then the wanted number of slices, then the most waves
-            const int bdk = best ? best->KT * best->KS * kstep : 0;
-            const bool want = e.KS == want_ks, bwant = best && best->KS == want_ks;
-            if (!best || dk < bdk || (dk == bdk && (want > bwant || (want == bwant && e.maxw > best->maxw)))) best = &e;
-        }
-        if (best) {
-            const int nwu_max = best->maxw / best->KS;
-            // most workgroups per group (shortest MFMA and point-wise phase per step) that still lets
-            // every group run at once; fall back to looping over groups
-            const int slots = (NG + kXcds - 1) / kXcds;       // groups per XCD if all run at once
-            int chosen = 0;
-            // (at least four waves per workgroup where the shape allows: the workgroup polls the group's rows
-            // together, and with fewer threads that takes more rounds - measured on D = 256 and 768)
-            const int nwu_min = 4 / best->KS > 1 ? 4 / best->KS : 1;
-            for (int pass = 0; pass < 2 && !chosen; ++pass)
-                for (int nwu = pass == 0 ? nwu_min : 1; nwu <= nwu_max; ++nwu) {
-                    if (units16 % nwu) continue;
-                    const int P = units16 / nwu;
-                    if (force_nwu ? nwu == force_nwu : P * slots <= cap) { chosen = nwu; break; }
+        const int bts[3] = {4, 8, 16};
+        for (int pass = 0; pass < 2 && !pl.e; ++pass) {
+            for (int bi = 0; bi < 3 && !pl.e; ++bi) {
+                const int BT = pass == 0 ? bts[bi] : bts[2 - bi];
+                if (force_bt && BT != force_bt) continue;
+                int cap = cus / kXcds - 2;                       // workgroups of one launch per XCD, with a margin
+                const int NG = d->NH * ((d->B + BT - 1) / BT);
+                const KernelEntry* best = nullptr;
+                for (int i = 0; i < tab.count; ++i) {
+                    const KernelEntry& e = tab.entries[i];
+                    const int dk = e.KT * e.KS * kstep;
+                    if (e.bwd != bwd || !e.multi || e.BT != BT || dk < kdim) continue;
+                    // least padding of the contraction axis first, then the wanted number of slices, then the most waves
+                    const int bdk = best ? best->KT * best->KS * kstep : 0;
+                    const bool want = e.KS == want_ks, bwant = best && best->KS == want_ks;
+                    if (!best || dk < bdk || (dk == bdk && (want > bwant || (want == bwant && e.maxw > best->maxw)))) best = &e;
                 }
-            int gpar = NG;
-            if (!chosen) {
-                // even the fewest workgroups per group do not fit all groups: loop over groups
-                for (int nwu = nwu_max; nwu >= 1 && !chosen; --nwu)
-                    if (units16 % nwu == 0 && units16 / nwu <= cap) chosen = nwu;
-                if (!chosen && units16 % nwu_max == 0 && units16 / nwu_max <= cus / kXcds) {
-                    // the largest heads need every CU of an XCD for one group (no margin: should a CU be taken, the
-                    // waits run into their spin limit and the call reports a timeout)
-                    chosen = nwu_max;
-                    cap = cus / kXcds;
+                if (!best) continue;
+                const int nwu_max = best->maxw / best->KS;
+                // most workgroups per group (shortest MFMA and point-wise phase per step) that still lets
+                // every group run at once; fall back to looping over groups
+                const int slots = (NG + kXcds - 1) / kXcds;       // groups per XCD if all run at once
+                int chosen = 0;
+                // (at least four waves per workgroup where the shape allows: the workgroup polls the group's rows
+                // together, and with fewer threads that takes more rounds - measured on D = 256 and 768)
+                const int nwu_min = 4 / best->KS > 1 ? 4 / best->KS : 1;
+                for (int p2 = 0; p2 < 2 && !chosen; ++p2)
+                    for (int nwu = p2 == 0 ? nwu_min : 1; nwu <= nwu_max; ++nwu) {
+                        if (units16 % nwu) continue;
+                        const int P = units16 / nwu;
+                        if (force_nwu ? nwu == force_nwu : P * slots <= cap) { chosen = nwu; break; }
+                    }
+                int gpar = NG;
+                if (!chosen && pass == 0 && !force_bt) continue;      // not all groups at once with this tile: try a larger one
+                if (!chosen) {
+                    // even the fewest workgroups per group do not fit all groups: loop over groups
+                    for (int nwu = nwu_max; nwu >= 1 && !chosen; --nwu)
+                        if (units16 % nwu == 0 && units16 / nwu <= cap) chosen = nwu;
+                    if (!chosen && units16 % nwu_max == 0 && units16 / nwu_max <= cus / kXcds) {
+                        // the largest heads need every CU of an XCD for one group (no margin: should a CU be taken, the
+                        // waits run into their spin limit and the call reports a timeout)
+                        chosen = nwu_max;
+                        cap = cus / kXcds;
+                    }
+                    if (chosen) gpar = kXcds * (cap / (units16 / chosen));
+                    if (gpar > NG) gpar = NG;
                 }
-                if (chosen) gpar = kXcds * (cap / (units16 / chosen));
-                if (gpar > NG) gpar = NG;
-            }
-            if (chosen && force_gpar > 0 && force_gpar < gpar) gpar = force_gpar;
-            if (chosen) {
-                pl.e = best;
-                pl.NWU = chosen;
-                pl.P = units16 / chosen;
-                pl.NG = NG;
-                pl.GPAR = gpar;
-                pl.grid = (gpar + kXcds - 1) / kXcds * pl.P * kXcds;
-                pl.block = 64 * chosen * best->KS;
-                pl.DK = best->KT * best->KS * kstep;
-                const int nt = bwd ? 1 : G;
-                // one buffer of 16 operand rows (polled once per workgroup and step), then the partial sums of the slices
-                pl.smem = (size_t)16 * (pl.DK + (bf ? 8 : 4)) * (bf ? 2 : 4) + (best->KS > 1 ? (size_t)2 * (best->KS - 1) * chosen * nt * 4 * 64 * 4 : 16);
-                pl.exch_bytes = (size_t)2 * gpar * 16 * pl.DK * (bf ? 4 : 8);
+                if (chosen && force_gpar > 0 && force_gpar < gpar) gpar = force_gpar;
+                if (chosen) {
+                    pl.e = best;
+                    pl.NWU = chosen;
+                    pl.P = units16 / chosen;
+                    pl.NG = NG;
+                    pl.GPAR = gpar;
+                    pl.grid = (gpar + kXcds - 1) / kXcds * pl.P * kXcds;
+                    pl.block = 64 * chosen * best->KS;
+                    pl.DK = best->KT * best->KS * kstep;
+                    const int nt = bwd ? 1 : G;
+                    // one buffer of BT operand rows (polled once per workgroup and step), then the partial sums of the slices
+                    pl.smem = (size_t)BT * (pl.DK + (bf ? 8 : 4)) * (bf ? 2 : 4) + (best->KS > 1 ? (size_t)2 * (best->KS - 1) * chosen * nt * 4 * 64 * 4 : 16);
+                    pl.exch_bytes = (size_t)2 * gpar * BT * pl.DK * (bf ? 4 : 8);
+                }
             }
         }
     }

@@ -11,6 +11,7 @@
 //     in registers for all T steps, paper Sec. 5.2), h_{t-1} (or the gate gradients) is the B operand.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <type_traits>
 #include <stdint.h>
 
 namespace flashrnn {
@@ -190,6 +191,28 @@ template <int BT> __device__ __forceinline__ void compact_tile(f32x4& a) {
         a[0] = dpp_row_shr<4, 0x2>(a[0], a[1]);
         a[0] = dpp_row_shr<8, 0x4>(a[0], a[2]);
         a[0] = dpp_row_shr<12, 0x8>(a[0], a[3]);
+    }
+}
+
+// The inverse of compact_tile for one value per pair: the lanes c < BT of a row collect the four consecutive
+// units 4q..4q+3 of their batch slot from the lanes that computed them (valid in those lanes only).
+template <int BT, int PP> __device__ __forceinline__ void expand_tile(const float (&v)[PP], float (&out)[4]) {
+    auto shl = [](float x, auto n) {   // lane i takes the value of lane i + n of its row
+        constexpr int N = decltype(n)::value;
+        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x100 + N, 0xF, 0xF, false));
+    };
+    if constexpr (BT == 16) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) out[i] = v[i];
+    } else if constexpr (BT == 8) {
+        out[0] = v[0]; out[1] = v[1];
+        out[2] = shl(v[0], std::integral_constant<int, 8>{});
+        out[3] = shl(v[1], std::integral_constant<int, 8>{});
+    } else {
+        out[0] = v[0];
+        out[1] = shl(v[0], std::integral_constant<int, 4>{});
+        out[2] = shl(v[0], std::integral_constant<int, 8>{});
+        out[3] = shl(v[0], std::integral_constant<int, 12>{});
     }
 }
 

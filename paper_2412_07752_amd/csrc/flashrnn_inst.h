@@ -35,9 +35,13 @@ static const KernelEntry kEntries[] = {
     FRNN_FB(6, 1, 16, 0, 12) FRNN_TILE(6, 3, 8, 12) FRNN_TILE(6, 3, 4, 12) FRNN_BTL(6, 1, 8, 12) FRNN_BTL(6, 1, 4, 12)
     FRNN_FBE(4, 16, 4, 2) FRNN_FBE(4, 8, 4, 2) FRNN_FBE(4, 4, 4, 2)
     FRNN_FBE(6, 16, 4, 3) FRNN_FBE(6, 8, 4, 3) FRNN_FBE(6, 4, 4, 3)
-    FRNN_FB(2, 1, 16, 1, 4) FRNN_FB(4, 1, 16, 1, 4) FRNN_FB(6, 1, 16, 1, 4) FRNN_FB(1, 4, 16, 1, 4)
-    FRNN_FB(8, 1, 16, 1, 8) FRNN_FB(12, 1, 16, 1, 8) FRNN_FB(16, 1, 16, 1, 4) FRNN_FB(24, 1, 16, 1, 4)
-    FRNN_FB(6, 4, 16, 1, 8) FRNN_FB(8, 4, 16, 1, 8)
+#define FRNN_MULTI_SHAPES(BT) \
+    FRNN_FB(2, 1, BT, 1, 4) FRNN_FB(4, 1, BT, 1, 4) FRNN_FB(6, 1, BT, 1, 4) FRNN_FB(1, 4, BT, 1, 4) \
+    FRNN_FB(8, 1, BT, 1, 8) FRNN_FB(12, 1, BT, 1, 8) FRNN_FB(16, 1, BT, 1, 4) FRNN_FB(24, 1, BT, 1, 4) \
+    FRNN_FB(6, 4, BT, 1, 8) FRNN_FB(8, 4, BT, 1, 8)
+    // a head split over workgroups, for batch tiles of 16, 8 and 4 rows (small tiles: more groups, less to exchange)
+    FRNN_MULTI_SHAPES(16) FRNN_MULTI_SHAPES(8) FRNN_MULTI_SHAPES(4)
+#undef FRNN_MULTI_SHAPES
 #else
     FRNN_FB(4, 1, 16, 0, 4) FRNN_FB(8, 1, 16, 0, 4) FRNN_FB(16, 1, 16, 0, 4) FRNN_FB(32, 1, 16, 0, 8)
     FRNN_FB(16, 1, 16, 1, 4) FRNN_FB(32, 1, 16, 1, 4) FRNN_FB(48, 1, 16, 1, 4) FRNN_FB(64, 1, 16, 1, 4)

@@ -226,13 +226,13 @@ __device__ __forceinline__ void stagger_waves(int w) {
 // 8- or 16-byte store, so payload and stamp always arrive together and no fence is needed.  Stores and
 // loads carry the agent-scope cache policy.  Two buffers alternate; writing round r+1 requires having
 // read round r from every member, which implies every member has finished reading round r-1.
-// The 16 operand rows of a group (cpr chunks of 16 bytes = two stamped
+// The operand rows of a group (`rows` of them, cpr chunks of 16 bytes = two stamped
 // words per row, rows xrow bytes apart from byte offset goff of rs) are polled once, NT threads taking consecutive
 // chunks, and their payloads go to LDS rows (lds_pitch bytes apart, plain element order).  The waves then read
 // their MFMA operands from LDS like the one-workgroup kernels do (every wave polling every row in L2 itself
 // measured 1.2x to 1.5x slower at D = 256 and 768).  The loads are marked volatile: every round goes to memory again.
 // Returns false on a timeout (the error word is set; the caller stops waiting from then on).
-__device__ __forceinline__ bool poll_rows_to_lds(__amdgpu_buffer_rsrc_t rs, uint32_t goff, uint32_t xrow, uint32_t cpr, char* lds,
+__device__ __forceinline__ bool poll_rows_to_lds(__amdgpu_buffer_rsrc_t rs, uint32_t goff, uint32_t rows, uint32_t xrow, uint32_t cpr, char* lds,
                                                  uint32_t lds_pitch, uint32_t stamp, int spin_limit, int* err, uint32_t tid, uint32_t NT) {
     constexpr int NB = 8;   // chunks per thread and round (a round costs one L2 round trip: few rounds)
     constexpr int kAuxPoll = (int)(0x80000000u | (unsigned)kAuxAgent);
@@ -241,7 +241,7 @@ __device__ __forceinline__ bool poll_rows_to_lds(__amdgpu_buffer_rsrc_t rs, uint
         __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return false;
     }
-    const uint32_t total = 16u * cpr;
+    const uint32_t total = rows * cpr;
     bool good = true;
     for (uint32_t base = 0; base < total && good; base += NT * NB) {
         uint32_t goffs[NB], loffs[NB];
@@ -285,6 +285,17 @@ __device__ __forceinline__ void publish4(__amdgpu_buffer_rsrc_t rs, uint32_t row
         __builtin_amdgcn_raw_buffer_store_b128(w0, rs, row_off + k * 8, 0, kAuxAgent);
         __builtin_amdgcn_raw_buffer_store_b128(w1, rs, row_off + k * 8 + 16, 0, kAuxAgent);
     }
+}
+
+// A wave publishes its 16 units of the group's BT rows: with BT < 16 the lanes c < BT collect the four consecutive
+// units 4q..4q+3 of their batch row first (every lane holds fewer values there), the other lanes' stores are dropped.
+template <bool BF16, int BT, int PP>
+__device__ __forceinline__ void publish_tile(__amdgpu_buffer_rsrc_t rs, uint32_t group_off, uint32_t xrow, const LaneMap<BT>& lm, int k_wave,
+                                             const float (&v)[PP], uint32_t stamp) {
+    float v4[4];
+    expand_tile<BT, PP>(v, v4);
+    const uint32_t row_off = lm.c < BT ? group_off + (uint32_t)lm.c * xrow : 0x80000000u;
+    publish4<BF16>(rs, row_off, k_wave + 4 * lm.quad, v4, stamp);
 }
 
 // LDS operand row: element type bf16 (as uint16) or float
@@ -368,7 +379,6 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
     constexpr int HP = DK + (BF16 ? 8 : 4);         // LDS row pitch in elements
     constexpr int BUF = BT * HP * ESZ;              // bytes of one LDS operand buffer
     constexpr int KC = poll_chunk<BF16>(KT);
-    static_assert(!MULTI || BT == 16, "several workgroups per group exchange full 16-row tiles");
     static_assert(KS == 1 || MULTI, "contraction slices are only used with several workgroups per group");
     static_assert(!MULTI || KT % KC == 0, "poll chunks must tile the k-steps");
     static_assert(EB == 1 || !MULTI, "several unit blocks per wave only with one workgroup per group");
@@ -386,11 +396,11 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
     const int k0 = ks * KT * OP::KSTEP;
 
     char* hbuf = smem;                                          // !MULTI: [2][BT][HP] operand rows
-    float* red = (float*)(smem + (MULTI ? 16 * HP * ESZ : 0));  // MULTI: one operand buffer [16][HP], then (KS > 1) the partial sums
+    float* red = (float*)(smem + (MULTI ? BUF : 0));            // MULTI: one operand buffer [BT][HP], then (KS > 1) the partial sums
     __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(p.exch, 0, 0x7FFFFFFF, 0x00020000);
     constexpr uint32_t XROW = DK * (BF16 ? 4 : 8);             // bytes per exchange row
-    const uint32_t xgroup = (uint32_t)bm.gpar * 16u * XROW;    // this group's rows inside one buffer
-    const uint32_t xbuf = (uint32_t)p.GPAR * 16u * XROW;       // bytes per buffer
+    const uint32_t xgroup = (uint32_t)bm.gpar * BT * XROW;     // this group's BT rows inside one buffer
+    const uint32_t xbuf = (uint32_t)p.GPAR * BT * XROW;        // bytes per buffer
     bool failed = false;
 
     // uniform strides in bytes
@@ -453,7 +463,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
         }
         if constexpr (MULTI) {   // the polled rows fill the first D elements; the padding up to DK stays zero
             __syncthreads();
-            for (int j = threadIdx.x; j < 16 * HP * ESZ / 4; j += blockDim.x) ((uint32_t*)hbuf)[j] = 0u;
+            for (int j = threadIdx.x; j < BUF / 4; j += blockDim.x) ((uint32_t*)hbuf)[j] = 0u;
         }
         if constexpr (!MULTI) {
             __syncthreads();  // the previous group is done with the operand rows
@@ -465,7 +475,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
         } else {
             if (ks == 0 && T > 0) {
                 const uint32_t cnt = (uint32_t)iter * (uint32_t)T;
-                publish4<BF16>(xr, (cnt & 1u) * xbuf + xgroup + (uint32_t)lm.bslot * XROW, e0, st[0][0], cnt + 1u);
+                publish_tile<BF16, BT, PP>(xr, (cnt & 1u) * xbuf + xgroup, XROW, lm, e_wave, st[0][0], cnt + 1u);
             }
         }
 
@@ -509,7 +519,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
                 const uint32_t cnt = (uint32_t)iter * (uint32_t)T + (uint32_t)(t - 1);
                 __syncthreads();   // every wave has read the previous step's rows
                 if (!failed)
-                    failed = !poll_rows_to_lds(xr, (cnt & 1u) * xbuf + xgroup, XROW, (uint32_t)D * (BF16 ? 4 : 8) / 16, hbuf, HP * ESZ, cnt + 1u,
+                    failed = !poll_rows_to_lds(xr, (cnt & 1u) * xbuf + xgroup, BT, XROW, (uint32_t)D * (BF16 ? 4 : 8) / 16, hbuf, HP * ESZ, cnt + 1u,
                                                p.spin_limit, p.err, threadIdx.x, blockDim.x);
                 __syncthreads();
 #pragma unroll
@@ -553,7 +563,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
                     } else {
                         if (t < T) {
                             const uint32_t cnt = (uint32_t)iter * (uint32_t)T + (uint32_t)t;
-                            publish4<BF16>(xr, (cnt & 1u) * xbuf + xgroup + (uint32_t)lm.bslot * XROW, e0, st[0][0], cnt + 1u);
+                            publish_tile<BF16, BT, PP>(xr, (cnt & 1u) * xbuf + xgroup, XROW, lm, e_wave, st[0][0], cnt + 1u);
                         }
                     }
                 }
@@ -607,7 +617,6 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
     constexpr int HP = DK + (BF16 ? 8 : 4);
     constexpr int BUF = BT * HP * ESZ;
     constexpr int KC = poll_chunk<BF16>(KT);
-    static_assert(!MULTI || BT == 16, "several workgroups per group exchange full 16-row tiles");
     static_assert(KS == 1 || MULTI, "contraction slices are only used with several workgroups per group");
     static_assert(!MULTI || KT % KC == 0, "poll chunks must tile the k-steps");
     static_assert(EB == 1 || !MULTI, "several unit blocks per wave only with one workgroup per group");
@@ -628,8 +637,8 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
     float* red = (float*)(smem + (MULTI ? BUF : 0));  // MULTI: one operand buffer [16][HP], then (KS > 1) the partial sums
     __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(p.exch, 0, 0x7FFFFFFF, 0x00020000);
     constexpr uint32_t XROW = DK * (BF16 ? 4 : 8);
-    const uint32_t xgroup = (uint32_t)bm.gpar * 16u * XROW;
-    const uint32_t xbuf = (uint32_t)p.GPAR * 16u * XROW;
+    const uint32_t xgroup = (uint32_t)bm.gpar * BT * XROW;
+    const uint32_t xbuf = (uint32_t)p.GPAR * BT * XROW;
     bool failed = false;
 
     const uint32_t HD = (uint32_t)NH * D;
@@ -762,7 +771,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
                         const uint32_t cnt = (uint32_t)iter * (uint32_t)T + (uint32_t)(T - t);
 #pragma unroll
                         for (int g2 = 0; g2 < G; ++g2)
-                            publish4<BF16>(xr, (cnt & 1u) * xbuf + xgroup + (uint32_t)lm.bslot * XROW, g2 * D + e0, dg[g2], cnt + 1u);
+                            publish_tile<BF16, BT, PP>(xr, (cnt & 1u) * xbuf + xgroup, XROW, lm, g2 * D + e_wave, dg[g2], cnt + 1u);
                     }
 #pragma unroll
                     for (int g2 = 0; g2 < G; ++g2) store_io_r<BF16, PP>(dwx_t, soff_wx + eb * 16 * ESZ, g2 * wx_gate, dwx[g2]);
@@ -790,7 +799,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
                 const uint32_t cnt = (uint32_t)iter * (uint32_t)T + (uint32_t)(T - t);
                 __syncthreads();   // every wave has read the previous step's rows
                 if (!failed)
-                    failed = !poll_rows_to_lds(xr, (cnt & 1u) * xbuf + xgroup, XROW, (uint32_t)(G * D) * (BF16 ? 4 : 8) / 16, gbuf, HP * ESZ, cnt + 1u,
+                    failed = !poll_rows_to_lds(xr, (cnt & 1u) * xbuf + xgroup, BT, XROW, (uint32_t)(G * D) * (BF16 ? 4 : 8) / 16, gbuf, HP * ESZ, cnt + 1u,
                                                p.spin_limit, p.err, threadIdx.x, blockDim.x);
                 __syncthreads();
 #pragma unroll

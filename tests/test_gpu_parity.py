@@ -70,8 +70,8 @@ def test_batch_tiles(cell, bt):
     ("f32", 64, {"FLASHRNN_NWU": "1"}), ("f32", 128, {"FLASHRNN_KS": "4"}), ("f32", 192, {}), ("f32", 256, {}),
 ])
 def test_groups_split_over_workgroups(cell, dtype, D, env):
-    """A head served by several workgroups that exchange h (forward) / dg (backward) every step."""
-    e = {"FLASHRNN_MULTI": "1"}
+    """A head served by several workgroups that exchange h (forward) / dg (backward) every step (full 16-row tiles)."""
+    e = {"FLASHRNN_MULTI": "1", "FLASHRNN_BT": "16"}
     e.update(env)
     w = Workload(f"multi_{cell}_{dtype}_D{D}", cell, 10, 19, 2, D, dtype, True, bias="uniform0.1", init="uniform0.1", seed=D + 1)
     _check(w, e, with_dlast=True)
@@ -153,11 +153,28 @@ def test_degenerate_lengths(cell, T):
 
 
 def test_large_single_head_split_with_contraction_slices():
-    """D = 768 in one head (R is 4.7 MB): 24 workgroups x 2 unit waves x 4 contraction slices."""
+    """D = 768 in one head (R is 4.7 MB): 24 workgroups x 2 unit waves x 4 contraction slices per group; with batch tiles
+    of 4 rows the 16 rows make 4 groups, one per XCD."""
     w = Workload("lstm_D768", CELL_LSTM, 12, 16, 1, 768, "bf16", True, seed=3)
     _check(w)
-    wg, per_head, waves = api.flashrnn_plan(api.make_desc(CELL_LSTM, 12, 16, 1, 768, api.FLASHRNN_BF16))
-    assert wg == per_head == 24 and waves == 8
+    d = api.make_desc(CELL_LSTM, 12, 16, 1, 768, api.FLASHRNN_BF16)
+    wg, per_head, waves = api.flashrnn_plan(d)
+    staged, bt, split = api.flashrnn_plan_kernel(d)
+    assert (wg, per_head, waves) == (96, 96, 8) and (staged, bt, split) == (False, 4, 24)
+    _check(w, {"FLASHRNN_BT": "16"})
+    assert api.flashrnn_plan(d) == (24, 24, 8)
+
+
+@pytest.mark.parametrize("cell", CELLS)
+@pytest.mark.parametrize("bt", [8, 4])
+@pytest.mark.parametrize("dtype,D,env", [("bf16", 256, {}), ("bf16", 128, {"FLASHRNN_KS": "4"}), ("bf16", 64, {"FLASHRNN_NWU": "1"})])
+def test_split_groups_on_small_batch_tiles(cell, bt, dtype, D, env):
+    """A head split over workgroups with batch tiles of 8 and 4 rows: fewer rows to exchange per group, lanes collect the four
+    units of an exchange word from their neighbours before publishing."""
+    e = {"FLASHRNN_MULTI": "1", "FLASHRNN_BT": str(bt)}
+    e.update(env)
+    w = Workload(f"multibt{bt}_{cell}_D{D}", cell, 9, 13, 2, D, dtype, True, bias="uniform0.1", init="uniform0.1", seed=D + bt)
+    _check(w, e, with_dlast=True)
 
 
 def test_runs_are_bitwise_reproducible():
