@@ -64,21 +64,39 @@ __global__ __launch_bounds__(256) void dr_gemm_kernel(const float* __restrict__ 
     f32x4 ra[2];
     i32x4 rb[2][BW];
     bool oka[2], okb[2];
-    auto load_tiles = [&](int kb) __attribute__((always_inline)) {
-        // rows k = (tt, b): A row = h_{tt}, tt = 0..T-1 is the state before step tt+1
+    // running position of this thread's two rows: contraction index k = (tt, b) and the element offsets of the row in the
+    // states (A operand) and in dWx / the candidate-gradient buffer (B operand), advanced per round without divisions
+    int kk_[2], bb_[2];
+    size_t offA[2], offB[2];
+    const size_t HD = (size_t)NH * D;
+    const int adv_q = TK / B, adv_r = TK % B;   // a round advances adv_q whole time steps + adv_r batch rows
+    const size_t incA0 = (size_t)TK * HD + (size_t)adv_q * (size_t)(S - 1) * B * HD, incA1 = incA0 + (size_t)(S - 1) * B * HD;
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const int k = kbeg + a_kp * 2 + r, tt = k / B;
+        kk_[r] = k;
+        bb_[r] = k - tt * B;
+        offA[r] = ((size_t)tt * S * B + bb_[r]) * HD + (size_t)n * D + d_glob;   // row = h_{tt}: the state before step tt + 1
+        offB[r] = (size_t)k * b_row + b_off;
+    }
+    auto load_tiles = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
-            const int k = kb + a_kp * 2 + r;
-            const int tt = k / B, b = k % B;
-            oka[r] = a_ok && k < kend;
-            okb[r] = b_ok && k < kend;
-            ra[r] = *(const f32x4*)(states + (oka[r] ? ((((size_t)tt * S + 0) * B + b) * NH + n) * D + d_glob : 0));
-            const char* src = b_base + (okb[r] ? (size_t)k * b_row + b_off : 0) * ESZ;   // row k = (tt, b) of dWx or of the candidate-gradient buffer
+            oka[r] = a_ok && kk_[r] < kend;
+            okb[r] = b_ok && kk_[r] < kend;
+            ra[r] = *(const f32x4*)(states + (oka[r] ? offA[r] : 0));
+            const char* src = b_base + (okb[r] ? offB[r] : 0) * ESZ;
 #pragma unroll
             for (int x = 0; x < BW; ++x) rb[r][x] = *(const i32x4*)(src + 16 * x);
+            kk_[r] += TK;
+            offB[r] += (size_t)TK * b_row;
+            int bb = bb_[r] + adv_r;
+            const bool wrap = bb >= B;
+            bb_[r] = wrap ? bb - B : bb;
+            offA[r] += wrap ? incA1 : incA0;
         }
     };
-    load_tiles(kbeg);
+    load_tiles();
     for (int kb = kbeg; kb < kend; kb += TK) {
         __syncthreads();  // previous round's reads are done
         {
@@ -111,7 +129,7 @@ __global__ __launch_bounds__(256) void dr_gemm_kernel(const float* __restrict__ 
             }
         }
         __syncthreads();
-        if (kb + TK < kend) load_tiles(kb + TK);
+        if (kb + TK < kend) load_tiles();
         if constexpr (BF16) {
             bf16x8 af[2], bf[4];
 #pragma unroll
