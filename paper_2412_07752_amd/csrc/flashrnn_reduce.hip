@@ -194,7 +194,15 @@ __global__ void sum_slices2_kernel(const float* __restrict__ part1, float* __res
         part = part2; out = out2; NS = NS2; stride = stride2;
     }
     f32x4 a = f32x4{0.f, 0.f, 0.f, 0.f};
-    for (int s = 0; s < NS; ++s) a += *(const f32x4*)(part + (size_t)s * stride + j);
+    int s = 0;
+    for (; s + 8 <= NS; s += 8) {   // eight loads in flight, added in index order
+        f32x4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = *(const f32x4*)(part + (size_t)(s + u) * stride + j);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) a += v[u];
+    }
+    for (; s < NS; ++s) a += *(const f32x4*)(part + (size_t)s * stride + j);
     *(f32x4*)(out + j) = a;
 }
 
