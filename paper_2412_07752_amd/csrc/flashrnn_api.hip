@@ -248,7 +248,7 @@ int carve(const flashrnn_desc_t* d, Workspace* w, Plan* pf, Plan* pb) {
     w->dgn_off = off; off += align_up(d->cell == FLASHRNN_GRU ? (size_t)d->T * d->B * d->NH * d->D * io_size(d->io_dtype) : 0);
     w->dbpart_off = off; off += align_up((size_t)d->B * d->NH * G * d->D * 4);
     w->drpart_off = off;
-    const int sk = dr_split_k(d->T, d->B, d->NH, d->D, G);
+    const int sk = dr_split_k(d->io_dtype == FLASHRNN_BF16, d->T, d->B, d->NH, d->D, G);
     off += align_up(sk > 1 ? (size_t)sk * d->NH * d->D * G * d->D * 4 : 0);
     w->total = off;
     return FLASHRNN_OK;

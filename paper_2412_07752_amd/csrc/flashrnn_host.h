@@ -37,7 +37,7 @@ KernelTable table_elman_f32();
 KernelTable table_gru4_bf16();
 KernelTable table_gru4_f32();
 
-int dr_split_k(int T, int B, int NH, int D, int G);
+int dr_split_k(bool bf16, int T, int B, int NH, int D, int G);
 hipError_t launch_dr_gemm(bool bf16, const float* states, const void* dWx, const void* dgn, float* part, float* dR, int T, int B,
                           int NH, int D, int G, int S, bool gru, const float* db_part, float* db, hipStream_t stream);
 hipError_t launch_sum_slices(const float* part, float* out, size_t count, int NS, size_t stride, hipStream_t stream);

@@ -170,6 +170,132 @@ __global__ __launch_bounds__(256) void dr_gemm_kernel(const float* __restrict__ 
         }
 }
 
+// bf16 operands, 128 x 256 outputs per workgroup (8 waves, 64 x 64 per wave: 16 MFMAs per 32 contraction rows from 8 LDS
+// reads): less traffic between L2 and the CUs per flop than the 64 x 128 tile.
+template <int WM>
+__global__ __launch_bounds__(WM * 256) void dr_gemm_wide_kernel(const float* __restrict__ states, const void* __restrict__ dWx,
+                                                               const void* __restrict__ dgn, float* __restrict__ out, int T, int B, int NH,
+                                                               int D, int G, int S, int SK, int gru) {
+    constexpr int TMW = 64 * WM, TNW = 256, NT = WM * 256, PITCH = TK + 8;
+    constexpr int NBI = NT >= 512 ? 1 : 2;
+    __shared__ __align__(16) char ldsA[TMW * PITCH * 2];
+    __shared__ __align__(16) char ldsB[TNW * PITCH * 2];
+    const int GD = G * D;
+    const int tiles_n = (GD + TNW - 1) / TNW, tiles_m = (D + TMW - 1) / TMW;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, tiles = tiles_n * tiles_m;
+    const int combo = (slot / tiles) * 8 + xcd, tile = slot % tiles;
+    if (combo >= SK * NH) return;
+    const int tn = tile % tiles_n, tm = tile / tiles_n;
+    const int sk = combo % SK, n = combo / SK;
+    const int K = T * B;
+    const int kchunk = ((K + SK - 1) / SK + TK - 1) / TK * TK;
+    const int kbeg = sk * kchunk, kend = min(K, kbeg + kchunk);
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int c = lane & 15, quad = lane >> 4;
+    const int wm = w >> 2, wn = w & 3;
+    f32x4 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int kp = tid & 15;
+    const int a_d = (tid >> 4) * 4;
+    const int d_glob = tm * TMW + a_d;
+    const bool a_ok = d_glob < D;
+    int b_j[NBI];
+    bool b_ok[NBI];
+    size_t b_off[NBI], b_row[NBI];
+    const char* b_base[NBI];
+#pragma unroll
+    for (int x = 0; x < NBI; ++x) {
+        const int item = (tid >> 4) + x * (NT / 16);
+        b_j[x] = item * 8;
+        const int j_glob = tn * TNW + b_j[x];
+        b_ok[x] = item < 32 && j_glob < GD;
+        const int bg = b_ok[x] ? j_glob / D : 0, be = b_ok[x] ? j_glob % D : 0;
+        const bool from_dgn = gru && bg == 2;
+        b_base[x] = (const char*)(from_dgn ? dgn : dWx);
+        b_row[x] = from_dgn ? (size_t)NH * D : (size_t)G * NH * D;
+        b_off[x] = from_dgn ? (size_t)n * D + be : ((size_t)bg * NH + n) * D + be;
+    }
+    int kk_[2], bb_[2];
+    size_t offA[2];
+    const size_t HD = (size_t)NH * D;
+    const int adv_q = TK / B, adv_r = TK % B;
+    const size_t incA0 = (size_t)TK * HD + (size_t)adv_q * (size_t)(S - 1) * B * HD, incA1 = incA0 + (size_t)(S - 1) * B * HD;
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const int k = kbeg + kp * 2 + r, tt = k / B;
+        kk_[r] = k;
+        bb_[r] = k - tt * B;
+        offA[r] = ((size_t)tt * S * B + bb_[r]) * HD + (size_t)n * D + d_glob;
+    }
+    f32x4 ra[2];
+    i32x4 rb[NBI][2];
+    bool okr[2];
+    auto load_tiles = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            okr[r] = kk_[r] < kend;
+            ra[r] = *(const f32x4*)(states + ((a_ok && okr[r]) ? offA[r] : 0));
+#pragma unroll
+            for (int x = 0; x < NBI; ++x)
+                rb[x][r] = *(const i32x4*)(b_base[x] + ((b_ok[x] && okr[r]) ? (size_t)kk_[r] * b_row[x] + b_off[x] : 0) * 2);
+            kk_[r] += TK;
+            int bb = bb_[r] + adv_r;
+            const bool wrap = bb >= B;
+            bb_[r] = wrap ? bb - B : bb;
+            offA[r] += wrap ? incA1 : incA0;
+        }
+    };
+    load_tiles();
+    for (int kb = kbeg; kb < kend; kb += TK) {
+        __syncthreads();
+        {
+            f32x4 a0 = ra[0], a1 = ra[1];
+            if (!(a_ok && okr[0])) a0 = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (!(a_ok && okr[1])) a1 = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) *(uint32_t*)(ldsA + ((a_d + i) * PITCH + kp * 2) * 2) = pack_bf16x2(a0[i], a1[i]);
+#pragma unroll
+            for (int x = 0; x < NBI; ++x) {
+                if (NBI == 1 && tid >= 512) break;
+                const i32x4 b0 = (b_ok[x] && okr[0]) ? rb[x][0] : i32x4{0, 0, 0, 0};
+                const i32x4 b1 = (b_ok[x] && okr[1]) ? rb[x][1] : i32x4{0, 0, 0, 0};
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const uint32_t x0 = (uint32_t)b0[i >> 1], x1 = (uint32_t)b1[i >> 1];
+                    const uint32_t v = (i & 1) ? ((x1 & 0xFFFF0000u) | (x0 >> 16)) : ((x1 << 16) | (x0 & 0xFFFFu));
+                    *(uint32_t*)(ldsB + ((b_j[x] + i) * PITCH + kp * 2) * 2) = v;
+                }
+            }
+        }
+        __syncthreads();
+        if (kb + TK < kend) load_tiles();
+        bf16x8 af[4], bf[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) af[i] = *(const bf16x8*)(ldsA + ((wm * 64 + i * 16 + c) * PITCH + quad * 8) * 2);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) bf[j] = *(const bf16x8*)(ldsB + ((wn * 64 + j * 16 + c) * PITCH + quad * 8) * 2);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+    }
+    float* dst = out + ((size_t)sk * NH + n) * (size_t)D * GD;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int col = tn * TNW + wn * 64 + j * 16 + c;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int row = tm * TMW + wm * 64 + i * 16 + quad * 4 + r;
+                if (row < D && col < GD) dst[(size_t)row * GD + col] = acc[i][j][r];
+            }
+        }
+}
+
 // out[j] = sum_{s < NS} part[s * stride + j], added in index order
 __global__ void sum_slices_kernel(const float* __restrict__ part, float* __restrict__ out, size_t count, int NS, size_t stride) {
     const size_t j = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -252,22 +378,33 @@ hipError_t launch_pack_r(bool bf16, bool bwd, const void* R, void* out, int NH, 
     return hipGetLastError();
 }
 
-int dr_split_k(int T, int B, int NH, int D, int G) {
-    const int tiles = NH * ((D + TM - 1) / TM) * ((G * D + TN - 1) / TN);
+// The 128 x 256 tile moves fewer bytes per flop but needs a large problem: with few output tiles it would take so many
+// contraction slices to fill the chip that writing and adding the partial results costs more than it saves (measured:
+// slower on C2 and C3, 28 % faster on C5).
+static bool dr_use_wide(bool bf16, int NH, int D, int G) { return bf16 && NH * ((D + 127) / 128) * ((G * D + 255) / 256) >= 64; }
+
+int dr_split_k(bool bf16, int T, int B, int NH, int D, int G) {
     const int K = T * B;
     int sk = 1;
+    const int tiles = dr_use_wide(bf16, NH, D, G) ? NH * ((D + 127) / 128) * ((G * D + 255) / 256)
+                                                  : NH * ((D + TM - 1) / TM) * ((G * D + TN - 1) / TN);
     while (tiles * sk < 512 && K / (sk * 2) >= 4 * TK && sk < 64) sk *= 2;
     return sk;
 }
 
 hipError_t launch_dr_gemm(bool bf16, const float* states, const void* dWx, const void* dgn, float* part, float* dR, int T, int B,
                           int NH, int D, int G, int S, bool gru, const float* db_part, float* db, hipStream_t stream) {
-    const int SK = dr_split_k(T, B, NH, D, G);
+    const int SK = dr_split_k(bf16, T, B, NH, D, G);
     const int GD = G * D;
-    const int grid = (NH * SK + 7) / 8 * 8 * ((D + TM - 1) / TM) * ((GD + TN - 1) / TN);   // (head, K slice) padded to the 8 XCDs
     float* target = SK == 1 ? dR : part;
-    if (bf16) hipLaunchKernelGGL(dr_gemm_kernel<true>, dim3(grid), dim3(256), 0, stream, states, dWx, dgn, target, T, B, NH, D, G, S, SK, gru ? 1 : 0);
-    else hipLaunchKernelGGL(dr_gemm_kernel<false>, dim3(grid), dim3(256), 0, stream, states, dWx, dgn, target, T, B, NH, D, G, S, SK, gru ? 1 : 0);
+    if (dr_use_wide(bf16, NH, D, G)) {
+        const int grid = (NH * SK + 7) / 8 * 8 * ((D + 127) / 128) * ((GD + 255) / 256);   // (head, K slice) padded to the 8 XCDs
+        hipLaunchKernelGGL(dr_gemm_wide_kernel<2>, dim3(grid), dim3(512), 0, stream, states, dWx, dgn, target, T, B, NH, D, G, S, SK, gru ? 1 : 0);
+    } else {
+        const int grid = (NH * SK + 7) / 8 * 8 * ((D + TM - 1) / TM) * ((GD + TN - 1) / TN);
+        if (bf16) hipLaunchKernelGGL(dr_gemm_kernel<true>, dim3(grid), dim3(256), 0, stream, states, dWx, dgn, target, T, B, NH, D, G, S, SK, gru ? 1 : 0);
+        else hipLaunchKernelGGL(dr_gemm_kernel<false>, dim3(grid), dim3(256), 0, stream, states, dWx, dgn, target, T, B, NH, D, G, S, SK, gru ? 1 : 0);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     // split-K partial sums of dR (if any) and the per-row partial sums of db, each added in index order

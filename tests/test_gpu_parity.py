@@ -135,6 +135,14 @@ def test_largest_head_takes_a_whole_xcd():
     assert api.flashrnn_plan(d)[0] == 32 and api.flashrnn_plan_kernel(d)[2] == 32
 
 
+@pytest.mark.parametrize("cell,NH,D", [(CELL_LSTM, 32, 128), (CELL_GRU, 24, 144), (CELL_SLSTM, 12, 144)])
+def test_weight_gradient_gemm_with_large_tiles(cell, NH, D):
+    """Many heads: the dR GEMM takes its 128 x 256 tile (ragged in both directions at D = 144; GRU: the candidate column of B comes
+    from the recurrent-side gradient buffer), and the contraction over (t, b) has a ragged last round."""
+    w = Workload(f"widegemm_{cell}_NH{NH}_D{D}", cell, 7, 5, NH, D, "bf16", True, bias="uniform0.1", init="uniform0.1", seed=NH + D)
+    _check(w, with_dlast=True)
+
+
 @pytest.mark.parametrize("cell", CELLS)
 def test_group_loop_when_groups_do_not_fit(cell):
     """More groups than run at once: workgroups loop over groups and reload R per head."""
