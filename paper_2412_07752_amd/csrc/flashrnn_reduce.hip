@@ -170,8 +170,9 @@ __global__ __launch_bounds__(256) void dr_gemm_kernel(const float* __restrict__ 
         }
 }
 
-// bf16 operands, 128 x 256 outputs per workgroup (8 waves, 64 x 64 per wave: 16 MFMAs per 32 contraction rows from 8 LDS
-// reads): less traffic between L2 and the CUs per flop than the 64 x 128 tile.
+// bf16 operands, (64 WM) x 256 outputs per workgroup (WM x 4 waves, 64 x 64 per wave: 16 MFMAs per 32 contraction rows from
+// 8 LDS reads): less traffic between L2 and the CUs per flop than the 64 x 128 tile.  Used with WM = 2.  Same loader as above:
+// a thread takes one pair of contraction rows x 4 consecutive d (A) and, the first 512 threads, x 8 consecutive columns (B).
 template <int WM>
 __global__ __launch_bounds__(WM * 256) void dr_gemm_wide_kernel(const float* __restrict__ states, const void* __restrict__ dWx,
                                                                const void* __restrict__ dgn, float* __restrict__ out, int T, int B, int NH,
