@@ -141,9 +141,9 @@ int flashrnn_plan_kernel(const flashrnn_desc_t* desc, int backward, int* staged,
 
 /*
  * Measurement aid (the only state the library keeps; meant for benchmarks, not thread-hot paths).
- * While enabled, every flashrnn_fwd / flashrnn_bwd call records one HIP event immediately before and
- * one immediately after its persistent time-loop kernel, on the call's stream (up to 256 calls per
- * direction; later calls are not recorded).  flashrnn_profile_enable(on) also resets the record.
+ * While enabled, every flashrnn_fwd / flashrnn_bwd call attaches a start and a stop HIP event to the dispatch of
+ * its persistent time-loop kernel on the call's stream (up to 256 calls per direction; later calls are not
+ * recorded).  flashrnn_profile_enable(on) also resets the record.
  * flashrnn_profile_kernel_ms waits for the recorded events and returns the mean duration in
  * milliseconds of the forward (backward = 0) or backward (backward = 1) persistent kernel and the
  * number of launches recorded.
