@@ -120,7 +120,8 @@ int flashrnn_bwd(const flashrnn_desc_t* desc, const void* R, const void* b, cons
  * _KS, _GPAR, _EB, _EBK and _KIND override single choices of the launch planner; they exist for the tests that
  * force every kernel family onto small shapes.  Returns FLASHRNN_OK, FLASHRNN_ERR_TIMEOUT
  * if a cross-CU wait ran into its spin limit (results are then invalid), or FLASHRNN_ERR_LAUNCH.
- * workspace may be NULL (returns OK).
+ * workspace may be NULL (returns OK).  A shape whose plans never wait across CUs (one workgroup per group) cannot
+ * time out: the call then only synchronizes the stream.
  */
 int flashrnn_check(const flashrnn_desc_t* desc, const void* workspace, void* hip_stream);
 

@@ -404,10 +404,14 @@ int flashrnn_bwd(const flashrnn_desc_t* d, const void* R, const void* b, const v
     const int G = num_gates(d->cell), S = num_states(d->cell);
     const bool bf = d->io_dtype == FLASHRNN_BF16;
     if (pb.exch_bytes && launch_fill_zero(ws + w.exch_off, align_up(pb.exch_bytes), stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
-    if (launch_pack_r(bf, true, R, ws + w.rpack_off, d->NH, d->D, G, pb.DK, (int*)(ws + w.err_off), stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
+    // The backward copy of R is R itself, padded along (gate, unit) to the kernel's contraction length: without padding
+    // and without cross-CU waits (whose error word the packing kernel clears) the kernel reads R where it is.
+    const bool r_in_place = !pb.e->multi && pb.DK == G * d->D;
+    if (!r_in_place && launch_pack_r(bf, true, R, ws + w.rpack_off, d->NH, d->D, G, pb.DK, (int*)(ws + w.err_off), stream) != hipSuccess)
+        return FLASHRNN_ERR_LAUNCH;
     KernelParams kp;
     memset(&kp, 0, sizeof(kp));
-    kp.R = ws + w.rpack_off; kp.states = (float*)const_cast<void*>(states); kp.cache = const_cast<void*>(gate_cache);
+    kp.R = r_in_place ? R : (const void*)(ws + w.rpack_off); kp.states = (float*)const_cast<void*>(states); kp.cache = const_cast<void*>(gate_cache);
     kp.dH = dH; kp.dlast = (const float*)dstates_last; kp.dWx = dWx; kp.dgn = ws + w.dgn_off;
     kp.clip = d->recurrent_grad_clip > 0.0f ? d->recurrent_grad_clip : d->recurrent_grad_clip < 0.0f ? 0.0f : __builtin_inff();
     kp.dstates0 = (float*)dstates0; kp.db_part = (float*)(ws + w.dbpart_off);
@@ -430,10 +434,15 @@ int flashrnn_bwd(const flashrnn_desc_t* d, const void* R, const void* b, const v
 }
 
 int flashrnn_check(const flashrnn_desc_t* d, const void* workspace, void* hip_stream) {
-    (void)d;
     if (!workspace) return FLASHRNN_OK;
     int flag = 0;
     hipStream_t stream = (hipStream_t)hip_stream;
+    {   // plans without cross-CU waits cannot time out and do not maintain the error word
+        Workspace w;
+        Plan pf, pb;
+        if (d && validate(d) == FLASHRNN_OK && carve(d, &w, &pf, &pb) == FLASHRNN_OK && !pf.e->multi && !pb.e->multi)
+            return hipStreamSynchronize(stream) == hipSuccess ? FLASHRNN_OK : FLASHRNN_ERR_LAUNCH;
+    }
     if (hipMemcpyAsync(&flag, workspace, sizeof(int), hipMemcpyDeviceToHost, stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
     if (hipStreamSynchronize(stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
     return flag == 0 ? FLASHRNN_OK : FLASHRNN_ERR_TIMEOUT;
