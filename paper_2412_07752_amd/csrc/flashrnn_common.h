@@ -310,6 +310,8 @@ __device__ __forceinline__ void load_chunk_to_lds(rsrc_t r, char* lds, uint32_t 
 #if defined(__HIP_DEVICE_COMPILE__)
     typedef __attribute__((address_space(3))) char lds_char;
     __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_char*)lds, 16, voff, 0, 0, 0);
+#else
+    (void)r; (void)lds; (void)voff;
 #endif
 }
 
