@@ -7,7 +7,8 @@
  *
  * Conventions for every function below
  *   - All tensor pointers are DEVICE pointers owned by the caller; the library never allocates or
- *     frees device memory and keeps no state between calls.
+ *     frees device memory and keeps no state between calls that a result depends on (it remembers the
+ *     launch plan of the last descriptor per thread, and which kernels it has prepared).
  *   - Calls are asynchronous on the HIP stream passed as `hip_stream` (a hipStream_t cast to void*,
  *     NULL = the default stream).  Buffers must stay valid until the stream has drained.
  *   - All tensors are dense, row major, in the layouts written next to each argument.
@@ -113,15 +114,19 @@ int flashrnn_bwd(const flashrnn_desc_t* desc, const void* R, const void* b, cons
                  void* dstates0, void* workspace, void* hip_stream);
 
 /*
- * Reads the error word the kernels of the last call on this workspace left behind (synchronizes
- * the stream).  The spin limit of the cross-CU waits is 2^21 polls; the environment variable
- * FLASHRNN_SPIN_LIMIT overrides it (a negative value makes every wait give up at once, which
- * exercises this error path without hanging anything).  The environment variables FLASHRNN_MULTI, _BT, _NWU,
- * _KS, _GPAR, _EB, _EBK and _KIND override single choices of the launch planner; they exist for the tests that
- * force every kernel family onto small shapes.  Returns FLASHRNN_OK, FLASHRNN_ERR_TIMEOUT
- * if a cross-CU wait ran into its spin limit (results are then invalid), or FLASHRNN_ERR_LAUNCH.
- * workspace may be NULL (returns OK).  A shape whose plans never wait across CUs (one workgroup per group) cannot
- * time out: the call then only synchronizes the stream.
+ * Reads the error words the kernels of the last forward and the last backward call on this workspace left behind
+ * (synchronizes the stream).  A plan that splits a head over several CUs waits for its partners with a bounded poll
+ * (2^21 polls); if a wait gives up, every kernel still runs to its end, flashrnn_fwd / flashrnn_bwd have long returned
+ * FLASHRNN_OK, and the results are invalid: on such plans (flashrnn_plan_kernel: *split > 1) call this after every
+ * forward / backward pair at the latest.  The forward call's word survives the backward call that follows it (a new
+ * forward call clears both), so one check after the backward call sees a timeout of either.  flashrnn_bwd on a workspace
+ * that no flashrnn_fwd call has used yet: zero its first 256 bytes first.
+ * Returns FLASHRNN_OK, FLASHRNN_ERR_TIMEOUT, or FLASHRNN_ERR_LAUNCH.  workspace may be NULL (returns OK).  A shape whose plans
+ * never wait across CUs (one workgroup per group) cannot time out: the call then only synchronizes the stream.
+ * Test hooks: with FLASHRNN_PLAN_OVERRIDES=1 in the environment when the library is first called, the variables
+ * FLASHRNN_SPIN_LIMIT (a negative value makes every wait give up at once, which exercises this error path without
+ * hanging anything) and FLASHRNN_MULTI, _BT, _NWU, _KS, _GPAR, _EB, _EBK, _KIND (single choices of the launch planner,
+ * to force every kernel family onto small shapes) are read on every call; without it the environment is never read.
  */
 int flashrnn_check(const flashrnn_desc_t* desc, const void* workspace, void* hip_stream);
 

@@ -167,7 +167,8 @@ def alloc_workspace(desc, device):
     n = flashrnn_workspace_bytes(desc)
     if n == 0:
         raise FlashRNNError(FLASHRNN_ERR_UNSUPPORTED, "flashrnn_workspace_bytes")
-    return torch.empty(n, dtype=torch.uint8, device=device)
+    # zero-filled once: a backward call on a workspace that no forward call has used must find clean error words
+    return torch.zeros(n, dtype=torch.uint8, device=device)
 
 
 def flashrnn_fwd(cell, Wx, R, b, states0=None, save_for_backward=True, workspace=None, stream=None, states=None, gate_cache=None):

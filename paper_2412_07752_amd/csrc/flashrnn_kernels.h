@@ -52,12 +52,11 @@ template <bool FAST> struct Cell<CELL_SLSTM, FAST> {
         const float pi = wx[0] + yb[0], pf = wx[1] + yb[1];
         float lf, sf;  // log sig(pf), sig(-pf)
         if constexpr (FAST) {
+            // log sig(f) = min(f, 0) - log(1 + exp(-|f|)): no product that could underflow for large |f|
             const float t = fast_exp2(-kLog2e * fabsf(pf));
             const float r = fast_rcp(1.0f + t);
-            const float tr = t * r;
-            const bool pos = pf >= 0.0f;
-            sf = pos ? tr : r;
-            lf = kLn2 * fast_log2(pos ? r : tr);
+            sf = pf >= 0.0f ? t * r : r;
+            lf = fmaf(kLn2, fast_log2(r), fminf(pf, 0.0f));
         } else {
             lf = pf >= 0.0f ? -log1pf(expf(-pf)) : pf - log1pf(expf(pf));
             sf = 1.0f / (1.0f + expf(pf));

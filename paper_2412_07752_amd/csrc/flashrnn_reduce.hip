@@ -341,11 +341,12 @@ __global__ void fill_zero_kernel(uint32_t* __restrict__ p, size_t count) {
 // Packed copies of R for the persistent kernels (made once per call, R is read once per launch):
 //   forward   Rt[n][g][e][k] = R[n][k][g][e]   (k = previous-state index, padded with zeros to DK)
 //   backward  Rb[n][d][k]    = R[n][d][k]       (k = gate * D + unit,    padded with zeros to DK)
-// The same launch clears the error word of the persistent kernel that follows.
+// The same launch clears the error word of the persistent kernel that follows (the forward one also the backward
+// kernels' word next to it; the backward one leaves the forward word alone, so a forward timeout stays visible).
 template <typename T>
 __global__ void pack_r_fwd_kernel(const T* __restrict__ R, T* __restrict__ out, int NH, int D, int G, int DK, int* __restrict__ err) {
     const size_t j = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (j == 0) *err = 0;
+    if (j == 0) { err[0] = 0; err[1] = 0; }   // a forward call starts a new forward / backward pair: both error words
     const size_t total = (size_t)NH * G * D * DK;
     if (j >= total) return;
     const int k = (int)(j % DK);

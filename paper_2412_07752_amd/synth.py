@@ -45,8 +45,9 @@ class Workload:
     dtype: str            # "f32" or "bf16": dtype of Wx, R, b, dH, dWx
     backward: bool
     bias: str = "zero"    # "zero" | "forget3" | "uniform0.1" | "forget_linspace_3_6"
-    init: str = "zero"    # "zero" | "uniform0.1"
+    init: str = "zero"    # "zero" | "uniform0.1" | "uniform0.1_bounded" (sLSTM: |c_0| <= n_0, so that |h| <= 1 from the start)
     seed: int = 0
+    wx: str = "normal"    # "normal": N(0,1) | "large_mix": N(0,1) plus offsets of 0, +-50, +-100, +-200 (saturated gates)
     extra: dict = field(default_factory=dict)
 
     @property
@@ -84,7 +85,19 @@ def make_inputs(w: Workload):
         return np.random.default_rng([w.seed, k])
 
     out = {}
-    out["Wx"] = rnd(stream(0).standard_normal((T, B, G, NH, D), dtype=np.float32))
+    Wx = stream(0).standard_normal((T, B, G, NH, D), dtype=np.float32)
+    if w.wx == "large_mix":
+        # the regime the sLSTM stabilizer exists for: about a third of the pre-activations far out in either tail
+        levels = np.array([0.0, 0.0, 0.0, 0.0, 50.0, -50.0, 100.0, -100.0, 200.0, -200.0], dtype=np.float32)
+        off = levels[stream(5).integers(0, len(levels), size=Wx.shape)]
+        if w.cell == CELL_SLSTM and w.init == "zero":
+            # an empty cell (n_0 = 0, m_0 = 0) cannot hold exp(i - m) below the float32 range as its normalizer:
+            # the first input gate stays on the non-negative side
+            off[0, :, 0] = np.abs(off[0, :, 0])
+        Wx = Wx + off
+    elif w.wx != "normal":
+        raise ValueError(w.wx)
+    out["Wx"] = rnd(Wx)
     out["R"] = rnd(stream(1).standard_normal((NH, D, G, D), dtype=np.float32) * np.float32(D ** -0.5))
     b = np.zeros((NH, G, D), dtype=np.float32)
     if w.bias == "forget3":
@@ -96,10 +109,12 @@ def make_inputs(w: Workload):
     elif w.bias != "zero":
         raise ValueError(w.bias)
     out["b"] = rnd(b)
-    if w.init == "uniform0.1":
+    if w.init in ("uniform0.1", "uniform0.1_bounded"):
         s0 = stream(3).uniform(0.0, 0.1, size=(S, B, NH, D)).astype(np.float32)
         if w.cell == CELL_SLSTM:
             s0[3] = 0.0  # stabilizer starts at zero
+            if w.init == "uniform0.1_bounded":
+                s0[1] *= s0[2] * np.float32(10.0)   # c_0 in [0, n_0]: the cell keeps |c_t| <= n_t, hence |h_t| <= 1
         out["states0"] = s0  # states are float32 in every configuration
     elif w.init == "zero":
         out["states0"] = None

@@ -2,6 +2,8 @@
 C-ABI library (GPU) on the same seeded inputs, and measure the differences.
 
 Error measure per output tensor: max|gpu - ref| / max(max|ref|, tiny)  ("rel"), and max|gpu - ref| ("abs").
+The states are checked element by element as well: |gpu - ref| <= rel_tol * (|ref| + rms(ref)), so that a small
+element is not hidden behind the tensor's largest value.
 """
 import numpy as np
 import torch
@@ -96,6 +98,19 @@ def compare(w, gpu, ref, scale_ref=None):
     return res
 
 
+def assert_states_elementwise(w, gpu, ref):
+    """Per element and state: |gpu - ref| <= rel_tol * (|ref| + rms(ref))."""
+    rel = TOL_BF16_REL if w.dtype == "bf16" else TOL_F32_REL
+    for s in range(w.S):
+        g, r = np.asarray(gpu["states"][:, s], dtype=np.float64), np.asarray(ref["states"][:, s], dtype=np.float64)
+        if r.size == 0:
+            continue
+        bound = rel * (np.abs(r) + np.sqrt(np.mean(r * r)))
+        bad = np.abs(g - r) > bound
+        assert not bad.any(), f"{w.name} states.{'hcnm'[s]}: {int(bad.sum())} of {r.size} elements off, worst " \
+                              f"{float(np.max(np.abs(g - r) / np.maximum(bound, 1e-300))):.2f} x bound"
+
+
 def assert_close(w, res):
     rel = TOL_BF16_REL if w.dtype == "bf16" else TOL_F32_REL
     for k, (r, a) in res.items():
@@ -103,4 +118,8 @@ def assert_close(w, res):
         # a reference that is identically zero (e.g. dstates0 of the stabilizer) must be matched exactly
         assert r <= rel or a == 0.0, f"{w.name} {k}: rel {r:.3e} abs {a:.3e} > {rel}"
     if w.dtype == "bf16":
-        assert res["states.h"][1] <= TOL_BF16_ABS_H, f"{w.name} h: abs {res['states.h'][1]:.3e}"
+        # max-abs 5e-2 on h is meant for h in its natural range |h| <= 1; initial states a caller passes in can push the
+        # sLSTM's h = o c / n beyond it (|c_0| > n_0), and the bound then scales with max|h|
+        r, a = res["states.h"]
+        h_max = a / r if r > 0 else 0.0
+        assert a <= TOL_BF16_ABS_H * max(1.0, h_max), f"{w.name} h: abs {a:.3e} (max|h| {h_max:.3g})"

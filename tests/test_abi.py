@@ -54,6 +54,16 @@ def test_bad_descriptors_are_rejected_on_the_host(bad):
     assert rc == api.FLASHRNN_ERR_SHAPE
 
 
+def test_time_step_slabs_beyond_32_bit_offsets_are_refused():
+    """The kernels address one time step of a tensor with 32-bit byte offsets: a shape whose per-step slab reaches 2 GiB
+    must be refused, not run with dropped accesses."""
+    d = api.make_desc(2, 4, 4096, 64, 1024, api.FLASHRNN_BF16)   # sLSTM states: 4 * 4 B * 2^28 units per step
+    assert api.flashrnn_workspace_bytes(d) == 0
+    assert api.lib().flashrnn_fwd(ctypes.byref(d), *([None] * 8)) == api.FLASHRNN_ERR_UNSUPPORTED
+    d = api.make_desc(2, 4, 64, 64, 1024, api.FLASHRNN_BF16)
+    assert api.lib().flashrnn_fwd(ctypes.byref(d), *([None] * 8)) == api.FLASHRNN_ERR_NULL
+
+
 def test_unsupported_head_size_and_null_pointers():
     d = api.make_desc(0, 4, 2, 1, 24, api.FLASHRNN_BF16)  # D not a multiple of 16
     assert api.lib().flashrnn_fwd(ctypes.byref(d), *([None] * 8)) == api.FLASHRNN_ERR_UNSUPPORTED

@@ -32,7 +32,7 @@ def _dlast(w, seed=99):
     return rng.standard_normal((w.S, w.B, w.NH, w.D)).astype(np.float32)
 
 
-def _check(w, env=None, with_dlast=False, clip=None):
+def _check(w, env=None, with_dlast=False, clip=None, elementwise=True):
     os.environ.update(env or {})
     print(f"case {w.name} env={env}", flush=True)
     inp = synth.make_inputs(w)
@@ -41,6 +41,8 @@ def _check(w, env=None, with_dlast=False, clip=None):
     gpu = pu.run_gpu(w, inp, dl, clip=clip)
     res = pu.compare(w, gpu, ref)
     pu.assert_close(w, res)
+    if elementwise:
+        pu.assert_states_elementwise(w, gpu, ref)
     return gpu
 
 
@@ -113,8 +115,19 @@ def test_recurrent_gradient_clip(cell, clip, dtype, D, env):
     inp, dl = synth.make_inputs(w), _dlast(w)
     ref, ref_free = pu.run_oracle(w, inp, dl, clip=clip), pu.run_oracle(w, inp, dl)
     gpu = pu.run_gpu(w, inp, dl, clip=clip)
-    # errors relative to the scale of the unclipped gradients (the clip shrinks values, not rounding errors)
-    pu.assert_close(w, pu.compare(w, gpu, ref, scale_ref=ref_free))
+    # errors relative to the scale of the unclipped gradients (the clip shrinks values, not rounding errors) ...
+    res = pu.compare(w, gpu, ref, scale_ref=ref_free)
+    pu.assert_close(w, res)
+    # ... and with an absolute bound: the unclipped run meets the tolerance as it is defined (relative to its own
+    # reference), and clipping must not make any tensor's absolute error larger than twice that run's (or than the
+    # plain tolerance on the clipped reference, whichever is larger)
+    gpu_free = pu.run_gpu(w, inp, dl)
+    res_free = pu.compare(w, gpu_free, ref_free)
+    pu.assert_close(w, res_free)
+    plain = pu.compare(w, gpu, ref)
+    tol = pu.TOL_BF16_REL if dtype == "bf16" else pu.TOL_F32_REL
+    for k, (r, a) in plain.items():
+        assert r <= tol or a <= 2.0 * res_free[k][1] + 1e-30, f"{w.name} {k}: abs {a:.3e} vs unclipped run's {res_free[k][1]:.3e}"
     if clip == 0.02:   # the bound did change the result
         assert np.abs(ref_free["dWx"] - gpu["dWx"]).max() > 1e-3
 
@@ -183,6 +196,83 @@ def test_split_groups_on_small_batch_tiles(cell, bt, dtype, D, env):
     e.update(env)
     w = Workload(f"multibt{bt}_{cell}_D{D}", cell, 9, 13, 2, D, dtype, True, bias="uniform0.1", init="uniform0.1", seed=D + bt)
     _check(w, e, with_dlast=True)
+
+
+LARGE_CASES = [
+    # (dtype, D, environment, batch): staged tile kernels, generic kernels, a head split over workgroups (with and
+    # without contraction slices), f32 single and split
+    ("bf16", 64, {}, 13), ("bf16", 192, {}, 6), ("bf16", 96, {"FLASHRNN_KIND": "0", "FLASHRNN_BT": "4"}, 9),
+    ("bf16", 64, {"FLASHRNN_BT": "16"}, 19), ("bf16", 256, {}, 7), ("bf16", 128, {"FLASHRNN_MULTI": "1", "FLASHRNN_KS": "4"}, 18),
+    ("f32", 64, {}, 5), ("f32", 192, {}, 6),
+]
+
+
+@pytest.mark.parametrize("cell", CELLS)
+@pytest.mark.parametrize("init", ["uniform0.1_bounded", "zero"])
+@pytest.mark.parametrize("dtype,D,env,B", LARGE_CASES)
+def test_saturated_gates(cell, init, dtype, D, env, B):
+    """Finite pre-activations far out in both tails (a third of all Wx entries shifted by +-50, +-100, +-200, on every
+    gate), non-zero R, 12 steps so that the sLSTM stabilizer is carried through jumps in both directions: the regime m
+    exists for (App. A).  Nothing may overflow, underflow into a wrong branch or turn into NaN, forward or backward.
+    Non-zero initial states respect the cell's invariant |c| <= n (|h| <= 1): bf16 rounding of an h of 100 and more would
+    move pre-activations by tenths.  With f32 I/O the element-wise check of the sLSTM states is left to the max-norm one:
+    the stabilizer reaches 230 here, where one float32 ulp is 1.5e-5, and every weight exp(. - m) carries that as a
+    relative error, so single elements sit at 1e-5 to 2e-5."""
+    w = Workload(f"sat_{cell}_{dtype}_D{D}_{init}", cell, 12, B, 2, D, dtype, True, bias="forget3" if cell in (CELL_LSTM, CELL_SLSTM) else "uniform0.1",
+                 init=init, seed=D + B, wx="large_mix")
+    gpu = _check(w, env, with_dlast=True, elementwise=not (cell == CELL_SLSTM and dtype == "f32"))
+    for k, v in gpu.items():
+        assert np.all(np.isfinite(v)), k
+
+
+def test_forward_timeout_survives_the_backward_call():
+    """A split plan whose forward waits gave up: the backward call that follows runs with a normal limit, and one check
+    after it still reports the forward timeout (the two passes keep separate error words; only a forward call clears both)."""
+    w = Workload("sticky", CELL_LSTM, 6, 16, 1, 64, "bf16", True)
+    inp = synth.make_inputs(w)
+    os.environ.update({"FLASHRNN_MULTI": "1", "FLASHRNN_NWU": "1", "FLASHRNN_SPIN_LIMIT": "-1"})
+    Wx, R, b, dH = (pu.to_device(inp[k], "bf16") for k in ("Wx", "R", "b", "dH"))
+    desc = api.make_desc(w.cell, w.T, w.B, w.NH, w.D, api.FLASHRNN_BF16)
+    states, cache, ws = api.flashrnn_fwd(w.cell, Wx, R, b)
+    os.environ["FLASHRNN_SPIN_LIMIT"] = "400000"
+    api.flashrnn_bwd(w.cell, R, b, states, cache, dH, workspace=ws)
+    with pytest.raises(api.FlashRNNError) as ei:
+        api.flashrnn_check(desc, ws)
+    assert ei.value.status == api.FLASHRNN_ERR_TIMEOUT
+    # the next forward / backward pair on the same workspace is clean and correct again
+    ref = pu.run_oracle(w, inp)
+    states, cache, ws = api.flashrnn_fwd(w.cell, Wx, R, b, workspace=ws)
+    dWx, dR, db, ds0 = api.flashrnn_bwd(w.cell, R, b, states, cache, dH, workspace=ws)
+    api.flashrnn_check(desc, ws)
+    gpu = {"states": pu.to_host64(states), "dWx": pu.to_host64(dWx), "dR": pu.to_host64(dR), "db": pu.to_host64(db), "dstates0": pu.to_host64(ds0)}
+    pu.assert_close(w, pu.compare(w, gpu, ref))
+
+
+def test_seeded_random_shapes():
+    """A seeded sweep over (cell, dtype, T, B, NH, D, forward-only / backward, clip, initial states, final-state gradients)
+    with whatever plan the library picks for each shape; stops at the first mismatch and names the case."""
+    import random
+    rng = random.Random(20241207)
+    for it in range(48):
+        cell = rng.choice(CELLS)
+        dtype = rng.choice(["bf16", "bf16", "bf16", "f32"])
+        D = 16 * rng.choice([1, 2, 3, 4, 5, 6, 8, 9, 10, 12, 16, 20, 24] if dtype == "bf16" else [1, 2, 3, 4, 6, 8, 12, 16])
+        NH = rng.choice([1, 2, 3, 5, 8, 20])
+        B = rng.choice([1, 2, 3, 4, 5, 7, 8, 9, 16, 17, 33, 64])
+        T = rng.choice([1, 2, 3, 4, 5, 8, 13])
+        while NH * B * D * T > 400000 and B > 1:
+            B = max(1, B // 2)
+        bw = rng.random() < 0.8
+        clip = rng.choice([None, None, 0.05, 0.0]) if bw else None
+        w = Workload(f"rand{it}", cell, T, B, NH, D, dtype, bw, bias="uniform0.1", init=rng.choice(["zero", "uniform0.1"]), seed=it + 1000)
+        print(f"case {it}: cell {cell} {dtype} T {T} B {B} NH {NH} D {D} bwd {bw} clip {clip}", flush=True)
+        inp = synth.make_inputs(w)
+        dl = _dlast(w, seed=it) if (bw and rng.random() < 0.5) else None
+        ref = pu.run_oracle(w, inp, dl, clip=clip)
+        free = pu.run_oracle(w, inp, dl) if clip is not None else None
+        gpu = pu.run_gpu(w, inp, dl, clip=clip)
+        pu.assert_close(w, pu.compare(w, gpu, ref, scale_ref=free))
+        pu.assert_states_elementwise(w, gpu, ref)
 
 
 def test_runs_are_bitwise_reproducible():

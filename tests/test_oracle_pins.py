@@ -180,6 +180,30 @@ def test_slstm_large_input_gate_is_stable():
     np.testing.assert_allclose(st[1:, 0], math.tanh(0.3) / (1 + math.exp(0.4)), rtol=1e-12)
 
 
+def test_slstm_saturated_gates_match_the_unstabilized_recurrence():
+    """The synthetic "large_mix" recipe of the GPU parity tests (pre-activations shifted by 0, +-50, +-100, +-200): in
+    float64 exp(+-200) is still representable, so over a few steps the unstabilized recurrence is computable and must give
+    the same h.  Catches a stabilizer that is only right for small values (wrong max argument, lost log sig(f) for large |f|)."""
+    from paper_2412_07752_amd import synth
+    w = synth.Workload("sat", CELL_SLSTM, 3, 3, 2, 16, "f32", False, bias="forget3", init="uniform0.1", seed=3, wx="large_mix")
+    inp = synth.make_inputs(w)
+    f64 = lambda a: np.ascontiguousarray(a, dtype=np.float64)
+    Wx, R, b, s0 = f64(inp["Wx"]), f64(inp["R"]), f64(inp["b"]), f64(inp["states0"])
+    assert np.abs(Wx).max() > 150.0
+    st = oracle.fwd(CELL_SLSTM, Wx, R, b, s0)
+    assert np.all(np.isfinite(st))
+    h, c, n = s0[0].copy(), s0[1] * np.exp(s0[3]), s0[2] * np.exp(s0[3])
+    sg = lambda v: 1.0 / (1.0 + np.exp(-v))
+    for t in range(w.T):
+        pre = Wx[t] + np.einsum("bnd,ndge->bgne", h, R) + b.transpose(1, 0, 2)[None]
+        i, f, z, o = pre[:, 0], pre[:, 1], pre[:, 2], pre[:, 3]
+        c = sg(f) * c + np.exp(i) * np.tanh(z)
+        n = sg(f) * n + np.exp(i)
+        h = sg(o) * c / n
+        assert np.all(np.isfinite(c)) and np.all(n > 0)
+        np.testing.assert_allclose(st[t + 1, 0], h, rtol=1e-9, atol=1e-12)
+
+
 # ----------------------------------------------------------------------------------------------
 # closed forms with R = 0 and constant inputs
 # ----------------------------------------------------------------------------------------------
