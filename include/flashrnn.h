@@ -43,7 +43,8 @@ typedef enum {
     FLASHRNN_ERR_UNSUPPORTED = -3, /* D not a multiple of 16 or above 1024 (bf16) / 256 (f32), or a misaligned pointer */
     FLASHRNN_ERR_WORKSPACE = -4,   /* workspace missing or misaligned (needs 256-byte alignment)   */
     FLASHRNN_ERR_LAUNCH = -5,      /* a HIP call failed                                            */
-    FLASHRNN_ERR_TIMEOUT = -6      /* a cross-CU wait gave up (reported by flashrnn_check)         */
+    FLASHRNN_ERR_TIMEOUT = -6,     /* a cross-CU wait gave up (reported by flashrnn_check)         */
+    FLASHRNN_ERR_SCRATCH = -7      /* flashrnn_fwd_static_scratch: the problem needs more than FLASHRNN_STATIC_SCRATCH_BYTES */
 } flashrnn_status_t;
 
 /*
@@ -92,6 +93,22 @@ int flashrnn_fwd(const flashrnn_desc_t* desc, const void* Wx, const void* R, con
                  void* states, void* gate_cache, void* workspace, void* hip_stream);
 
 /*
+ * flashrnn_fwd for callers that can neither allocate device memory nor hand a workspace over (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments without `workspace`, same kernels,
+ * same results bit for bit.  The scratch memory (error words, cross-CU exchange buffers, the packed copy of R) is a
+ * static array of FLASHRNN_STATIC_SCRATCH_BYTES inside the library's code object; every GPU the library runs on holds
+ * its own copy until the process ends.  The call allocates nothing and frees nothing.
+ *   - A problem whose forward scratch does not fit returns FLASHRNN_ERR_SCRATCH (nothing is launched); every one of
+ *     the five benchmark shapes fits (the largest, one head of 768 units, needs 4.6 MiB + exchange buffers).
+ *   - All calls on one GPU share that GPU's array, on whatever stream: calls that overlap in time race.  The array
+ *     keeps the last call's content; what a call needs cleared (exchange stamps, error words) it clears itself.
+ *   - Timeouts of split plans: flashrnn_check(desc, FLASHRNN_STATIC_SCRATCH, stream).
+ */
+#define FLASHRNN_STATIC_SCRATCH_BYTES (16u << 20)
+int flashrnn_fwd_static_scratch(const flashrnn_desc_t* desc, const void* Wx, const void* R, const void* b,
+                                const void* states0, void* states, void* gate_cache, void* hip_stream);
+
+/*
  * Backward pass, BPTT (paper Sec. 4 eq. (3)-(7)), with L depending on h_1..h_T through dH and on the
  * final states through dstates_last:
  *     dg_t = dP/dg ds_t ;  ds_{t-1} = dP/ds ds_t (+ R^T dg_t on the hidden state) ;
@@ -121,13 +138,15 @@ int flashrnn_bwd(const flashrnn_desc_t* desc, const void* R, const void* b, cons
  * forward / backward pair at the latest.  The forward call's word survives the backward call that follows it (a new
  * forward call clears both), so one check after the backward call sees a timeout of either.  flashrnn_bwd on a workspace
  * that no flashrnn_fwd call has used yet: zero its first 256 bytes first.
- * Returns FLASHRNN_OK, FLASHRNN_ERR_TIMEOUT, or FLASHRNN_ERR_LAUNCH.  workspace may be NULL (returns OK).  A shape whose plans
+ * Returns FLASHRNN_OK, FLASHRNN_ERR_TIMEOUT, or FLASHRNN_ERR_LAUNCH.  workspace may be NULL (returns OK) or
+ * FLASHRNN_STATIC_SCRATCH (the array flashrnn_fwd_static_scratch works in, on the current device).  A shape whose plans
  * never wait across CUs (one workgroup per group) cannot time out: the call then only synchronizes the stream.
  * Test hooks: with FLASHRNN_PLAN_OVERRIDES=1 in the environment when the library is first called, the variables
  * FLASHRNN_SPIN_LIMIT (a negative value makes every wait give up at once, which exercises this error path without
  * hanging anything) and FLASHRNN_MULTI, _BT, _NWU, _KS, _GPAR, _EB, _EBK, _KIND (single choices of the launch planner,
  * to force every kernel family onto small shapes) are read on every call; without it the environment is never read.
  */
+#define FLASHRNN_STATIC_SCRATCH ((const void*)(size_t)1)
 int flashrnn_check(const flashrnn_desc_t* desc, const void* workspace, void* hip_stream);
 
 /*

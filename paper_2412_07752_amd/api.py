@@ -13,7 +13,9 @@ FLASHRNN_LSTM, FLASHRNN_GRU, FLASHRNN_SLSTM, FLASHRNN_ELMAN, FLASHRNN_GRU4 = 0, 
 FLASHRNN_F32, FLASHRNN_BF16 = 0, 1
 FLASHRNN_OK = 0
 FLASHRNN_ERR_NULL, FLASHRNN_ERR_SHAPE, FLASHRNN_ERR_UNSUPPORTED = -1, -2, -3
-FLASHRNN_ERR_WORKSPACE, FLASHRNN_ERR_LAUNCH, FLASHRNN_ERR_TIMEOUT = -4, -5, -6
+FLASHRNN_ERR_WORKSPACE, FLASHRNN_ERR_LAUNCH, FLASHRNN_ERR_TIMEOUT, FLASHRNN_ERR_SCRATCH = -4, -5, -6, -7
+FLASHRNN_STATIC_SCRATCH_BYTES = 16 << 20
+STATIC_SCRATCH = "static"   # stands for FLASHRNN_STATIC_SCRATCH in flashrnn_check
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libflashrnn.so")
 _lib = None
@@ -54,6 +56,8 @@ def lib():
         L.flashrnn_workspace_bytes.restype = ctypes.c_size_t
         L.flashrnn_fwd.argtypes = [dp] + [vp] * 8
         L.flashrnn_fwd.restype = ctypes.c_int
+        L.flashrnn_fwd_static_scratch.argtypes = [dp] + [vp] * 7
+        L.flashrnn_fwd_static_scratch.restype = ctypes.c_int
         L.flashrnn_bwd.argtypes = [dp] + [vp] * 12
         L.flashrnn_bwd.restype = ctypes.c_int
         L.flashrnn_check.argtypes = [dp, vp, vp]
@@ -73,7 +77,7 @@ def lib():
 
 
 EXPORTS = ["flashrnn_num_states", "flashrnn_num_gates", "flashrnn_gate_cache_bytes", "flashrnn_workspace_bytes", "flashrnn_fwd",
-           "flashrnn_bwd", "flashrnn_check", "flashrnn_plan", "flashrnn_plan_kernel", "flashrnn_profile_enable", "flashrnn_profile_kernel_ms",
+           "flashrnn_fwd_static_scratch", "flashrnn_bwd", "flashrnn_check", "flashrnn_plan", "flashrnn_plan_kernel", "flashrnn_profile_enable", "flashrnn_profile_kernel_ms",
            "flashrnn_status_string"]
 
 
@@ -171,6 +175,31 @@ def alloc_workspace(desc, device):
     return torch.zeros(n, dtype=torch.uint8, device=device)
 
 
+def flashrnn_fwd_static_scratch(cell, Wx, R, b, states0=None, save_for_backward=True, stream=None, states=None, gate_cache=None):
+    """flashrnn_fwd without a workspace: the library works in its own static device array (no allocation in the call
+    when `states` and `gate_cache` are passed in).  Returns (states, gate_cache or None)."""
+    T, B, G, NH, D = Wx.shape
+    S = flashrnn_num_states(cell)
+    if G != flashrnn_num_gates(cell):
+        raise ValueError("gate axis of Wx does not match the cell")
+    dt = Wx.dtype
+    desc = make_desc(cell, T, B, NH, D, _io_dtype(Wx))
+    _chk(Wx, (T, B, G, NH, D), dt, "Wx")
+    _chk(R, (NH, D, G, D), dt, "R")
+    _chk(b, (NH, G, D), dt, "b")
+    _chk(states0, (S, B, NH, D), torch.float32, "states0", optional=True)
+    if states is None:
+        states = torch.empty((T + 1, S, B, NH, D), dtype=torch.float32, device=Wx.device)
+    _chk(states, (T + 1, S, B, NH, D), torch.float32, "states")
+    if save_for_backward and gate_cache is None:
+        gate_cache = torch.empty(max(flashrnn_gate_cache_bytes(desc), 16), dtype=torch.uint8, device=Wx.device)
+    rc = lib().flashrnn_fwd_static_scratch(ctypes.byref(desc), _ptr(Wx), _ptr(R), _ptr(b), _ptr(states0), _ptr(states),
+                                           _ptr(gate_cache) if save_for_backward else None, _stream(stream))
+    if rc != FLASHRNN_OK:
+        raise FlashRNNError(rc, "flashrnn_fwd_static_scratch")
+    return states, (gate_cache if save_for_backward else None)
+
+
 def flashrnn_fwd(cell, Wx, R, b, states0=None, save_for_backward=True, workspace=None, stream=None, states=None, gate_cache=None):
     """Forward pass.  Wx[T,B,G,NH,D], R[NH,D,G,D], b[NH,G,D] (bf16 or f32), states0[S,B,NH,D] f32 or None.
     Returns (states[T+1,S,B,NH,D] f32, gate_cache or None, workspace)."""
@@ -233,6 +262,7 @@ def flashrnn_bwd(cell, R, b, states, gate_cache, dH, dstates_last=None, workspac
 
 def flashrnn_check(desc, workspace, stream=None):
     """Synchronizes and raises FlashRNNError if a kernel of the last call reported a timeout."""
-    rc = lib().flashrnn_check(ctypes.byref(desc), _ptr(workspace), _stream(stream))
+    ws = ctypes.c_void_p(1) if isinstance(workspace, str) and workspace == STATIC_SCRATCH else _ptr(workspace)
+    rc = lib().flashrnn_check(ctypes.byref(desc), ws, _stream(stream))
     if rc != FLASHRNN_OK:
         raise FlashRNNError(rc, "flashrnn_check")

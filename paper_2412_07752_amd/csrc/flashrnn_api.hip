@@ -350,6 +350,27 @@ int launch_persistent(const Plan& pl, KernelParams& kp, hipStream_t stream) {
     return FLASHRNN_OK;
 }
 
+// Scratch memory of flashrnn_fwd_static_scratch: one array per GPU, part of the loaded code object (no allocation call
+// ever).  Host code must not use the array's name as an address: the device address is looked up once per device, with
+// that device current, and kept.
+constexpr size_t kStaticScratchBytes = (size_t)FLASHRNN_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+void* static_scratch_ptr() {
+    static std::mutex mu;
+    static void* ptrs[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { (void)hipGetLastError(); return nullptr; }
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptrs[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) { (void)hipGetLastError(); return nullptr; }
+        ptrs[dev] = ptr;
+    }
+    return ptrs[dev];
+}
+
 // Forward call on the workspace `workspace`; ws_limit > 0: the workspace is the library's own array of that size and
 // only the part a forward call touches has to fit.
 int fwd_impl(const flashrnn_desc_t* d, const void* Wx, const void* R, const void* b, const void* states0, void* states,
@@ -364,6 +385,7 @@ int fwd_impl(const flashrnn_desc_t* d, const void* Wx, const void* R, const void
     rc = carve(d, &w, &pf, &pb);
     if (rc != FLASHRNN_OK) return rc;
     if (!workspace || ((uintptr_t)workspace & (kAlign - 1))) return FLASHRNN_ERR_WORKSPACE;
+    if (ws_limit && w.fwd_total > ws_limit) return FLASHRNN_ERR_SCRATCH;
     hipStream_t stream = (hipStream_t)hip_stream;
     char* ws = (char*)workspace;
     const int G = num_gates(d->cell);
@@ -431,6 +453,15 @@ int flashrnn_fwd(const flashrnn_desc_t* d, const void* Wx, const void* R, const 
     return fwd_impl(d, Wx, R, b, states0, states, gate_cache, workspace, 0, hip_stream);
 }
 
+int flashrnn_fwd_static_scratch(const flashrnn_desc_t* d, const void* Wx, const void* R, const void* b, const void* states0,
+                                void* states, void* gate_cache, void* hip_stream) {
+    const int rc = validate(d);   // argument errors are reported without touching a device
+    if (rc != FLASHRNN_OK) return rc;
+    void* ws = static_scratch_ptr();
+    if (!ws) return FLASHRNN_ERR_LAUNCH;
+    return fwd_impl(d, Wx, R, b, states0, states, gate_cache, ws, kStaticScratchBytes, hip_stream);
+}
+
 int flashrnn_bwd(const flashrnn_desc_t* d, const void* R, const void* b, const void* states, const void* gate_cache,
                  const void* dH, const void* dstates_last, void* dWx, void* dR, void* db, void* dstates0, void* workspace,
                  void* hip_stream) {
@@ -482,6 +513,10 @@ int flashrnn_bwd(const flashrnn_desc_t* d, const void* R, const void* b, const v
 
 int flashrnn_check(const flashrnn_desc_t* d, const void* workspace, void* hip_stream) {
     if (!workspace) return FLASHRNN_OK;
+    if (workspace == FLASHRNN_STATIC_SCRATCH) {
+        workspace = static_scratch_ptr();
+        if (!workspace) return FLASHRNN_ERR_LAUNCH;
+    }
     int flags[2] = {0, 0};
     hipStream_t stream = (hipStream_t)hip_stream;
     bool fwd_waits = true, bwd_waits = true;
@@ -527,6 +562,7 @@ const char* flashrnn_status_string(int status) {
         case FLASHRNN_ERR_WORKSPACE: return "workspace missing or not 256-byte aligned";
         case FLASHRNN_ERR_LAUNCH: return "a HIP call failed";
         case FLASHRNN_ERR_TIMEOUT: return "a cross-CU wait ran into its spin limit";
+        case FLASHRNN_ERR_SCRATCH: return "the problem needs more scratch memory than the library's static array holds";
         default: return "unknown status";
     }
 }

@@ -33,7 +33,7 @@ def test_cell_tables_match_paper_appendix_a():
 
 def test_status_strings():
     seen = set()
-    for s in range(0, -7, -1):
+    for s in range(0, -8, -1):
         txt = api.status_string(s)
         assert txt and txt not in seen
         seen.add(txt)
@@ -62,6 +62,12 @@ def test_time_step_slabs_beyond_32_bit_offsets_are_refused():
     assert api.lib().flashrnn_fwd(ctypes.byref(d), *([None] * 8)) == api.FLASHRNN_ERR_UNSUPPORTED
     d = api.make_desc(2, 4, 64, 64, 1024, api.FLASHRNN_BF16)
     assert api.lib().flashrnn_fwd(ctypes.byref(d), *([None] * 8)) == api.FLASHRNN_ERR_NULL
+
+
+def test_static_scratch_entry_checks_arguments_first():
+    d = api.make_desc(0, 4, 2, 1, 24, api.FLASHRNN_BF16)
+    assert api.lib().flashrnn_fwd_static_scratch(ctypes.byref(d), *([None] * 7)) == api.FLASHRNN_ERR_UNSUPPORTED
+    assert api.lib().flashrnn_fwd_static_scratch(None, *([None] * 7)) == api.FLASHRNN_ERR_NULL
 
 
 def test_unsupported_head_size_and_null_pointers():
