@@ -40,7 +40,8 @@ typedef enum {
     FLASHRNN_OK = 0,
     FLASHRNN_ERR_NULL = -1,        /* a required pointer is NULL                                   */
     FLASHRNN_ERR_SHAPE = -2,       /* T < 0, or B, NH, D <= 0, or unknown cell / dtype             */
-    FLASHRNN_ERR_UNSUPPORTED = -3, /* D not a multiple of 16 or above 1024 (bf16) / 256 (f32), or a misaligned pointer */
+    FLASHRNN_ERR_UNSUPPORTED = -3, /* D not a multiple of 16 or above 2688 (bf16) / 256 (f32), a time step of more than
+                                      2 GiB in one tensor, or a misaligned pointer */
     FLASHRNN_ERR_WORKSPACE = -4,   /* workspace missing or misaligned (needs 256-byte alignment)   */
     FLASHRNN_ERR_LAUNCH = -5,      /* a HIP call failed                                            */
     FLASHRNN_ERR_TIMEOUT = -6,     /* a cross-CU wait gave up (reported by flashrnn_check)         */

@@ -66,7 +66,7 @@ KernelTable table_for(int cell, int dt) {
 
 struct Plan {
     const KernelEntry* e = nullptr;
-    int NWU = 0, P = 0, NG = 0, GPAR = 0, grid = 0, block = 0, DK = 0;
+    int NWU = 0, P = 0, NG = 0, GPAR = 0, grid = 0, block = 0, DK = 0, spread = 0;
     size_t smem = 0, exch_bytes = 0, rpack_bytes = 0;
 };
 
@@ -114,7 +114,7 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
     const int units16 = d->D / 16;
     const KernelTable tab = table_for(d->cell, d->io_dtype);
     const int cus = device_cus();
-    const int force_multi = env_int("FLASHRNN_MULTI", -1);   // 1: always split groups, 0: never
+    const int force_multi = env_int("FLASHRNN_MULTI", -1);   // 1: always split groups, 0: never, 2: always spread over all XCDs
     const int force_bt = env_int("FLASHRNN_BT", 0);
     const int force_nwu = env_int("FLASHRNN_NWU", 0);
     const int force_ks = env_int("FLASHRNN_KS", 0);
@@ -124,7 +124,7 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
     const int force_eb = env_int("FLASHRNN_EB", 0);          // blocks of 16 units per wave (one workgroup per group)      // groups in flight when groups are split (testing the group loop)
     Plan pl;
 
-    if (force_multi != 1) {
+    if (force_multi < 1) {
         // Every (batch tile, kernel) pair that can run the shape gets a cost: rounds of workgroups over the CUs
         // times a relative time per step.  The relative times are measured ones (D = 192 and 128, MI355X): the
         // staged tile kernels run a step of 4 rows in 1.0, of 8 rows in about 1.5; the generic kernels, whose
@@ -175,7 +175,7 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
             pl.exch_bytes = 0;
         }
     }
-    if (!pl.e && force_multi != 0) {
+    if (!pl.e && force_multi != 0 && force_multi != 2) {
         // Batch tiles of 16, 8 or 4 rows here too.  A smaller tile means more groups (each with its own workgroups, on its
         // own XCD when there are few) and proportionally less to exchange and less point-wise work per workgroup; the
         // smallest tile whose groups all run at once is taken, else the largest (fewest rounds over the groups).
@@ -243,6 +243,44 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
                     pl.exch_bytes = (size_t)2 * gpar * BT * pl.DK * (bf ? 4 : 8);
                 }
             }
+        }
+    }
+    if (!pl.e && force_multi != 0 && bf) {
+        // Heads beyond what the CUs of one XCD can hold (D > 1024): the group is spread over the CUs of all XCDs, one
+        // block of 16 units and 4 contraction slices per workgroup (one wave per SIMD, up to 336 registers of R each),
+        // and h / dg cross the XCDs through memory.  The largest batch tile whose kernel neither spills registers nor
+        // overflows the LDS; as many groups at once as fit the chip (with a margin), the rest in turn.
+        const int budget = cus - 16;
+        const int bts[3] = {16, 8, 4};
+        for (int bi = 0; bi < 3 && !pl.e; ++bi) {
+            const int BT = bts[bi];
+            if (force_bt && BT != force_bt) continue;
+            const KernelEntry* best = nullptr;
+            for (int i = 0; i < tab.count; ++i) {
+                const KernelEntry& e = tab.entries[i];
+                const int dk = e.KT * e.KS * kstep;
+                if (e.bwd != bwd || !e.multi || e.BT != BT || e.KS != 4 || e.maxw != 4 || dk < kdim) continue;
+                if (!best || dk < best->KT * best->KS * kstep) best = &e;
+            }
+            if (!best || units16 > budget) continue;
+            const int dk = best->KT * best->KS * kstep, nt = bwd ? 1 : G;
+            const size_t smem = (size_t)BT * (dk + 8) * 2 + (size_t)2 * 3 * nt * 4 * 64 * 4;
+            if (smem > kLdsBytes || kernel_spills(best->fn)) continue;
+            const int NG = d->NH * ((d->B + BT - 1) / BT);
+            int gpar = budget / units16;
+            if (gpar > NG) gpar = NG;
+            if (force_gpar > 0 && force_gpar < gpar) gpar = force_gpar;
+            pl.e = best;
+            pl.NWU = 1;
+            pl.P = units16;
+            pl.NG = NG;
+            pl.GPAR = gpar;
+            pl.grid = gpar * pl.P;
+            pl.block = 64 * 4;
+            pl.DK = dk;
+            pl.smem = smem;
+            pl.exch_bytes = (size_t)2 * gpar * BT * dk * 4;
+            pl.spread = 1;
         }
     }
     if (!pl.e) return FLASHRNN_ERR_UNSUPPORTED;
@@ -338,6 +376,7 @@ int launch_persistent(const Plan& pl, KernelParams& kp, hipStream_t stream) {
     kp.NWU = pl.NWU;
     kp.NG = pl.NG;
     kp.GPAR = pl.GPAR;
+    kp.spread = pl.spread;
     kp.spin_limit = env_int("FLASHRNN_SPIN_LIMIT", 1 << 21);
     void* args[] = {&kp};
     if (e0 && e1) {

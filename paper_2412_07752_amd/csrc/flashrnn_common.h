@@ -135,6 +135,7 @@ struct KernelParams {
     int NG;                // groups in total: NH * batch tiles; group id = tile * NH + head
     int GPAR;              // groups processed concurrently; a workgroup set loops over NG / GPAR of them
     int spin_limit;
+    int spread;            // several workgroups per group: 0 = a group's members share an XCD, 1 = they are spread over all XCDs
     float clip;            // bwd: bound of the recurrent gradient term per value (+inf = not clipped, 0 = cut)
 };
 

@@ -3,7 +3,9 @@
 //
 // Shapes (KT = k-steps per wave, 32 contraction elements per bf16 step, 4 per f32 step):
 //   one workgroup per group:   units D <= 32 / 64 / 128 / 192 (bf16) or 16 / 32 / 64 / 128 (f32)
-//   several workgroups:        D up to 1024 (bf16) / 256 (f32), optionally 4 contraction slices
+//   several workgroups:        D up to 1024 (bf16) / 256 (f32) inside one XCD, optionally 4 contraction slices;
+//                              D up to 2688 (bf16) spread over all XCDs: one block of 16 units and 4 contraction slices
+//                              per workgroup, one wave per SIMD with up to 336 registers of R
 #pragma once
 #include "flashrnn_host.h"
 #include "flashrnn_kernels.h"
@@ -24,6 +26,9 @@ namespace flashrnn {
 #define FRNN_BTL(KT, EBK, BT, MAXW) \
     {FRNN_CELL, FRNN_BF16, 1, (KT) * FRNN_G, 1, BT, 0, MAXW, EBK, 1, (const void*)&bwd_tile_kernel<FRNN_CELL, (KT) * FRNN_G / (EBK), EBK, BT, MAXW>},
 #define FRNN_TILE(KT, EBK, BT, MAXW) FRNN_FT(KT, BT, MAXW) FRNN_B(KT, 1, BT, 0, MAXW, 1) FRNN_BTL(KT, EBK, BT, MAXW)
+// the largest heads: one block of 16 units per workgroup, 4 contraction slices, one wave per SIMD
+#define FRNN_FL(KT, BT) FRNN_F(KT, 4, BT, 1, 4, 1)
+#define FRNN_BL(KT, BT) FRNN_B(KT, 4, BT, 1, 4, 1)
 // EB blocks of 16 units per wave (fewer, fatter waves: the operand is read from LDS once per wave)
 #define FRNN_FBE(KT, BT, MAXW, EB) FRNN_F(KT, 1, BT, 0, MAXW, EB) FRNN_B(KT, 1, BT, 0, MAXW, EB)
 
@@ -42,6 +47,13 @@ static const KernelEntry kEntries[] = {
     // a head split over workgroups, for batch tiles of 16, 8 and 4 rows (small tiles: more groups, less to exchange)
     FRNN_MULTI_SHAPES(16) FRNN_MULTI_SHAPES(8) FRNN_MULTI_SHAPES(4)
 #undef FRNN_MULTI_SHAPES
+    // heads of 1040 .. 2688 units: contraction lengths 1280, 1536, 2048, 2560, 2688.  Forward with all 16 rows of a
+    // batch tile where the registers allow, backward (whose point-wise phase holds more values per row) with 8 or 4;
+    // the planner takes the largest tile whose kernel neither spills nor overflows the LDS.
+    FRNN_FL(10, 16) FRNN_FL(12, 16) FRNN_FL(16, 16) FRNN_FL(20, 16) FRNN_FL(21, 16)
+    FRNN_FL(10, 4) FRNN_FL(12, 4) FRNN_FL(16, 4) FRNN_FL(20, 4) FRNN_FL(21, 4)
+    FRNN_BL(10, 8) FRNN_BL(12, 8) FRNN_BL(16, 8) FRNN_BL(20, 8) FRNN_BL(21, 8)
+    FRNN_BL(10, 4) FRNN_BL(12, 4) FRNN_BL(16, 4) FRNN_BL(20, 4) FRNN_BL(21, 4)
 #else
     FRNN_FB(4, 1, 16, 0, 4) FRNN_FB(8, 1, 16, 0, 4) FRNN_FB(16, 1, 16, 0, 4) FRNN_FB(32, 1, 16, 0, 8)
     FRNN_FB(16, 1, 16, 1, 4) FRNN_FB(32, 1, 16, 1, 4) FRNN_FB(48, 1, 16, 1, 4) FRNN_FB(64, 1, 16, 1, 4)
@@ -53,6 +65,8 @@ static const KernelEntry kEntries[] = {
 #undef FRNN_B
 #undef FRNN_FB
 #undef FRNN_FBE
+#undef FRNN_FL
+#undef FRNN_BL
 #undef FRNN_FT
 #undef FRNN_BTL
 #undef FRNN_TILE

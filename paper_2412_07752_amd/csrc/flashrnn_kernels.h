@@ -188,12 +188,17 @@ template <int BT> struct LaneMap {
 // group / member of a workgroup.  With several workgroups per group the members of a group get
 // block indices that are equal modulo 8: the hardware hands consecutive workgroups to the 8 XCDs in
 // turn, so a group's members share one XCD and its L2.
+// A head too large for the registers of one XCD's CUs is spread over all of them (p.spread): consecutive block
+// indices, hence all eight XCDs in turn, serve one group; the exchange then goes through memory at agent scope.
 struct BlockMap {
     int member, gpar;
     bool active;
     __device__ __forceinline__ BlockMap(const KernelParams& p, bool multi) {
         const int L = blockIdx.x;
-        if (multi) {
+        if (multi && p.spread) {
+            member = L % p.P;
+            gpar = L / p.P;
+        } else if (multi) {
             const int xcd = L & 7, slot = L >> 3;
             member = slot % p.P;
             gpar = (slot / p.P) * 8 + xcd;

@@ -92,3 +92,11 @@ def test_sizes_and_plans_of_the_benchmark_configurations():
     # a head that is too large for the compiled shapes is refused, not mis-run
     d = api.make_desc(0, 4, 2, 1, 4096, api.FLASHRNN_BF16)
     assert api.flashrnn_workspace_bytes(d) == 0
+    # ... up to the largest fused head the paper reports (App. H.1) every multiple of 16 has a plan: beyond 1024 units
+    # one workgroup per block of 16 units, spread over the whole chip
+    for D in (1040, 1536, 2048, 2688):
+        d = api.make_desc(0, 4, 16, 1, D, api.FLASHRNN_BF16)
+        assert api.flashrnn_workspace_bytes(d) > 0
+        for bwd in (False, True):
+            assert api.flashrnn_plan(d, bwd)[0] % (D // 16) == 0 and api.flashrnn_plan_kernel(d, bwd)[2] == D // 16
+    assert api.flashrnn_workspace_bytes(api.make_desc(0, 4, 2, 1, 2704, api.FLASHRNN_BF16)) == 0

@@ -148,6 +148,26 @@ def test_largest_head_takes_a_whole_xcd():
     assert api.flashrnn_plan(d)[0] == 32 and api.flashrnn_plan_kernel(d)[2] == 32
 
 
+@pytest.mark.parametrize("cell,D,B,NH", [(CELL_LSTM, 1040, 5, 1), (CELL_LSTM, 1280, 19, 1), (CELL_LSTM, 1536, 6, 2), (CELL_LSTM, 2048, 9, 1),
+                                         (CELL_LSTM, 2688, 5, 1), (CELL_SLSTM, 1536, 7, 1), (CELL_SLSTM, 2048, 16, 1), (CELL_GRU, 1280, 12, 1),
+                                         (CELL_GRU, 2688, 3, 1), (CELL_ELMAN, 2048, 4, 1), (CELL_GRU4, 1536, 4, 1)])
+def test_heads_beyond_one_xcd_are_spread_over_the_chip(cell, D, B, NH):
+    """Heads of more than 1024 units (App. H.1 quotes 2688 as the largest fused head on the paper's GPU): R does not fit the
+    registers of one XCD's CUs, so a group's workgroups sit on all eight XCDs and exchange h / dg through memory."""
+    w = Workload(f"spread_{cell}_D{D}", cell, 5, B, NH, D, "bf16", True, bias="uniform0.1", init="uniform0.1", seed=D + B)
+    _check(w, with_dlast=True)
+    d = api.make_desc(cell, 5, B, NH, D, api.FLASHRNN_BF16)
+    for bwd in (False, True):
+        assert api.flashrnn_plan_kernel(d, bwd)[2] == D // 16
+
+
+@pytest.mark.parametrize("cell", CELLS)
+def test_spread_groups_loop_when_they_do_not_fit(cell):
+    """The spread placement forced onto a small head, two groups in flight out of nine: workgroups loop over groups."""
+    w = Workload(f"spreadloop_{cell}", cell, 6, 33, 1, 64, "bf16", True, bias="uniform0.1", init="uniform0.1", seed=6)
+    _check(w, {"FLASHRNN_MULTI": "2", "FLASHRNN_GPAR": "2"}, with_dlast=True)
+
+
 @pytest.mark.parametrize("cell,NH,D", [(CELL_LSTM, 32, 128), (CELL_GRU, 24, 144), (CELL_SLSTM, 12, 144)])
 def test_weight_gradient_gemm_with_large_tiles(cell, NH, D):
     """Many heads: the dR GEMM takes its 128 x 256 tile (ragged in both directions at D = 144; GRU: the candidate column of B comes
