@@ -28,8 +28,9 @@ import sys
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 sys.path.insert(0, ROOT)
 
-KINDS = (("fwd", ("fwd_tile_kernel", "fwd_kernel")), ("bwd", ("bwd_tile_kernel", "bwd_kernel")), ("dr_gemm", ("dr_gemm",)),
-         ("sum_slices", ("sum_slices",)), ("pack_r", ("pack_r",)))
+# (the packing kernels are called pack_r_fwd_kernel / pack_r_bwd_kernel: they are looked for first)
+KINDS = (("pack_r", ("pack_r",)), ("sum_slices", ("sum_slices",)), ("dr_gemm", ("dr_gemm",)),
+         ("fwd", ("fwd_tile_kernel", "fwd_kernel")), ("bwd", ("bwd_tile_kernel", "bwd_kernel")))
 
 
 def kind_of(kernel_name):
