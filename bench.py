@@ -9,6 +9,8 @@ states).  Inputs are resident in HBM before the timed region.  Prints ONE JSON l
     python bench.py --copy-calibration     # a plain copy of known size, for scaling rocprofv3's HBM counters
     python bench.py --shape slstm,1024,16,4,192   # any (cell, T, B, NH, D) of the paper's sweeps; add ",fwd" for forward only
     python bench.py --sweep [--sweep-out FILE]    # the paper's runtime sweeps (Sec. 6.1, App. H.3/H.5) in one run, as a table
+    python bench.py --workload 4 --trace-phases   # per-phase clocks of a time step (split-group kernels; needs the trace build:
+                                                  # python -m paper_2412_07752_amd.build --trace), printed instead of the bench line
 
 The `roofline` object (dominant kernel = the longer of the two persistent time-loop kernels):
   bound      the roofline that binds by arithmetic intensity: flops / algorithmic bytes against the ridge
@@ -180,6 +182,8 @@ def main():
                          "drawn on the GPU; no oracle timing")
     ap.add_argument("--sweep", action="store_true", help="run the paper's head-size / batch / sequence-length sweeps and print a table")
     ap.add_argument("--sweep-out", type=str, default=None, help="also write the sweep table to this file")
+    ap.add_argument("--trace-phases", action="store_true",
+                    help="load the trace build of the library and print the mean clocks per time step and phase of the persistent kernels")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain elementwise copy of 256 MiB (reads 256 MiB, writes 256 MiB) five times and exit")
     args = ap.parse_args()
@@ -187,6 +191,8 @@ def main():
         print("bench.py: this build runs on ONE GPU only (the time loop never crosses GPUs); use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
+    if args.trace_phases:
+        os.environ["FLASHRNN_LIB"] = "trace"
     import numpy as np
     import torch
     from paper_2412_07752_amd import api, synth
@@ -231,6 +237,22 @@ def main():
     desc = runner.desc
     ms_per_step, fwd_ms, bwd_ms, launches = runner.run(args.steps, args.warmup)
     value = B * T / (ms_per_step * 1e-3)
+    if args.trace_phases:
+        names = {False: ["prefetch_issue", "barrier_rows_read", "wait_exchange_and_lds_fill", "barrier_rows_ready", "lds_reads_mfma_slice_sums",
+                         "pointwise_publish", "stores_and_input_wait", "poll_first_round_trip"],
+                 True: ["loads_pointwise_publish_dwx", "barrier_rows_read", "wait_exchange_and_lds_fill", "barrier_rows_ready",
+                        "lds_reads_mfma_slice_sums", "input_wait", "-", "poll_first_round_trip"]}
+        res = {"workload": w.name, "plan_signature": plan_signature(api, desc, w.backward), "unit": "shader clocks per time step, mean over waves",
+               "fwd_kernel_ms": round(fwd_ms, 4), "bwd_kernel_ms": round(bwd_ms, 4)}
+        for bwd in ([False, True] if w.backward else [False]):
+            clocks, waves = api.flashrnn_trace_phases(desc, runner.ws, bwd)
+            groups_per_wg = max(1, -(-(NH * -(-B // api.flashrnn_plan_kernel(desc, bwd)[1])) // max(1, api.flashrnn_plan(desc, bwd)[0] // api.flashrnn_plan_kernel(desc, bwd)[2])))
+            per = {n: round(c / (T * groups_per_wg), 1) for n, c in zip(names[bwd], clocks) if n != "-"}
+            per["sum"] = round(sum(per.values()), 1)
+            per["waves_recorded"] = waves
+            res["bwd" if bwd else "fwd"] = per
+        print(json.dumps(res))
+        return
 
     # ---- rooflines of the two persistent time-loop kernels
     H = NH * D

@@ -177,6 +177,18 @@ int flashrnn_plan_kernel(const flashrnn_desc_t* desc, int backward, int* staged,
 int flashrnn_profile_enable(int on);
 int flashrnn_profile_kernel_ms(int backward, float* mean_ms, int* launches);
 
+/*
+ * Measurement aid of a library built with -DFLASHRNN_TRACE (python -m paper_2412_07752_amd.build --trace builds it as
+ * libflashrnn_trace.so); the ordinary library returns FLASHRNN_ERR_UNSUPPORTED.  In a trace build the persistent kernels
+ * of plans that split a head over several workgroups stamp the shader clock between the phases of every time step
+ * (Alg. 1: wait for the other workgroups' part of the state, matrix product, point-wise function, stores).  After a
+ * forward (backward = 0) or backward (backward = 1) call on `workspace` this returns, per phase, the clocks a wave spent
+ * in it over the whole call, averaged over the *waves recorded.  clocks holds 8 values; the phases are listed where the
+ * kernels define them (csrc/flashrnn_kernels.h).  Synchronizes the stream.
+ */
+int flashrnn_trace_phases(const flashrnn_desc_t* desc, const void* workspace, int backward, double* clocks, int* waves,
+                          void* hip_stream);
+
 const char* flashrnn_status_string(int status);
 
 #ifdef __cplusplus

@@ -17,7 +17,9 @@ FLASHRNN_ERR_WORKSPACE, FLASHRNN_ERR_LAUNCH, FLASHRNN_ERR_TIMEOUT, FLASHRNN_ERR_
 FLASHRNN_STATIC_SCRATCH_BYTES = 16 << 20
 STATIC_SCRATCH = "static"   # stands for FLASHRNN_STATIC_SCRATCH in flashrnn_check
 
-_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libflashrnn.so")
+# FLASHRNN_LIB=trace selects the library built with per-phase clock stamps (python -m paper_2412_07752_amd.build --trace)
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)),
+                         "libflashrnn_trace.so" if os.environ.get("FLASHRNN_LIB") == "trace" else "libflashrnn.so")
 _lib = None
 
 
@@ -70,6 +72,8 @@ def lib():
         L.flashrnn_profile_enable.restype = ctypes.c_int
         L.flashrnn_profile_kernel_ms.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int)]
         L.flashrnn_profile_kernel_ms.restype = ctypes.c_int
+        L.flashrnn_trace_phases.argtypes = [dp, vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int), vp]
+        L.flashrnn_trace_phases.restype = ctypes.c_int
         L.flashrnn_status_string.argtypes = [ctypes.c_int]
         L.flashrnn_status_string.restype = ctypes.c_char_p
         _lib = L
@@ -78,7 +82,7 @@ def lib():
 
 EXPORTS = ["flashrnn_num_states", "flashrnn_num_gates", "flashrnn_gate_cache_bytes", "flashrnn_workspace_bytes", "flashrnn_fwd",
            "flashrnn_fwd_static_scratch", "flashrnn_bwd", "flashrnn_check", "flashrnn_plan", "flashrnn_plan_kernel", "flashrnn_profile_enable", "flashrnn_profile_kernel_ms",
-           "flashrnn_status_string"]
+           "flashrnn_trace_phases", "flashrnn_status_string"]
 
 
 def status_string(status):
@@ -137,6 +141,16 @@ def flashrnn_profile_kernel_ms(backward):
     if rc != FLASHRNN_OK:
         raise FlashRNNError(rc, "flashrnn_profile_kernel_ms")
     return ms.value, n.value
+
+
+def flashrnn_trace_phases(desc, workspace, backward, stream=None):
+    """(clocks per phase [8], waves recorded) of the last forward / backward call on `workspace`; trace builds only."""
+    arr = (ctypes.c_double * 8)()
+    n = ctypes.c_int()
+    rc = lib().flashrnn_trace_phases(ctypes.byref(desc), _ptr(workspace), int(bool(backward)), arr, ctypes.byref(n), _stream(stream))
+    if rc != FLASHRNN_OK:
+        raise FlashRNNError(rc, "flashrnn_trace_phases")
+    return list(arr), n.value
 
 
 def _ptr(t):

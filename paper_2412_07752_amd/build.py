@@ -27,16 +27,20 @@ def _newest_header():
     return max(os.path.getmtime(h) for h in hs)
 
 
-def _compile(src, obj):
-    r = subprocess.run([HIPCC] + FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+def _compile(src, obj, extra=()):
+    r = subprocess.run([HIPCC] + FLAGS + list(extra) + ["-c", os.path.join(CSRC, src), "-o", obj], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     log = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{log}")
     return log
 
 
-def build(force=False, jobs=None):
-    bdir = os.path.join(CSRC, "_build")
+def build(force=False, jobs=None, trace=False):
+    """trace=True: the same sources with -DFLASHRNN_TRACE (per-phase clock stamps in the split-group kernels), as
+    libflashrnn_trace.so; a measurement build, never what the tests or the benchmark's numbers run on."""
+    bdir = os.path.join(CSRC, "_build_trace" if trace else "_build")
+    flags_extra = (["-DFLASHRNN_TRACE"] + os.environ.get("FLASHRNN_TRACE_FLAGS", "").split()) if trace else []
+    out = OUT.replace("libflashrnn.so", "libflashrnn_trace.so") if trace else OUT
     os.makedirs(bdir, exist_ok=True)
     hdr = _newest_header()
     todo, objs = [], []
@@ -47,13 +51,13 @@ def build(force=False, jobs=None):
             todo.append((src, obj))
     jobs = jobs or min(8, os.cpu_count() or 1)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
-        for log in ex.map(lambda so: _compile(*so), todo):
+        for log in ex.map(lambda so: _compile(*so, extra=flags_extra), todo):
             if log.strip():
                 print(log)
-    if todo or not os.path.exists(OUT):
-        subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", OUT])
-    return OUT
+    if todo or not os.path.exists(out):
+        subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", out])
+    return out
 
 
 if __name__ == "__main__":
-    print(build(force="--force" in sys.argv))
+    print(build(force="--force" in sys.argv, trace="--trace" in sys.argv))

@@ -87,6 +87,8 @@ int validate(const flashrnn_desc_t* d) {
 }
 
 constexpr size_t kLdsBytes = 160 * 1024;   // LDS of one CU
+constexpr int kTraceGrid = 512;            // workgroups whose per-phase clock sums a trace build keeps
+constexpr size_t kTraceBytes = (size_t)kTraceGrid * kTraceWaves * kTracePhases * 8;
 
 // true if the kernel keeps part of its registers in scratch memory (known once a device is there)
 bool kernel_spills(const void* fn) {
@@ -188,10 +190,13 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
                 int cap = cus / kXcds - 2;                       // workgroups of one launch per XCD, with a margin
                 const int NG = d->NH * ((d->B + BT - 1) / BT);
                 const KernelEntry* best = nullptr;
+                for (int spills_ok = 0; spills_ok < 2 && !best; ++spills_ok)   // a kernel that keeps registers in scratch memory only as a last resort
                 for (int i = 0; i < tab.count; ++i) {
                     const KernelEntry& e = tab.entries[i];
                     const int dk = e.KT * e.KS * kstep;
                     if (e.bwd != bwd || !e.multi || e.BT != BT || dk < kdim) continue;
+                    if (e.maxw == 4 && e.KS == 4 && e.KT * (bwd ? 1 : G) >= 40) continue;   // the shapes of the spread placement
+                    if (!spills_ok && kernel_spills(e.fn)) continue;
                     // least padding of the contraction axis first, then the wanted number of slices, then the most waves
                     const int bdk = best ? best->KT * best->KS * kstep : 0;
                     const bool want = e.KS == want_ks, bwant = best && best->KS == want_ks;
@@ -252,6 +257,7 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
         // overflows the LDS; as many groups at once as fit the chip (with a margin), the rest in turn.
         const int budget = cus - 16;
         const int bts[3] = {16, 8, 4};
+        for (int spills_ok = 0; spills_ok < 2 && !pl.e; ++spills_ok)   // (a kernel with a few registers in scratch memory only if no tile is free of them)
         for (int bi = 0; bi < 3 && !pl.e; ++bi) {
             const int BT = bts[bi];
             if (force_bt && BT != force_bt) continue;
@@ -265,7 +271,7 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
             if (!best || units16 > budget) continue;
             const int dk = best->KT * best->KS * kstep, nt = bwd ? 1 : G;
             const size_t smem = (size_t)BT * (dk + 8) * 2 + (size_t)2 * 3 * nt * 4 * 64 * 4;
-            if (smem > kLdsBytes || kernel_spills(best->fn)) continue;
+            if (smem > kLdsBytes || (!spills_ok && kernel_spills(best->fn))) continue;
             const int NG = d->NH * ((d->B + BT - 1) / BT);
             int gpar = budget / units16;
             if (gpar > NG) gpar = NG;
@@ -290,7 +296,7 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
 }
 
 struct Workspace {
-    size_t err_off, exch_off, rpack_off, dgn_off, dbpart_off, drpart_off, total;
+    size_t err_off, exch_off, rpack_off, dgn_off, dbpart_off, drpart_off, trace_off, total;
     size_t fwd_total;   // bytes a forward call touches: error words, exchange buffers, the forward copy of R
 };
 
@@ -310,6 +316,10 @@ int carve_uncached(const flashrnn_desc_t* d, Workspace* w, Plan* pf, Plan* pb) {
     w->drpart_off = off;
     const int sk = dr_split_k(d->io_dtype == FLASHRNN_BF16, d->T, d->B, d->NH, d->D, G);
     off += align_up(sk > 1 ? (size_t)sk * d->NH * d->D * G * d->D * 4 : 0);
+    w->trace_off = off;
+#ifdef FLASHRNN_TRACE
+    off += 2 * kTraceBytes;   // forward, backward
+#endif
     w->total = off;
     return FLASHRNN_OK;
 }
@@ -440,6 +450,12 @@ int fwd_impl(const flashrnn_desc_t* d, const void* Wx, const void* R, const void
     kp.exch = (uint32_t*)(ws + w.exch_off);
     kp.err = (int*)(ws + w.err_off);
     kp.T = d->T; kp.B = d->B; kp.NH = d->NH; kp.D = d->D;
+#ifdef FLASHRNN_TRACE
+    if (!ws_limit && pf.grid <= kTraceGrid) {
+        kp.trace = (unsigned long long*)(ws + w.trace_off);
+        if (launch_fill_zero(kp.trace, kTraceBytes, stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
+    }
+#endif
     return launch_persistent(pf, kp, stream);
 }
 
@@ -535,6 +551,12 @@ int flashrnn_bwd(const flashrnn_desc_t* d, const void* R, const void* b, const v
     kp.exch = (uint32_t*)(ws + w.exch_off);
     kp.err = (int*)(ws + w.err_off) + 1;   // the forward call's word stays as it is: flashrnn_check reports both
     kp.T = d->T; kp.B = d->B; kp.NH = d->NH; kp.D = d->D;
+#ifdef FLASHRNN_TRACE
+    if (pb.grid <= kTraceGrid) {
+        kp.trace = (unsigned long long*)(ws + w.trace_off + kTraceBytes);
+        if (launch_fill_zero(kp.trace, kTraceBytes, stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
+    }
+#endif
     rc = launch_persistent(pb, kp, stream);
     if (rc != FLASHRNN_OK) return rc;
     // db: sum of the per-row partial sums in row order; dR: GEMM over (t, b)
@@ -568,6 +590,39 @@ int flashrnn_check(const flashrnn_desc_t* d, const void* workspace, void* hip_st
     if (hipMemcpyAsync(flags, workspace, sizeof(flags), hipMemcpyDeviceToHost, stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
     if (hipStreamSynchronize(stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
     return ((fwd_waits && flags[0] != 0) || (bwd_waits && flags[1] != 0)) ? FLASHRNN_ERR_TIMEOUT : FLASHRNN_OK;
+}
+
+int flashrnn_trace_phases(const flashrnn_desc_t* d, const void* workspace, int backward, double* clocks, int* waves, void* hip_stream) {
+#ifdef FLASHRNN_TRACE
+    int rc = validate(d);
+    if (rc != FLASHRNN_OK) return rc;
+    if (!workspace || !clocks) return FLASHRNN_ERR_NULL;
+    Workspace w;
+    Plan pf, pb;
+    rc = carve(d, &w, &pf, &pb);
+    if (rc != FLASHRNN_OK) return rc;
+    static unsigned long long host[kTraceGrid * kTraceWaves * kTracePhases];
+    hipStream_t stream = (hipStream_t)hip_stream;
+    if (hipMemcpyAsync(host, (const char*)workspace + w.trace_off + (backward ? kTraceBytes : 0), kTraceBytes, hipMemcpyDeviceToHost, stream) != hipSuccess ||
+        hipStreamSynchronize(stream) != hipSuccess)
+        return FLASHRNN_ERR_LAUNCH;
+    // mean over the waves that recorded anything
+    double sum[kTracePhases] = {0};
+    int n = 0;
+    for (int i = 0; i < kTraceGrid * kTraceWaves; ++i) {
+        unsigned long long tot = 0;
+        for (int j = 0; j < kTracePhases; ++j) tot += host[(size_t)i * kTracePhases + j];
+        if (tot == 0) continue;
+        for (int j = 0; j < kTracePhases; ++j) sum[j] += (double)host[(size_t)i * kTracePhases + j];
+        ++n;
+    }
+    for (int j = 0; j < kTracePhases; ++j) clocks[j] = n ? sum[j] / n : 0.0;
+    if (waves) *waves = n;
+    return FLASHRNN_OK;
+#else
+    (void)d; (void)workspace; (void)backward; (void)clocks; (void)waves; (void)hip_stream;
+    return FLASHRNN_ERR_UNSUPPORTED;
+#endif
 }
 
 int flashrnn_profile_enable(int on) {

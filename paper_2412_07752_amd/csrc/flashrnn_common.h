@@ -114,6 +114,9 @@ constexpr float kLn2 = 0.6931471805599453f;
 // Cache policy bits of the raw buffer intrinsics on gfx942/gfx950.
 constexpr int kAuxAgent = 16;  // sc1: coherent at agent scope (misses the CU's vector L1)
 
+// per-phase clock sums of a trace build: [workgroup][kTraceWaves][kTracePhases]
+constexpr int kTracePhases = 8, kTraceWaves = 16;
+
 struct KernelParams {
     const void* Wx;        // fwd: [T,B,G,NH,D] io
     const void* R;         // [NH,D,G,D] io
@@ -136,6 +139,7 @@ struct KernelParams {
     int GPAR;              // groups processed concurrently; a workgroup set loops over NG / GPAR of them
     int spin_limit;
     int spread;            // several workgroups per group: 0 = a group's members share an XCD, 1 = they are spread over all XCDs
+    unsigned long long* trace;   // per-phase clock sums [workgroup][16 waves][8 phases] (trace builds only), or null
     float clip;            // bwd: bound of the recurrent gradient term per value (+inf = not clipped, 0 = cut)
 };
 

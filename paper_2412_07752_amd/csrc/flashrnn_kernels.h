@@ -170,6 +170,37 @@ template <int N> __device__ __forceinline__ void pin(float (&v)[N]) {
     for (int i = 0; i < N; ++i) asm volatile("" : "+v"(v[i]) : : "memory");
 }
 
+// Per-phase clock stamps of a time step (a library built with -DFLASHRNN_TRACE; no code otherwise).  Every wave adds up, per
+// phase, the shader clocks between consecutive marks; at the end of the kernel lane 0 of each wave writes its sums to
+// p.trace[workgroup][wave][phase].  Phases of the kernels whose groups span several workgroups:
+//   forward   0 issue of the input prefetch | 1 barrier (all waves have read the old rows) | 7 first round trip of the poll
+//             (everything the wave has in flight retires first) | 2 further rounds until the partners' h_{t-1} is complete,
+//             payloads into LDS | 3 barrier | 4 operand reads + MFMA chain + slice sums | 5 point-wise + publish h_t
+//             | 6 stores of states / saved values and the wait for the prefetched inputs
+//   backward  0 issue of the loads of step t-1, point-wise Jacobians of step t, publish dg_t, dWx stores | 1 barrier | 7 first
+//             round trip of the poll | 2 further rounds until the partners' dg_t is complete, payloads into LDS | 3 barrier | 4 operand reads + MFMA chain + slice sums | 5 wait for
+//             the prefetched inputs
+#ifdef FLASHRNN_TRACE
+#define FRNN_TRACE_BEGIN() unsigned long long tr_acc[kTracePhases] = {0, 0, 0, 0, 0, 0, 0, 0}; unsigned long long tr_t = __builtin_amdgcn_s_memtime(), tr_first = 0;
+#define FRNN_TRACE_MARK(i) { __builtin_amdgcn_sched_barrier(0); const unsigned long long tr_n = __builtin_amdgcn_s_memtime(); \
+                             tr_acc[i] += tr_n - tr_t; tr_t = tr_n; __builtin_amdgcn_sched_barrier(0); }
+#define FRNN_TRACE_FIRST (&tr_first)
+// the time up to `tr_first` (taken inside the phase) goes to phase a, the rest to phase b
+#define FRNN_TRACE_SPLIT(a, b) { __builtin_amdgcn_sched_barrier(0); const unsigned long long tr_n = __builtin_amdgcn_s_memtime(); \
+                                 if (tr_first > tr_t && tr_first <= tr_n) { tr_acc[a] += tr_first - tr_t; tr_acc[b] += tr_n - tr_first; } else tr_acc[b] += tr_n - tr_t; \
+                                 tr_t = tr_n; tr_first = 0; __builtin_amdgcn_sched_barrier(0); }
+#define FRNN_TRACE_RESET() { __builtin_amdgcn_sched_barrier(0); tr_t = __builtin_amdgcn_s_memtime(); __builtin_amdgcn_sched_barrier(0); }
+#define FRNN_TRACE_END(p) if ((p).trace != nullptr && (threadIdx.x & 63) == 0 && (threadIdx.x >> 6) < kTraceWaves) { \
+        for (int tr_j = 0; tr_j < kTracePhases; ++tr_j) (p).trace[((size_t)blockIdx.x * kTraceWaves + (threadIdx.x >> 6)) * kTracePhases + tr_j] = tr_acc[tr_j]; }
+#else
+#define FRNN_TRACE_BEGIN()
+#define FRNN_TRACE_FIRST nullptr
+#define FRNN_TRACE_SPLIT(a, b)
+#define FRNN_TRACE_MARK(i)
+#define FRNN_TRACE_RESET()
+#define FRNN_TRACE_END(p)
+#endif
+
 // ---------------------------------------------------------------------------------------------
 // common per-lane geometry
 // ---------------------------------------------------------------------------------------------
@@ -236,32 +267,56 @@ __device__ __forceinline__ void stagger_waves(int w) {
 // their MFMA operands from LDS like the one-workgroup kernels do (every wave polling every row in L2 itself
 // measured 1.2x to 1.5x slower at D = 256 and 768).  The loads are marked volatile: every round goes to memory again.
 // Returns false on a timeout (the error word is set; the caller stops waiting from then on).
-__device__ __forceinline__ bool poll_rows_to_lds(__amdgpu_buffer_rsrc_t rs, uint32_t goff, uint32_t rows, uint32_t xrow, uint32_t cpr, char* lds,
-                                                 uint32_t lds_pitch, uint32_t stamp, int spin_limit, int* err, uint32_t tid, uint32_t NT) {
-    constexpr int NB = 8;   // chunks per thread and round (a round costs one L2 round trip: few rounds)
-    constexpr int kAuxPoll = (int)(0x80000000u | (unsigned)kAuxAgent);
-    constexpr uint32_t kDrop = 0x80000000u;
-    if (spin_limit < 0) {   // host-forced failure (tests of the error path): give up without looking
-        __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        return false;
+// Everything about a thread's chunks that does not change from step to step is formed once per kernel (Poller): the
+// global and LDS offsets of its first NB chunks and how many of them its wave really has.  A step then only supplies the
+// (uniform) offset of the buffer in use as the scalar offset of the loads.  Forming the offsets inside the time loop --
+// sixteen integer divisions and a hundred more instructions per thread and step -- cost more than the hand-over itself
+// (measured: 2000 of 7500 clocks per step at D = 256).
+struct Poller {
+    static constexpr int NBP = 2;  // chunks per thread whose offsets are kept for the whole kernel (the usual shapes need no more)
+    static constexpr int NB = 8;   // chunks per thread and round beyond those (a round costs one L2 round trip: few rounds)
+    static constexpr uint32_t kDrop = 0x80000000u;
+    uint32_t voff[NBP], loff[NBP];  // first round: byte offset inside the group's rows (kDrop = no chunk), LDS offset
+    int nb;                         // chunks of this wave in the first round
+    uint32_t total, cpr, xrow, lds_pitch, tid, NT;
+    uint32_t row, c, dq, dr;        // position of chunk tid + NBP * NT and the step to the chunk NT further on
+    __device__ __forceinline__ Poller(uint32_t tid_, uint32_t NT_, uint32_t rows, uint32_t cpr_, uint32_t xrow_, uint32_t lds_pitch_)
+        : total(rows * cpr_), cpr(cpr_), xrow(xrow_), lds_pitch(lds_pitch_), tid(tid_), NT(NT_) {
+        row = tid / cpr; c = tid % cpr; dq = NT / cpr; dr = NT % cpr;
+#pragma unroll
+        for (int j = 0; j < NBP; ++j) place(tid + (uint32_t)j * NT, voff[j], loff[j]);
+        const uint32_t wave_first = tid & ~63u;
+        nb = wave_first >= total ? 0 : (int)min((uint32_t)NBP, (total - wave_first + NT - 1) / NT);
     }
-    const uint32_t total = rows * cpr;
-    bool good = true;
-    for (uint32_t base = 0; base < total && good; base += NT * NB) {
-        uint32_t goffs[NB], loffs[NB];
-#pragma unroll
-        for (int j = 0; j < NB; ++j) {
-            const uint32_t idx = base + tid + (uint32_t)j * NT, row = idx / cpr, c = idx % cpr;
-            goffs[j] = idx < total ? goff + row * xrow + c * 16u : kDrop;
-            loffs[j] = row * lds_pitch + c * 8u;
-        }
-        i32x4 raw[NB];
+    // offsets of chunk idx (the running position is at idx) and the advance to chunk idx + NT
+    __device__ __forceinline__ void place(uint32_t idx, uint32_t& vo, uint32_t& lo) {
+        vo = idx < total ? row * xrow + c * 16u : kDrop;
+        lo = row * lds_pitch + c * 8u;
+        row += dq;
+        c += dr;
+        if (c >= cpr) { c -= cpr; ++row; }
+    }
+    // one set of up to N chunks: poll until every stamp is there, then move the payloads to LDS
+    template <int N>
+    __device__ __forceinline__ bool round(__amdgpu_buffer_rsrc_t rs, uint32_t goff, const uint32_t (&vo)[N], const uint32_t (&lo)[N], int n, char* lds,
+                                          uint32_t stamp, int spin_limit, int* err, unsigned long long* first_round) const {
+        constexpr int kAuxPoll = (int)(0x80000000u | (unsigned)kAuxAgent);
+        i32x4 raw[N];
+        bool good = true;
         for (int spins = 0;; ++spins) {
+            // (a load whose lanes are all out of range still costs its issue slot in the memory pipeline: only the n real ones)
 #pragma unroll
-            for (int j = 0; j < NB; ++j) raw[j] = __builtin_amdgcn_raw_buffer_load_b128(rs, goffs[j], 0, kAuxPoll);
+            for (int j = 0; j < N; ++j)
+                if (j < n) raw[j] = __builtin_amdgcn_raw_buffer_load_b128(rs, vo[j], goff, kAuxPoll);
             bool ok = true;
 #pragma unroll
-            for (int j = 0; j < NB; ++j) ok = ok && (goffs[j] == kDrop || ((uint32_t)raw[j][1] == stamp && (uint32_t)raw[j][3] == stamp));
+            for (int j = 0; j < N; ++j)
+                if (j < n) ok = ok && (vo[j] == kDrop || ((uint32_t)raw[j][1] == stamp && (uint32_t)raw[j][3] == stamp));
+#ifdef FLASHRNN_TRACE
+            if (first_round != nullptr && spins == 0) { asm volatile("" : : "v"(ok) : "memory"); *first_round = __builtin_amdgcn_s_memtime(); }
+#else
+            (void)first_round;
+#endif
             if (__all((int)ok)) break;
             if (spins > spin_limit) {
                 __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -271,23 +326,52 @@ __device__ __forceinline__ bool poll_rows_to_lds(__amdgpu_buffer_rsrc_t rs, uint
             if ((spins & 255) == 255 && __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) { good = false; break; }
         }
 #pragma unroll
-        for (int j = 0; j < NB; ++j)
-            if (goffs[j] != kDrop) *(i32x2*)(lds + loffs[j]) = i32x2{raw[j][0], raw[j][2]};
+        for (int j = 0; j < N; ++j)
+            if (j < n && vo[j] != kDrop) *(i32x2*)(lds + lo[j]) = i32x2{raw[j][0], raw[j][2]};
+        return good;
     }
-    return good;
-}
+    // goff: byte offset of the group's rows in the buffer in use (uniform).  Returns false on a timeout.
+    __device__ __forceinline__ bool poll(__amdgpu_buffer_rsrc_t rs, uint32_t goff, char* lds, uint32_t stamp, int spin_limit, int* err,
+                                         unsigned long long* first_round = nullptr) const {
+        if (spin_limit < 0) {   // host-forced failure (tests of the error path): give up without looking
+            __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return false;
+        }
+        bool good = round<NBP>(rs, goff, voff, loff, nb, lds, stamp, spin_limit, err, first_round);
+        if (total > NT * NBP) {   // long rows: further sets, their offsets formed on the way
+            Poller run = *this;
+            for (uint32_t base = NT * NBP; base < total && good; base += NT * NB) {
+                uint32_t vo[NB], lo[NB];
+#pragma unroll
+                for (int j = 0; j < NB; ++j) run.place(base + tid + (uint32_t)j * NT, vo[j], lo[j]);
+                good = round<NB>(rs, goff, vo, lo, NB, lds, stamp, spin_limit, err, nullptr);
+            }
+        }
+        return good;
+    }
+};
 
-// write PP = 4 consecutive operand elements of one row as stamped words
+// write PP = 4 consecutive operand elements of one row as stamped words.  far = the group's workgroups sit on several
+// XCDs: the store must go through to memory (agent scope).  Inside one XCD the L2 is the point of coherence and an
+// ordinary store reaches it (the vector L1 writes through); it is acknowledged by the L2, not by memory, which matters
+// because a wave's memory operations retire in order: the next poll's first answer waits for this store's acknowledgement
+// (measured: 0.9 us per step with the write-through store).
 template <bool BF16>
-__device__ __forceinline__ void publish4(__amdgpu_buffer_rsrc_t rs, uint32_t row_off, int k, const float (&v)[4], uint32_t stamp) {
+__device__ __forceinline__ void publish4(__amdgpu_buffer_rsrc_t rs, uint32_t row_off, int k, const float (&v)[4], uint32_t stamp, bool far) {
     if constexpr (BF16) {
         const i32x4 w = {(int)pack_bf16x2(v[0], v[1]), (int)stamp, (int)pack_bf16x2(v[2], v[3]), (int)stamp};
-        __builtin_amdgcn_raw_buffer_store_b128(w, rs, row_off + k * 4, 0, kAuxAgent);
+        if (far) __builtin_amdgcn_raw_buffer_store_b128(w, rs, row_off + k * 4, 0, kAuxAgent);
+        else __builtin_amdgcn_raw_buffer_store_b128(w, rs, row_off + k * 4, 0, 0);
     } else {
         const i32x4 w0 = {__builtin_bit_cast(int, v[0]), (int)stamp, __builtin_bit_cast(int, v[1]), (int)stamp};
         const i32x4 w1 = {__builtin_bit_cast(int, v[2]), (int)stamp, __builtin_bit_cast(int, v[3]), (int)stamp};
-        __builtin_amdgcn_raw_buffer_store_b128(w0, rs, row_off + k * 8, 0, kAuxAgent);
-        __builtin_amdgcn_raw_buffer_store_b128(w1, rs, row_off + k * 8 + 16, 0, kAuxAgent);
+        if (far) {
+            __builtin_amdgcn_raw_buffer_store_b128(w0, rs, row_off + k * 8, 0, kAuxAgent);
+            __builtin_amdgcn_raw_buffer_store_b128(w1, rs, row_off + k * 8 + 16, 0, kAuxAgent);
+        } else {
+            __builtin_amdgcn_raw_buffer_store_b128(w0, rs, row_off + k * 8, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b128(w1, rs, row_off + k * 8 + 16, 0, 0);
+        }
     }
 }
 
@@ -295,11 +379,11 @@ __device__ __forceinline__ void publish4(__amdgpu_buffer_rsrc_t rs, uint32_t row
 // units 4q..4q+3 of their batch row first (every lane holds fewer values there), the other lanes' stores are dropped.
 template <bool BF16, int BT, int PP>
 __device__ __forceinline__ void publish_tile(__amdgpu_buffer_rsrc_t rs, uint32_t group_off, uint32_t xrow, const LaneMap<BT>& lm, int k_wave,
-                                             const float (&v)[PP], uint32_t stamp) {
+                                             const float (&v)[PP], uint32_t stamp, bool far) {
     float v4[4];
     expand_tile<BT, PP>(v, v4);
     const uint32_t row_off = lm.c < BT ? group_off + (uint32_t)lm.c * xrow : 0x80000000u;
-    publish4<BF16>(rs, row_off, k_wave + 4 * lm.quad, v4, stamp);
+    publish4<BF16>(rs, row_off, k_wave + 4 * lm.quad, v4, stamp, far);
 }
 
 // LDS operand row: element type bf16 (as uint16) or float
@@ -406,6 +490,8 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
     const uint32_t xgroup = (uint32_t)bm.gpar * BT * XROW;     // this group's BT rows inside one buffer
     const uint32_t xbuf = (uint32_t)p.GPAR * BT * XROW;        // bytes per buffer
     bool failed = false;
+    const Poller poller(MULTI ? threadIdx.x : 0u, MULTI ? blockDim.x : 64u, MULTI ? BT : 0, (uint32_t)p.D * (BF16 ? 4 : 8) / 16, XROW, HP * ESZ);
+    FRNN_TRACE_BEGIN();
 
     // uniform strides in bytes
     const uint32_t HD = (uint32_t)NH * D;
@@ -479,7 +565,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
         } else {
             if (ks == 0 && T > 0) {
                 const uint32_t cnt = (uint32_t)iter * (uint32_t)T;
-                publish_tile<BF16, BT, PP>(xr, (cnt & 1u) * xbuf + xgroup, XROW, lm, e_wave, st[0][0], cnt + 1u);
+                publish_tile<BF16, BT, PP>(xr, (cnt & 1u) * xbuf + xgroup, XROW, lm, e_wave, st[0][0], cnt + 1u, p.spread != 0);
             }
         }
 
@@ -492,16 +578,20 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
             for (int g = 0; g < G; ++g) load_io_r<BF16, PP>(make_rsrc(wx_g), voff_wx + eb * 16 * ESZ, g * wx_gate, wx[eb][g]);
         }
 
+        FRNN_TRACE_RESET();
         for (int t = 1; t <= T; ++t) {
-            // ---- prefetch the inputs of step t + 1 (clamped at the end)
+            // ---- prefetch the inputs of step t + 1 (clamped at the end).  A wave's vector memory operations retire in
+            // order: with several workgroups per group the loads are issued behind the poll for h_{t-1}, not in front of it
+            // (the poll's first answer would otherwise wait for these to come back from HBM: measured 1.2 us per step)
             float wxn[EB][G][PP];
-            {
+            auto prefetch_inputs = [&]() {
                 const rsrc_t rsn = make_rsrc(wx_g + (size_t)(t < T ? t : T - 1) * wx_step);
 #pragma unroll
                 for (int eb = 0; eb < EB; ++eb)
 #pragma unroll
                 for (int g = 0; g < G; ++g) load_io_r<BF16, PP>(rsn, voff_wx + eb * 16 * ESZ, g * wx_gate, wxn[eb][g]);
-            }
+            };
+            if constexpr (!MULTI) prefetch_inputs();
             // ---- recurrent product y = R^T h_{t-1} on the matrix cores
             f32x4 accs[EB][G];
 #pragma unroll
@@ -521,11 +611,18 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
             } else {
                 // h_{t-1} of the whole group: polled once per workgroup into LDS, then read like in the one-workgroup case
                 const uint32_t cnt = (uint32_t)iter * (uint32_t)T + (uint32_t)(t - 1);
+                FRNN_TRACE_MARK(0);
                 __syncthreads();   // every wave has read the previous step's rows
-                if (!failed)
-                    failed = !poll_rows_to_lds(xr, (cnt & 1u) * xbuf + xgroup, BT, XROW, (uint32_t)D * (BF16 ? 4 : 8) / 16, hbuf, HP * ESZ, cnt + 1u,
-                                               p.spin_limit, p.err, threadIdx.x, blockDim.x);
+                FRNN_TRACE_MARK(1);
+#ifdef FLASHRNN_TRACE_DRAIN
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                FRNN_TRACE_MARK(0);
+#endif
+                if (!failed) failed = !poller.poll(xr, (cnt & 1u) * xbuf + xgroup, hbuf, cnt + 1u, p.spin_limit, p.err, FRNN_TRACE_FIRST);
+                FRNN_TRACE_SPLIT(7, 2);
                 __syncthreads();
+                FRNN_TRACE_MARK(3);
+                prefetch_inputs();
 #pragma unroll
                 for (int kc = 0; kc < KT; kc += KC) {
                     op_t hB[KC];
@@ -541,6 +638,9 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
                 }
             }
             reduce_slices<G, KS>(red, t & 1, ks, wu, p.NWU, lane, acc);
+#ifdef FLASHRNN_TRACE
+            if constexpr (MULTI) { asm volatile("" : "+v"(acc[0]), "+v"(acc[G - 1]) : : "memory"); FRNN_TRACE_MARK(4); }
+#endif
 
             if (KS == 1 || ks == 0) {
                 float cvs[EB][NC][PP];
@@ -567,10 +667,11 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
                     } else {
                         if (t < T) {
                             const uint32_t cnt = (uint32_t)iter * (uint32_t)T + (uint32_t)t;
-                            publish_tile<BF16, BT, PP>(xr, (cnt & 1u) * xbuf + xgroup, XROW, lm, e_wave, st[0][0], cnt + 1u);
+                            publish_tile<BF16, BT, PP>(xr, (cnt & 1u) * xbuf + xgroup, XROW, lm, e_wave, st[0][0], cnt + 1u, p.spread != 0);
                         }
                     }
                 }
+                if constexpr (MULTI) FRNN_TRACE_MARK(5);
                 // stores of lanes without a valid row (and of the saved values in a forward-only call) carry
                 // an out-of-range offset and are dropped by the buffer bounds check: no branch, so the
                 // wait for the prefetched inputs at the end of the step does not have to cover them
@@ -598,8 +699,12 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
 #pragma unroll
                 for (int i = 0; i < PP; ++i) wx[eb][g][i] = wxn[eb][g][i];
             if constexpr (!MULTI) __syncthreads();
+#ifdef FLASHRNN_TRACE
+            if constexpr (MULTI) { pin(wx[0]); FRNN_TRACE_MARK(6); }
+#endif
         }
     }
+    FRNN_TRACE_END(p);
 }
 
 // =============================================================================================
@@ -644,6 +749,8 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
     const uint32_t xgroup = (uint32_t)bm.gpar * BT * XROW;
     const uint32_t xbuf = (uint32_t)p.GPAR * BT * XROW;
     bool failed = false;
+    const Poller poller(MULTI ? threadIdx.x : 0u, MULTI ? blockDim.x : 64u, MULTI ? BT : 0, (uint32_t)(G * p.D) * (BF16 ? 4 : 8) / 16, XROW, HP * ESZ);
+    FRNN_TRACE_BEGIN();
 
     const uint32_t HD = (uint32_t)NH * D;
     const size_t wx_step = (size_t)B * G * HD * ESZ;
@@ -742,11 +849,13 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
         };
         if ((KS == 1 || ks == 0) && T > 0) load_step(T, cv, sc, sp, dh_ext);
 
+        FRNN_TRACE_RESET();
         for (int t = T; t >= 1; --t) {
             float cvn[EB][NC][PP], scn[EB][S][PP], spn[EB][S][PP], dhn[EB][PP];
             if (KS == 1 || ks == 0) {
                 // ---- prefetch the inputs of the next (earlier) step; they are pinned after the MFMA phase
-                load_step(t > 1 ? t - 1 : 1, cvn, scn, spn, dhn);
+                // (with several workgroups per group they are issued behind the poll for dg_t: see the forward kernel)
+                if constexpr (!MULTI) load_step(t > 1 ? t - 1 : 1, cvn, scn, spn, dhn);
                 // ---- point-wise Jacobians
                 const rsrc_t dwx_t = make_rsrc(dwx_g + (size_t)(t - 1) * wx_step);
 #pragma unroll
@@ -775,7 +884,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
                         const uint32_t cnt = (uint32_t)iter * (uint32_t)T + (uint32_t)(T - t);
 #pragma unroll
                         for (int g2 = 0; g2 < G; ++g2)
-                            publish_tile<BF16, BT, PP>(xr, (cnt & 1u) * xbuf + xgroup, XROW, lm, g2 * D + e_wave, dg[g2], cnt + 1u);
+                            publish_tile<BF16, BT, PP>(xr, (cnt & 1u) * xbuf + xgroup, XROW, lm, g2 * D + e_wave, dg[g2], cnt + 1u, p.spread != 0);
                     }
 #pragma unroll
                     for (int g2 = 0; g2 < G; ++g2) store_io_r<BF16, PP>(dwx_t, soff_wx + eb * 16 * ESZ, g2 * wx_gate, dwx[g2]);
@@ -801,11 +910,18 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
             } else {
                 // dg_t of the whole group: polled once per workgroup into LDS, then read like in the one-workgroup case
                 const uint32_t cnt = (uint32_t)iter * (uint32_t)T + (uint32_t)(T - t);
+                FRNN_TRACE_MARK(0);
                 __syncthreads();   // every wave has read the previous step's rows
-                if (!failed)
-                    failed = !poll_rows_to_lds(xr, (cnt & 1u) * xbuf + xgroup, BT, XROW, (uint32_t)(G * D) * (BF16 ? 4 : 8) / 16, gbuf, HP * ESZ, cnt + 1u,
-                                               p.spin_limit, p.err, threadIdx.x, blockDim.x);
+                FRNN_TRACE_MARK(1);
+#ifdef FLASHRNN_TRACE_DRAIN
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                FRNN_TRACE_MARK(0);
+#endif
+                if (!failed) failed = !poller.poll(xr, (cnt & 1u) * xbuf + xgroup, gbuf, cnt + 1u, p.spin_limit, p.err, FRNN_TRACE_FIRST);
+                FRNN_TRACE_SPLIT(7, 2);
                 __syncthreads();
+                FRNN_TRACE_MARK(3);
+                if (KS == 1 || ks == 0) load_step(t > 1 ? t - 1 : 1, cvn, scn, spn, dhn);
 #pragma unroll
                 for (int kc = 0; kc < KT; kc += KC) {
                     op_t gB[KC];
@@ -825,6 +941,9 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
                 else accs[eb][0] = a4[eb][0] + a4[eb][1];
             }
             reduce_slices<1, KS>(red, t & 1, ks, wu, p.NWU, lane, accs[0]);
+#ifdef FLASHRNN_TRACE
+            if constexpr (MULTI) { asm volatile("" : "+v"(accs[0][0]) : : "memory"); FRNN_TRACE_MARK(4); }
+#endif
             if (KS == 1 || ks == 0) {
 #pragma unroll
                 for (int eb = 0; eb < EB; ++eb) {
@@ -846,6 +965,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
                     dh_ext[eb][i] = dhn[eb][i];
                 }
             }
+            if constexpr (MULTI) FRNN_TRACE_MARK(5);
         }
         // ---- gradients w.r.t. the initial states, per-row partial sums of db
         if (lane_ok) {
@@ -859,6 +979,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
             }
         }
     }
+    FRNN_TRACE_END(p);
 }
 
 }  // namespace flashrnn
