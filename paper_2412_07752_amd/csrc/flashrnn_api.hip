@@ -81,7 +81,7 @@ int validate(const flashrnn_desc_t* d) {
     // and the saved-values records.
     const unsigned long long units = (unsigned long long)d->B * d->NH * d->D, e = io_size(d->io_dtype);
     const unsigned long long slab_max = 0x7FFFFFFFull;
-    if (units * num_states(d->cell) * 4 > slab_max || units * num_gates(d->cell) * e > slab_max || units * kCacheSlots * e > slab_max)
+    if (units * num_states(d->cell) * 4 > slab_max || units * num_gates(d->cell) * e > slab_max || units * record_slots(d->cell) * e > slab_max)
         return FLASHRNN_ERR_UNSUPPORTED;
     return FLASHRNN_OK;
 }
@@ -147,7 +147,7 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
             size_t smem = (size_t)2 * e.BT * (dk + (bf ? 8 : 4)) * (bf ? 2 : 4);
             if (e.tile == 1 && bwd) {
                 const int nsb = d->cell == FLASHRNN_SLSTM ? 2 : d->cell == FLASHRNN_ELMAN ? 0 : 1, go = d->cell == FLASHRNN_GRU ? G + 1 : G;
-                smem = tile_lds_bwd(e.BT, go, nsb, d->D, dk * 2, e.eb).total;
+                smem = tile_lds_bwd(e.BT, go, nsb, d->D, dk * 2, e.eb, record_slots(d->cell) * 2).total;
             } else if (e.tile == 1) {
                 smem = tile_lds(e.BT, G, num_states(d->cell), d->D, 64 * nw, dk * 2).total_fwd;
             }
@@ -468,7 +468,7 @@ int flashrnn_num_gates(int cell) { return num_gates(cell); }
 
 size_t flashrnn_gate_cache_bytes(const flashrnn_desc_t* d) {
     if (validate(d) != FLASHRNN_OK) return 0;
-    return (size_t)d->T * d->B * d->NH * d->D * kCacheSlots * io_size(d->io_dtype);
+    return (size_t)d->T * d->B * d->NH * d->D * record_slots(d->cell) * io_size(d->io_dtype);
 }
 
 size_t flashrnn_workspace_bytes(const flashrnn_desc_t* d) {

@@ -26,22 +26,24 @@ typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4;
 typedef __attribute__((__vector_size__(2 * sizeof(int)))) int i32x2;
 
 template <int CELL> struct CellTraits;
-template <> struct CellTraits<CELL_LSTM> { static constexpr int G = 4, S = 2, NC = 4; };
-template <> struct CellTraits<CELL_GRU> { static constexpr int G = 3, S = 1, NC = 4; };
-template <> struct CellTraits<CELL_SLSTM> { static constexpr int G = 4, S = 4, NC = 5; };
-template <> struct CellTraits<CELL_ELMAN> { static constexpr int G = 1, S = 1, NC = 1; };
-template <> struct CellTraits<CELL_GRU4> { static constexpr int G = 4, S = 1, NC = 4; };
+template <> struct CellTraits<CELL_LSTM> { static constexpr int G = 4, S = 2, NC = 4, RS = 4; };
+template <> struct CellTraits<CELL_GRU> { static constexpr int G = 3, S = 1, NC = 4, RS = 4; };
+template <> struct CellTraits<CELL_SLSTM> { static constexpr int G = 4, S = 4, NC = 5, RS = 8; };
+template <> struct CellTraits<CELL_ELMAN> { static constexpr int G = 1, S = 1, NC = 1, RS = 1; };
+template <> struct CellTraits<CELL_GRU4> { static constexpr int G = 4, S = 1, NC = 4, RS = 4; };
 // NC = values per (t, batch row, unit) the forward pass saves for the backward pass:
 //   LSTM  sig(i), sig(f), tanh(z), sig(o)
 //   GRU   sig(r), sig(z), tanh(candidate), yn = R_n h + b_n
 //   sLSTM input weight exp(i - m_t), forget weight exp(log sig(f) + m_{t-1} - m_t), tanh(z), sig(o), sig(-f)
 //   Elman h_t
 //   GRU4  sig(z), sig(r), tanh(n + sig(r) tanh(g)), tanh(g)
-
-// The saved values of one (t, batch row, head, unit) form one 16-byte record of kCacheSlots elements
-// (bf16 I/O; with f32 I/O the record is 32 bytes): cache[T][B][NH][D][kCacheSlots].  One record is one
-// wide store in the forward pass and one wide load in the backward pass.
-constexpr int kCacheSlots = 8;
+// They form one record of RS >= NC elements of the I/O dtype per (t, batch row, head, unit): cache[T][B][NH][D][RS].
+// RS = NC except for the sLSTM, whose five values are padded to eight: a bf16 record is then one aligned 16-byte access
+// in HBM and in the LDS images (8 bytes for the four-value cells, 2 for Elman; twice that with f32 I/O).  A 12-byte
+// sLSTM record was measured: its unaligned accesses cost the staged backward kernel 5 % (three 4-byte LDS reads) to 12 %
+// (one 12-byte read) at D = 192, and neither sLSTM workload is bound by HBM traffic.  One record is one store in the
+// forward pass and one load in the backward pass.
+__host__ __device__ constexpr int record_slots(int cell) { return cell == CELL_SLSTM ? 8 : cell == CELL_ELMAN ? 1 : 4; }
 
 // Row pitch (bytes) of an LDS row image whose rows hold `row_bytes` of data: padded so that
 // consecutive rows start 16 banks (64 bytes) apart modulo the 64 banks, which keeps the 4-rows x
@@ -90,7 +92,7 @@ struct TileLdsBwd {
     uint32_t total;
 };
 __host__ __device__ inline uint32_t round_up(uint32_t a, uint32_t b) { return (a + b - 1) / b * b; }
-__host__ __device__ inline TileLdsBwd tile_lds_bwd(int BT, int GO, int NSB, int D, int k_bytes, int EBK) {
+__host__ __device__ inline TileLdsBwd tile_lds_bwd(int BT, int GO, int NSB, int D, int k_bytes, int EBK, int rec_bytes) {
     TileLdsBwd L;
     const uint32_t NT = 4u * (uint32_t)D, PP = (uint32_t)BT / 4u;
     L.hp = lds_row_pitch((uint32_t)k_bytes);
@@ -98,7 +100,7 @@ __host__ __device__ inline TileLdsBwd tile_lds_bwd(int BT, int GO, int NSB, int 
     L.red_off = 2u * BT * L.hp;
     const uint32_t red_bytes = EBK > 1 ? (NT / 64u) * EBK * 64u * PP * 4u : 0u;
     L.in_off = L.red_off + red_bytes;
-    L.st_off = (uint32_t)BT * D * 16u;
+    L.st_off = round_up((uint32_t)BT * D * (uint32_t)rec_bytes, 1024u);
     L.dh_off = L.st_off + round_up((uint32_t)BT * NSB * D * 4u, 1024u);
     L.in_pitch = L.dh_off + round_up((uint32_t)BT * D * 2u, 1024u);
     L.out_off = L.in_off + 2u * L.in_pitch;
@@ -123,7 +125,7 @@ struct KernelParams {
     const void* bias;      // [NH,G,D] io
     const float* states0;  // fwd: [S,B,NH,D] or null
     float* states;         // [T+1,S,B,NH,D]
-    void* cache;           // [T,B,NH,D,kCacheSlots] io dtype, may be null in fwd
+    void* cache;           // [T,B,NH,D,RS] io dtype (RS = record_slots(cell)), may be null in fwd
     const void* dH;        // bwd: [T,B,NH,D] io
     const float* dlast;    // bwd: [S,B,NH,D] or null
     void* dWx;             // bwd: [T,B,G,NH,D] io
@@ -320,39 +322,76 @@ __device__ __forceinline__ void load_chunk_to_lds(rsrc_t r, char* lds, uint32_t 
 #endif
 }
 
-// one saved-values record (NC values used of kCacheSlots) at byte offset voff + soff of resource r
-template <bool BF16, int NC> __device__ __forceinline__ void store_record(rsrc_t r, uint32_t voff, uint32_t soff, const float (&v)[NC]) {
-    float w[kCacheSlots];
+// One saved-values record (NC values, padded with zeros to RS slots) at byte offset voff + soff of resource r:
+// RS elements of the I/O dtype, moved by the widest instructions that tile its 2 .. 32 bytes.
+typedef __attribute__((__vector_size__(3 * sizeof(int)))) int i32x3;
+template <int NW> struct RecordWords { uint32_t w[NW]; };   // a record as 32-bit words (NW = 0: one 16-bit element in w0)
+template <bool BF16, int RS, int NC> __device__ __forceinline__ void pack_record(const float (&v)[NC], uint32_t (&w)[(BF16 ? (RS + 1) / 2 : RS)]) {
+    float x[RS + 1];
 #pragma unroll
-    for (int j = 0; j < kCacheSlots; ++j) w[j] = j < NC ? v[j] : 0.0f;
+    for (int j = 0; j < RS + 1; ++j) x[j] = j < NC ? v[j] : 0.0f;
     if constexpr (BF16) {
-        __builtin_amdgcn_raw_buffer_store_b128(i32x4{(int)pack_bf16x2(w[0], w[1]), (int)pack_bf16x2(w[2], w[3]), (int)pack_bf16x2(w[4], w[5]),
-                                                     (int)pack_bf16x2(w[6], w[7])}, r, voff, soff, 0);
+#pragma unroll
+        for (int j = 0; j < (RS + 1) / 2; ++j) w[j] = pack_bf16x2(x[2 * j], x[2 * j + 1]);
     } else {
-        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(i32x4, f32x4{w[0], w[1], w[2], w[3]}), r, voff, soff, 0);
-        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(i32x4, f32x4{w[4], w[5], w[6], w[7]}), r, voff + 16, soff, 0);
+#pragma unroll
+        for (int j = 0; j < RS; ++j) w[j] = __builtin_bit_cast(uint32_t, x[j]);
     }
 }
-template <bool BF16, int NC> __device__ __forceinline__ void unpack_record(const i32x4 lo, const i32x4 hi, float (&v)[NC]) {
-    float w[kCacheSlots];
-    if constexpr (BF16) {
-        const int a = lo[0], b = lo[1], c2 = lo[2], d = lo[3];
-        w[0] = bf16_bits_to_f32((uint32_t)a & 0xFFFFu); w[1] = __builtin_bit_cast(float, (uint32_t)a & 0xFFFF0000u);
-        w[2] = bf16_bits_to_f32((uint32_t)b & 0xFFFFu); w[3] = __builtin_bit_cast(float, (uint32_t)b & 0xFFFF0000u);
-        w[4] = bf16_bits_to_f32((uint32_t)c2 & 0xFFFFu); w[5] = __builtin_bit_cast(float, (uint32_t)c2 & 0xFFFF0000u);
-        w[6] = bf16_bits_to_f32((uint32_t)d & 0xFFFFu); w[7] = __builtin_bit_cast(float, (uint32_t)d & 0xFFFF0000u);
-    } else {
-        const f32x4 x = __builtin_bit_cast(f32x4, lo), y = __builtin_bit_cast(f32x4, hi);
-        w[0] = x[0]; w[1] = x[1]; w[2] = x[2]; w[3] = x[3]; w[4] = y[0]; w[5] = y[1]; w[6] = y[2]; w[7] = y[3];
-    }
+template <bool BF16, int RS, int NC> __device__ __forceinline__ void unpack_words(const uint32_t (&w)[(BF16 ? (RS + 1) / 2 : RS)], float (&v)[NC]) {
 #pragma unroll
-    for (int j = 0; j < NC; ++j) v[j] = w[j];
+    for (int j = 0; j < NC; ++j) {
+        if constexpr (BF16) v[j] = (j & 1) ? __builtin_bit_cast(float, w[j / 2] & 0xFFFF0000u) : bf16_bits_to_f32(w[j / 2] & 0xFFFFu);
+        else v[j] = __builtin_bit_cast(float, w[j]);
+    }
 }
-template <bool BF16, int NC> __device__ __forceinline__ void load_record(rsrc_t r, uint32_t voff, uint32_t soff, float (&v)[NC]) {
-    const i32x4 lo = __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
-    i32x4 hi = lo;
-    if constexpr (!BF16) hi = __builtin_amdgcn_raw_buffer_load_b128(r, voff + 16, soff, 0);
-    unpack_record<BF16, NC>(lo, hi, v);
+template <bool BF16, int RS, int NC> __device__ __forceinline__ void store_record(rsrc_t r, uint32_t voff, uint32_t soff, const float (&v)[NC]) {
+    constexpr int NW = BF16 ? (RS + 1) / 2 : RS;
+    uint32_t w[NW];
+    pack_record<BF16, RS, NC>(v, w);
+    if constexpr (BF16 && RS == 1) __builtin_amdgcn_raw_buffer_store_b16((unsigned short)(w[0] & 0xFFFFu), r, voff, soff, 0);
+    else if constexpr (NW == 1) __builtin_amdgcn_raw_buffer_store_b32(w[0], r, voff, soff, 0);
+    else if constexpr (NW == 2) __builtin_amdgcn_raw_buffer_store_b64(i32x2{(int)w[0], (int)w[1]}, r, voff, soff, 0);
+    else if constexpr (NW == 3) __builtin_amdgcn_raw_buffer_store_b96(i32x3{(int)w[0], (int)w[1], (int)w[2]}, r, voff, soff, 0);
+    else if constexpr (NW == 4) __builtin_amdgcn_raw_buffer_store_b128(i32x4{(int)w[0], (int)w[1], (int)w[2], (int)w[3]}, r, voff, soff, 0);
+    else {
+        static_assert(NW == 8, "record sizes: 1, 2, 3, 4 or 8 dwords");
+        __builtin_amdgcn_raw_buffer_store_b128(i32x4{(int)w[0], (int)w[1], (int)w[2], (int)w[3]}, r, voff, soff, 0);
+        __builtin_amdgcn_raw_buffer_store_b128(i32x4{(int)w[4], (int)w[5], (int)w[6], (int)w[7]}, r, voff + 16, soff, 0);
+    }
+}
+template <bool BF16, int RS, int NC> __device__ __forceinline__ void load_record(rsrc_t r, uint32_t voff, uint32_t soff, float (&v)[NC]) {
+    constexpr int NW = BF16 ? (RS + 1) / 2 : RS;
+    uint32_t w[NW];
+    if constexpr (BF16 && RS == 1) w[0] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(r, voff, soff, 0);
+    else if constexpr (NW == 1) w[0] = __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0);
+    else if constexpr (NW == 2) { const i32x2 x = __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0); w[0] = (uint32_t)x[0]; w[1] = (uint32_t)x[1]; }
+    else if constexpr (NW == 3) { const i32x3 x = __builtin_amdgcn_raw_buffer_load_b96(r, voff, soff, 0); w[0] = (uint32_t)x[0]; w[1] = (uint32_t)x[1]; w[2] = (uint32_t)x[2]; }
+    else if constexpr (NW == 4) { const i32x4 x = __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0); w[0] = (uint32_t)x[0]; w[1] = (uint32_t)x[1]; w[2] = (uint32_t)x[2]; w[3] = (uint32_t)x[3]; }
+    else {
+        static_assert(NW == 8, "record sizes: 1, 2, 3, 4 or 8 dwords");
+        const i32x4 x = __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
+        const i32x4 y = __builtin_amdgcn_raw_buffer_load_b128(r, voff + 16, soff, 0);
+        w[0] = (uint32_t)x[0]; w[1] = (uint32_t)x[1]; w[2] = (uint32_t)x[2]; w[3] = (uint32_t)x[3];
+        w[4] = (uint32_t)y[0]; w[5] = (uint32_t)y[1]; w[6] = (uint32_t)y[2]; w[7] = (uint32_t)y[3];
+    }
+    unpack_words<BF16, RS, NC>(w, v);
+}
+// a bf16 record out of an LDS image (4-byte aligned, 2-byte aligned for the one-element record)
+template <int RS, int NC> __device__ __forceinline__ void take_record_lds(const char* p, float (&v)[NC]) {
+    constexpr int NW = (RS + 1) / 2;
+    uint32_t w[NW];
+    typedef int i32x2_a4 __attribute__((ext_vector_type(2), aligned(4)));
+    typedef int i32x3_a4 __attribute__((ext_vector_type(3), aligned(4)));
+    if constexpr (RS == 1) w[0] = *(const uint16_t*)p;
+    else if constexpr (NW == 2) { const i32x2_a4 x = *(const i32x2_a4*)p; w[0] = (uint32_t)x.x; w[1] = (uint32_t)x.y; }
+    else if constexpr (NW == 3) { const i32x3_a4 x = *(const i32x3_a4*)p; w[0] = (uint32_t)x.x; w[1] = (uint32_t)x.y; w[2] = (uint32_t)x.z; }
+    else if constexpr (NW == 4) { const i32x4 x = *(const i32x4*)p; w[0] = (uint32_t)x[0]; w[1] = (uint32_t)x[1]; w[2] = (uint32_t)x[2]; w[3] = (uint32_t)x[3]; }
+    else {
+#pragma unroll
+        for (int j = 0; j < NW; ++j) w[j] = ((const uint32_t*)p)[j];
+    }
+    unpack_words<true, RS, NC>(w, v);
 }
 
 template <int PP> __device__ __forceinline__ void load_f32(const float* base, size_t idx, float (&out)[PP]) {

@@ -416,16 +416,15 @@ template <bool BF16, int PP> __device__ __forceinline__ void write_operand_lds(c
     }
 }
 
-// partial sums of the KS contraction slices meet in LDS: slices 1.. write, slice 0 adds
+// partial sums of the KS contraction slices meet in LDS: slices 1.. write, slice 0 adds.  A lane's four values of a tile
+// travel as one 16-byte access (64 lanes x 16 bytes back to back: no bank conflicts, a quarter of the LDS instructions).
 template <int NT, int KS>
 __device__ __forceinline__ void reduce_slices(float* red, int parity, int ks, int wu, int NWU, int lane, f32x4 (&acc)[NT]) {
     if constexpr (KS > 1) {
         if (ks > 0) {
 #pragma unroll
             for (int g = 0; g < NT; ++g)
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    red[((((size_t)(parity * (KS - 1) + ks - 1) * NWU + wu) * NT + g) * 4 + i) * 64 + lane] = acc[g][i];
+                *(f32x4*)(red + (((((size_t)(parity * (KS - 1) + ks - 1) * NWU + wu) * NT + g) * 64 + lane) * 4)) = acc[g];
         }
         __syncthreads();
         if (ks == 0) {
@@ -433,9 +432,7 @@ __device__ __forceinline__ void reduce_slices(float* red, int parity, int ks, in
             for (int s = 1; s < KS; ++s)
 #pragma unroll
                 for (int g = 0; g < NT; ++g)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        acc[g][i] += red[((((size_t)(parity * (KS - 1) + s - 1) * NWU + wu) * NT + g) * 4 + i) * 64 + lane];
+                    acc[g] += *(const f32x4*)(red + (((((size_t)(parity * (KS - 1) + s - 1) * NWU + wu) * NT + g) * 64 + lane) * 4));
         }
     }
 }
@@ -499,7 +496,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
     const uint32_t wx_gate = HD * ESZ;
     const size_t st_step = (size_t)S * B * HD * 4;
     const uint32_t st_state = (uint32_t)B * HD * 4;
-    constexpr uint32_t REC = kCacheSlots * ESZ;                 // bytes of one saved-values record
+    constexpr uint32_t REC = CT::RS * ESZ;                      // bytes of one saved-values record
     const size_t c_step = (size_t)B * HD * REC;
     // LDS lane offsets inside one operand buffer
     const uint32_t lds_rd = (uint32_t)lm.bslot * HP * ESZ;     // row this lane reads as the B operand column
@@ -687,7 +684,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
                             float rec[NC];
 #pragma unroll
                             for (int c2 = 0; c2 < NC; ++c2) rec[c2] = cvs[eb][c2][i];
-                            store_record<BF16, NC>(rs_c, soff_c + (eb * 16 + i) * REC, 0, rec);
+                            store_record<BF16, CT::RS, NC>(rs_c, soff_c + (eb * 16 + i) * REC, 0, rec);
                         }
                     }
                 }
@@ -757,7 +754,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
     const uint32_t wx_gate = HD * ESZ;
     const size_t st_step = (size_t)S * B * HD * 4;
     const uint32_t st_state = (uint32_t)B * HD * 4;
-    constexpr uint32_t REC = kCacheSlots * ESZ;                 // bytes of one saved-values record
+    constexpr uint32_t REC = CT::RS * ESZ;                      // bytes of one saved-values record
     const size_t c_step = (size_t)B * HD * REC;
     const size_t dh_step = (size_t)B * HD * ESZ;
     const uint32_t lds_row = (uint32_t)lm.bslot * HP * ESZ;
@@ -829,7 +826,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
 #pragma unroll
             for (int i = 0; i < PP; ++i) {
                 float rec[NC];
-                load_record<BF16, NC>(c_t, voff_c + (eb * 16 + i) * REC, 0, rec);
+                load_record<BF16, CT::RS, NC>(c_t, voff_c + (eb * 16 + i) * REC, 0, rec);
 #pragma unroll
                 for (int c2 = 0; c2 < NC; ++c2) cv_[eb][c2][i] = rec[c2];
             }

@@ -35,7 +35,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
     constexpr int DK = KT * 32;
     constexpr int NCH_IN = (BT * G + 31) / 32, NCH_ST = (BT * S + 15) / 16;
     constexpr uint32_t kDrop = 0x80000000u;
-    constexpr uint32_t REC = kCacheSlots * ESZ;
+    constexpr uint32_t REC = CT::RS * ESZ;
     static_assert(BT == 4 || BT == 8, "batch tiles of 4 or 8 rows");
 
     extern __shared__ __align__(16) char smem[];
@@ -235,7 +235,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
             Cell<CELL, true>::fwd(wxi, ybi, sti, cvi);
 #pragma unroll
             for (int s = 0; s < S; ++s) st[s][i] = sti[s];
-            store_record<true, NC>(rs_c, voff_c + i * REC, 0, cvi);
+            store_record<true, CT::RS, NC>(rs_c, voff_c + i * REC, 0, cvi);
         }
         write_operand_lds<true, PP>(hbuf + (t & 1) * BUF + lds_row, e0, st[0]);
 #pragma unroll
@@ -297,7 +297,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
     constexpr int GO = CELL == CELL_GRU ? G + 1 : G;  // output rows per batch row: dWx (+ the recurrent-side candidate gradient)
     constexpr int NA = EBK == 1 ? 4 : (EBK == 2 ? 2 : 1);   // accumulators per block: independent MFMAs in flight
     constexpr uint32_t kDrop = 0x80000000u;
-    constexpr uint32_t REC = kCacheSlots * ESZ;
+    constexpr uint32_t REC = CT::RS * ESZ;
     static_assert(BT == 4 || BT == 8, "batch tiles of 4 or 8 rows");
     static_assert(BT * NSB <= 16 && BT * GO <= 32, "one chunk per thread and image");
 
@@ -316,7 +316,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
     const size_t wx_step = (size_t)B * G * HD * ESZ, st_step = (size_t)S * B * HD * 4, c_step = (size_t)B * HD * REC;
     const size_t dh_step = (size_t)B * HD * ESZ;
     const uint32_t st_state = (uint32_t)B * HD * 4;
-    const TileLdsBwd L = tile_lds_bwd(BT, GO, NSB, D, DK * 2, EBK);
+    const TileLdsBwd L = tile_lds_bwd(BT, GO, NSB, D, DK * 2, EBK, REC);
     const uint32_t BUF = BT * L.hp;
     char* gbuf = smem;
     float* red = (float*)(smem + L.red_off);
@@ -343,15 +343,18 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
     const uint32_t voff_st = ((uint32_t)bb * HD + e0) * 4;
 
     // ---- chunk roles: global byte offsets (out of range = nothing to move)
-    uint32_t cc_g[PP], cst_g, cdh_g, cout_g, cout_n, cout_l;
-    bool out_real;
+    constexpr int NCC = (BT * (int)REC + 63) / 64;   // record chunks per thread: BT rows of D records, NT = 4 D threads
+    uint32_t cc_g[NCC], cst_g, cdh_g, cout_g, cout_n, cout_l;
+    bool out_real, c_wave[NCC];
     const uint32_t cpr_io = (uint32_t)D / 8;
     const bool st_wave = (uint32_t)w * 64 < (uint32_t)BT * NSB * (D / 4), dh_wave = (uint32_t)w * 64 < (uint32_t)BT * cpr_io;
     {
+        const uint32_t cpr_c = (uint32_t)D * REC / 16, nch_c = (uint32_t)BT * cpr_c;
 #pragma unroll
-        for (int k2 = 0; k2 < PP; ++k2) {   // records: chunk idx = slot * D + unit
-            const uint32_t idx = tid + k2 * NT, row = idx / (uint32_t)D, u = idx % (uint32_t)D, brow = q * BT + row;
-            cc_g[k2] = brow < (uint32_t)B ? (brow * HD + u) * REC : kDrop;
+        for (int k2 = 0; k2 < NCC; ++k2) {   // records: a row of the image is the D records of one batch row
+            const uint32_t idx = tid + k2 * NT, row = idx / cpr_c, ch = idx % cpr_c, brow = q * BT + row;
+            cc_g[k2] = (idx < nch_c && brow < (uint32_t)B) ? (brow * HD) * REC + ch * 16 : kDrop;
+            c_wave[k2] = (uint32_t)w * 64 + k2 * NT < nch_c;   // (a wave beyond the image must not land zeros behind it)
         }
         {   // state rows: row = state * BT + slot
             const uint32_t cpr_st = (uint32_t)D / 4;
@@ -403,7 +406,8 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
                      rdh = make_rsrc(dh_g + (size_t)(j - 1) * dh_step);
         char* img = in_img + (j & 1) * L.in_pitch + (uint32_t)w * 1024;
 #pragma unroll
-        for (int k2 = 0; k2 < PP; ++k2) load_chunk_to_lds(rc, img + (uint32_t)k2 * NT * 16, cc_g[k2]);
+        for (int k2 = 0; k2 < NCC; ++k2)
+            if (c_wave[k2]) load_chunk_to_lds(rc, img + (uint32_t)k2 * NT * 16, cc_g[k2]);
         if (st_wave) load_chunk_to_lds(rst, img + L.st_off, cst_g);
         if (dh_wave) load_chunk_to_lds(rdh, img + L.dh_off, cdh_g);
     };
@@ -413,8 +417,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
 #pragma unroll
         for (int i = 0; i < PP; ++i) {
             float rec[NC];
-            const i32x4 r = *(const i32x4*)(img + l_c + i * REC);
-            unpack_record<true, NC>(r, r, rec);
+            take_record_lds<CT::RS, NC>(img + l_c + i * REC, rec);
 #pragma unroll
             for (int c2 = 0; c2 < NC; ++c2) cv[c2][i] = rec[c2];
         }

@@ -84,7 +84,8 @@ def test_sizes_and_plans_of_the_benchmark_configurations():
     from paper_2412_07752_amd import synth
     for w in synth.CONFIGS:
         d = api.make_desc(w.cell, w.T, w.B, w.NH, w.D, api.FLASHRNN_BF16 if w.dtype == "bf16" else api.FLASHRNN_F32)
-        assert api.flashrnn_gate_cache_bytes(d) == w.T * w.B * w.NH * w.D * 8 * (2 if w.dtype == "bf16" else 4)
+        slots = {0: 4, 1: 4, 2: 8, 3: 1, 4: 4}[w.cell]   # values saved per (t, row, unit): four, the sLSTM's five padded to eight, Elman one
+        assert api.flashrnn_gate_cache_bytes(d) == w.T * w.B * w.NH * w.D * slots * (2 if w.dtype == "bf16" else 4)
         assert api.flashrnn_workspace_bytes(d) > 0
         for bwd in (False, True):
             wgs, per_head, waves = api.flashrnn_plan(d, bwd)
