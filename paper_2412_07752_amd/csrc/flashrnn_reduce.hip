@@ -170,19 +170,29 @@ __global__ __launch_bounds__(256) void dr_gemm_kernel(const float* __restrict__ 
         }
 }
 
-// bf16 operands, (64 WM) x 256 outputs per workgroup (WM x 4 waves, 64 x 64 per wave: 16 MFMAs per 32 contraction rows from
-// 8 LDS reads): less traffic between L2 and the CUs per flop than the 64 x 128 tile.  Used with WM = 2.  Same loader as above:
-// a thread takes one pair of contraction rows x 4 consecutive d (A) and, the first 512 threads, x 8 consecutive columns (B).
-template <int WM>
-__global__ __launch_bounds__(WM * 256) void dr_gemm_wide_kernel(const float* __restrict__ states, const void* __restrict__ dWx,
-                                                               const void* __restrict__ dgn, float* __restrict__ out, int T, int B, int NH,
-                                                               int D, int G, int S, int SK, int gru) {
-    constexpr int TMW = 64 * WM, TNW = 256, NT = WM * 256, PITCH = TK + 8;
-    constexpr int NBI = NT >= 512 ? 1 : 2;
-    __shared__ __align__(16) char ldsA[TMW * PITCH * 2];
-    __shared__ __align__(16) char ldsB[TNW * PITCH * 2];
+// bf16 operands without any hand transposition.  Both operands have the contraction index (t, b) as their slow memory
+// axis; the tiles go to LDS as they are, [contraction row][column], 16 bytes at a time (h converted from f32 on the way),
+// and the matrix-core operands -- 8 contraction elements per lane -- are read with the transposing LDS load of gfx950
+// (ds_read_b64_tr_b16: the 16 lanes of a quad read 4 rows x 16 columns and each lane gets the 4 rows of its column).
+// Quad q's 8 elements are the rows 4q..4q+3 and 16+4q..16+4q+3 of a round of 32 rows (any assignment of rows to lanes is
+// right as long as both operands use the same one): one load then touches 16 consecutive rows, which a row pitch of
+// (width + 16 elements) spreads over all 64 banks twice, the minimum for its 512 bytes.
+// Tile: (16 FM WM) x (16 FN WN) outputs per workgroup of WM x WN waves, 32 contraction rows per round, two LDS buffers
+// (one barrier per round), the next round's global loads in flight during the MFMAs.
+template <int FM, int FN, int WM, int WN>
+__global__ __launch_bounds__(WM * WN * 64) void dr_gemm_tr_kernel(const float* __restrict__ states, const void* __restrict__ dWx,
+                                                                 const void* __restrict__ dgn, float* __restrict__ out, int T, int B, int NH,
+                                                                 int D, int G, int S, int SK, int gru) {
+    constexpr int TMW = 16 * FM * WM, TNW = 16 * FN * WN, NT = 64 * WM * WN;
+    constexpr int PA = TMW + 16, PB = TNW + 16;                   // LDS row pitches in bf16 elements
+    constexpr int LA = TK * TMW / 4 / NT, LB = TK * TNW / 8 / NT;   // 16-byte global chunks per thread and round
+    static_assert(TK == 32 && LA >= 1 && LB >= 1 && (TK * TMW / 4) % NT == 0 && (TK * TNW / 8) % NT == 0, "loader tiling");
+    __shared__ __align__(16) uint16_t ldsA[2][TK * PA];
+    __shared__ __align__(16) uint16_t ldsB[2][TK * PB];
     const int GD = G * D;
     const int tiles_n = (GD + TNW - 1) / TNW, tiles_m = (D + TMW - 1) / TMW;
+    // Workgroup i runs on XCD i % 8.  All tiles of one (head, K slice) share their operand rows, so they get block indices
+    // that are equal modulo 8 and re-read those rows from one L2.
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, tiles = tiles_n * tiles_m;
     const int combo = (slot / tiles) * 8 + xcd, tile = slot % tiles;
     if (combo >= SK * NH) return;
@@ -193,105 +203,120 @@ __global__ __launch_bounds__(WM * 256) void dr_gemm_wide_kernel(const float* __r
     const int kbeg = sk * kchunk, kend = min(K, kbeg + kchunk);
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int c = lane & 15, quad = lane >> 4;
-    const int wm = w >> 2, wn = w & 3;
-    f32x4 acc[4][4];
+    const int wm = w / WN, wn = w % WN;
+
+    f32x4 acc[FM][FN];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < FM; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const int kp = tid & 15;
-    const int a_d = (tid >> 4) * 4;
-    const int d_glob = tm * TMW + a_d;
-    const bool a_ok = d_glob < D;
-    int b_j[NBI];
-    bool b_ok[NBI];
-    size_t b_off[NBI], b_row[NBI];
-    const char* b_base[NBI];
-#pragma unroll
-    for (int x = 0; x < NBI; ++x) {
-        const int item = (tid >> 4) + x * (NT / 16);
-        b_j[x] = item * 8;
-        const int j_glob = tn * TNW + b_j[x];
-        b_ok[x] = item < 32 && j_glob < GD;
-        const int bg = b_ok[x] ? j_glob / D : 0, be = b_ok[x] ? j_glob % D : 0;
-        const bool from_dgn = gru && bg == 2;
-        b_base[x] = (const char*)(from_dgn ? dgn : dWx);
-        b_row[x] = from_dgn ? (size_t)NH * D : (size_t)G * NH * D;
-        b_off[x] = from_dgn ? (size_t)n * D + be : ((size_t)bg * NH + n) * D + be;
-    }
-    int kk_[2], bb_[2];
-    size_t offA[2];
+        for (int j = 0; j < FN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // ---- loader roles.  A chunk = 4 consecutive d of one contraction row (f32), B chunk = 8 consecutive columns (bf16).
+    // Chunk x of a thread: row ra_row[x] of the round, fixed column; the row's position k = (tt, b) is advanced per round
+    // without divisions (a round is TK rows = adv_q time steps + adv_r batch rows).
+    constexpr int CA = TMW / 4, CB = TNW / 8;   // chunks per tile row
     const size_t HD = (size_t)NH * D;
     const int adv_q = TK / B, adv_r = TK % B;
     const size_t incA0 = (size_t)TK * HD + (size_t)adv_q * (size_t)(S - 1) * B * HD, incA1 = incA0 + (size_t)(S - 1) * B * HD;
+    int a_row[LA], a_col[LA], a_bb[LA];
+    size_t a_off[LA];
+    bool a_ok[LA];
 #pragma unroll
-    for (int r = 0; r < 2; ++r) {
-        const int k = kbeg + kp * 2 + r, tt = k / B;
-        kk_[r] = k;
-        bb_[r] = k - tt * B;
-        offA[r] = ((size_t)tt * S * B + bb_[r]) * HD + (size_t)n * D + d_glob;
+    for (int x = 0; x < LA; ++x) {
+        const int ch = tid + x * NT;
+        a_row[x] = ch / CA;
+        a_col[x] = (ch % CA) * 4;
+        const int d_glob = tm * TMW + a_col[x];
+        a_ok[x] = d_glob < D;
+        const int k = kbeg + a_row[x], tt = k / B;
+        a_bb[x] = k - tt * B;
+        a_off[x] = ((size_t)tt * S * B + a_bb[x]) * HD + (size_t)n * D + (a_ok[x] ? d_glob : 0);   // row = h_{tt}: the state before step tt + 1
     }
-    f32x4 ra[2];
-    i32x4 rb[NBI][2];
-    bool okr[2];
+    int b_row[LB], b_col[LB];
+    size_t b_off[LB], b_rowstride[LB];
+    const char* b_base[LB];
+    bool b_ok[LB];
+#pragma unroll
+    for (int x = 0; x < LB; ++x) {
+        const int ch = tid + x * NT;
+        b_row[x] = ch / CB;
+        b_col[x] = (ch % CB) * 8;
+        const int j_glob = tn * TNW + b_col[x];
+        b_ok[x] = j_glob < GD;
+        const int bg = b_ok[x] ? j_glob / D : 0, be = b_ok[x] ? j_glob % D : 0;
+        const bool from_dgn = gru && bg == 2;
+        b_base[x] = (const char*)(from_dgn ? dgn : dWx);
+        b_rowstride[x] = from_dgn ? (size_t)NH * D : (size_t)G * NH * D;
+        b_off[x] = (size_t)(kbeg + b_row[x]) * b_rowstride[x] + (from_dgn ? (size_t)n * D + be : ((size_t)bg * NH + n) * D + be);
+    }
+    f32x4 ra[LA];
+    i32x4 rb[LB];
+    int kround = kbeg;   // first contraction row of the round the registers hold
     auto load_tiles = [&]() __attribute__((always_inline)) {
 #pragma unroll
-        for (int r = 0; r < 2; ++r) {
-            okr[r] = kk_[r] < kend;
-            ra[r] = *(const f32x4*)(states + ((a_ok && okr[r]) ? offA[r] : 0));
-#pragma unroll
-            for (int x = 0; x < NBI; ++x)
-                rb[x][r] = *(const i32x4*)(b_base[x] + ((b_ok[x] && okr[r]) ? (size_t)kk_[r] * b_row[x] + b_off[x] : 0) * 2);
-            kk_[r] += TK;
-            int bb = bb_[r] + adv_r;
+        for (int x = 0; x < LA; ++x) {
+            const bool ok = a_ok[x] && kround + a_row[x] < kend;
+            ra[x] = *(const f32x4*)(states + (ok ? a_off[x] : 0));
+            if (!ok) ra[x] = f32x4{0.f, 0.f, 0.f, 0.f};
+            int bb = a_bb[x] + adv_r;
             const bool wrap = bb >= B;
-            bb_[r] = wrap ? bb - B : bb;
-            offA[r] += wrap ? incA1 : incA0;
+            a_bb[x] = wrap ? bb - B : bb;
+            a_off[x] += wrap ? incA1 : incA0;
         }
+#pragma unroll
+        for (int x = 0; x < LB; ++x) {
+            const bool ok = b_ok[x] && kround + b_row[x] < kend;
+            rb[x] = *(const i32x4*)(b_base[x] + (ok ? b_off[x] : 0) * 2);
+            if (!ok) rb[x] = i32x4{0, 0, 0, 0};
+            b_off[x] += (size_t)TK * b_rowstride[x];
+        }
+        kround += TK;
     };
+    auto park_tiles = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int x = 0; x < LA; ++x)
+            *(i32x2*)(&ldsA[buf][a_row[x] * PA + a_col[x]]) = i32x2{(int)pack_bf16x2(ra[x][0], ra[x][1]), (int)pack_bf16x2(ra[x][2], ra[x][3])};
+#pragma unroll
+        for (int x = 0; x < LB; ++x) *(i32x4*)(&ldsB[buf][b_row[x] * PB + b_col[x]]) = rb[x];
+    };
+    // this lane's part of a transposing load: row 4 quad + c / 4 (+ 16 for the second half), columns 4 (c % 4) .. + 3 of a 16-column block
+    const int tr_row = 4 * quad + (c >> 2), tr_col = 4 * (c & 3);
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    auto operand = [&](const uint16_t* tile, int pitch, int col0) __attribute__((always_inline)) -> bf16x8 {
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + tr_row * pitch + col0 + tr_col));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + (16 + tr_row) * pitch + col0 + tr_col));
+        typedef short s16x8 __attribute__((ext_vector_type(8)));
+        const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        return __builtin_bit_cast(bf16x8, v);
+    };
+
     load_tiles();
-    for (int kb = kbeg; kb < kend; kb += TK) {
-        __syncthreads();
-        {
-            f32x4 a0 = ra[0], a1 = ra[1];
-            if (!(a_ok && okr[0])) a0 = f32x4{0.f, 0.f, 0.f, 0.f};
-            if (!(a_ok && okr[1])) a1 = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int i = 0; i < 4; ++i) *(uint32_t*)(ldsA + ((a_d + i) * PITCH + kp * 2) * 2) = pack_bf16x2(a0[i], a1[i]);
-#pragma unroll
-            for (int x = 0; x < NBI; ++x) {
-                if (NBI == 1 && tid >= 512) break;
-                const i32x4 b0 = (b_ok[x] && okr[0]) ? rb[x][0] : i32x4{0, 0, 0, 0};
-                const i32x4 b1 = (b_ok[x] && okr[1]) ? rb[x][1] : i32x4{0, 0, 0, 0};
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const uint32_t x0 = (uint32_t)b0[i >> 1], x1 = (uint32_t)b1[i >> 1];
-                    const uint32_t v = (i & 1) ? ((x1 & 0xFFFF0000u) | (x0 >> 16)) : ((x1 << 16) | (x0 & 0xFFFFu));
-                    *(uint32_t*)(ldsB + ((b_j[x] + i) * PITCH + kp * 2) * 2) = v;
-                }
-            }
-        }
+    int buf = 0;
+    for (int kb = kbeg; kb < kend; kb += TK, buf ^= 1) {
+        park_tiles(buf);       // (the buffer was last read two rounds ago: the barrier of the previous round lies in between)
         __syncthreads();
         if (kb + TK < kend) load_tiles();
-        bf16x8 af[4], bf[4];
+        bf16x8 af[FM], bfr[FN];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) af[i] = *(const bf16x8*)(ldsA + ((wm * 64 + i * 16 + c) * PITCH + quad * 8) * 2);
+        for (int i = 0; i < FM; ++i) af[i] = operand(ldsA[buf], PA, (wm * FM + i) * 16);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) bf[j] = *(const bf16x8*)(ldsB + ((wn * 64 + j * 16 + c) * PITCH + quad * 8) * 2);
+        for (int j = 0; j < FN; ++j) bfr[j] = operand(ldsB[buf], PB, (wn * FN + j) * 16);
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < FM; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+            for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
+    // ---- store: lane holds column c and rows 4*quad + r of each 16x16 tile
     float* dst = out + ((size_t)sk * NH + n) * (size_t)D * GD;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < FM; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int col = tn * TNW + wn * 64 + j * 16 + c;
+        for (int j = 0; j < FN; ++j) {
+            const int col = tn * TNW + (wn * FN + j) * 16 + c;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int row = tm * TMW + wm * 64 + i * 16 + quad * 4 + r;
+                const int row = tm * TMW + (wm * FM + i) * 16 + quad * 4 + r;
                 if (row < D && col < GD) dst[(size_t)row * GD + col] = acc[i][j][r];
             }
         }
@@ -401,10 +426,10 @@ hipError_t launch_dr_gemm(bool bf16, const float* states, const void* dWx, const
     float* target = SK == 1 ? dR : part;
     if (dr_use_wide(bf16, NH, D, G)) {
         const int grid = (NH * SK + 7) / 8 * 8 * ((D + 127) / 128) * ((GD + 255) / 256);   // (head, K slice) padded to the 8 XCDs
-        hipLaunchKernelGGL(dr_gemm_wide_kernel<2>, dim3(grid), dim3(512), 0, stream, states, dWx, dgn, target, T, B, NH, D, G, S, SK, gru ? 1 : 0);
+        hipLaunchKernelGGL((dr_gemm_tr_kernel<4, 4, 2, 4>), dim3(grid), dim3(512), 0, stream, states, dWx, dgn, target, T, B, NH, D, G, S, SK, gru ? 1 : 0);
     } else {
         const int grid = (NH * SK + 7) / 8 * 8 * ((D + TM - 1) / TM) * ((GD + TN - 1) / TN);
-        if (bf16) hipLaunchKernelGGL(dr_gemm_kernel<true>, dim3(grid), dim3(256), 0, stream, states, dWx, dgn, target, T, B, NH, D, G, S, SK, gru ? 1 : 0);
+        if (bf16) hipLaunchKernelGGL((dr_gemm_tr_kernel<2, 4, 2, 2>), dim3(grid), dim3(256), 0, stream, states, dWx, dgn, target, T, B, NH, D, G, S, SK, gru ? 1 : 0);
         else hipLaunchKernelGGL(dr_gemm_kernel<false>, dim3(grid), dim3(256), 0, stream, states, dWx, dgn, target, T, B, NH, D, G, S, SK, gru ? 1 : 0);
     }
     hipError_t e = hipGetLastError();
