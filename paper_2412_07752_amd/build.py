@@ -39,7 +39,7 @@ def build(force=False, jobs=None, trace=False):
     """trace=True: the same sources with -DFLASHRNN_TRACE (per-phase clock stamps in the split-group kernels), as
     libflashrnn_trace.so; a measurement build, never what the tests or the benchmark's numbers run on."""
     bdir = os.path.join(CSRC, "_build_trace" if trace else "_build")
-    flags_extra = (["-DFLASHRNN_TRACE"] + os.environ.get("FLASHRNN_TRACE_FLAGS", "").split()) if trace else []
+    flags_extra = ["-DFLASHRNN_TRACE"] if trace else []
     out = OUT.replace("libflashrnn.so", "libflashrnn_trace.so") if trace else OUT
     os.makedirs(bdir, exist_ok=True)
     hdr = _newest_header()

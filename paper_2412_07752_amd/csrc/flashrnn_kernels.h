@@ -611,10 +611,6 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
                 FRNN_TRACE_MARK(0);
                 __syncthreads();   // every wave has read the previous step's rows
                 FRNN_TRACE_MARK(1);
-#ifdef FLASHRNN_TRACE_DRAIN
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                FRNN_TRACE_MARK(0);
-#endif
                 if (!failed) failed = !poller.poll(xr, (cnt & 1u) * xbuf + xgroup, hbuf, cnt + 1u, p.spin_limit, p.err, FRNN_TRACE_FIRST);
                 FRNN_TRACE_SPLIT(7, 2);
                 __syncthreads();
@@ -910,10 +906,6 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
                 FRNN_TRACE_MARK(0);
                 __syncthreads();   // every wave has read the previous step's rows
                 FRNN_TRACE_MARK(1);
-#ifdef FLASHRNN_TRACE_DRAIN
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                FRNN_TRACE_MARK(0);
-#endif
                 if (!failed) failed = !poller.poll(xr, (cnt & 1u) * xbuf + xgroup, gbuf, cnt + 1u, p.spin_limit, p.err, FRNN_TRACE_FIRST);
                 FRNN_TRACE_SPLIT(7, 2);
                 __syncthreads();
