@@ -9,6 +9,7 @@ states).  Inputs are resident in HBM before the timed region.  Prints ONE JSON l
     python bench.py --copy-calibration     # a plain copy of known size, for scaling rocprofv3's HBM counters
     python bench.py --shape slstm,1024,16,4,192   # any (cell, T, B, NH, D) of the paper's sweeps; add ",fwd" for forward only
     python bench.py --sweep [--sweep-out FILE]    # the paper's runtime sweeps (Sec. 6.1, App. H.3/H.5) in one run, as a table
+    python bench.py --workload 4 --recompute      # backward pass without saved values (flashrnn_bwd_recompute)
     python bench.py --workload 4 --trace-phases   # per-phase clocks of a time step (split-group kernels; needs the trace build:
                                                   # python -m paper_2412_07752_amd.build --trace), printed instead of the bench line
 
@@ -66,15 +67,19 @@ def algorithmic_bytes(w, esz, backward_kernel, saves):
 class Runner:
     """Device buffers of one workload and the timed loop over the C-ABI calls."""
 
-    def __init__(self, w, tensors, api, torch):
+    def __init__(self, w, tensors, api, torch, recompute=False):
         self.w, self.api, self.torch = w, api, torch
+        self.recompute = recompute and w.backward
         self.Wx, self.R, self.b, self.s0, self.dH = tensors
         bf16 = w.dtype == "bf16"
         self.desc = api.make_desc(w.cell, w.T, w.B, w.NH, w.D, api.FLASHRNN_BF16 if bf16 else api.FLASHRNN_F32)
         self.ws = api.alloc_workspace(self.desc, "cuda")
+        if self.recompute:   # backward without saved values: the workspace also holds one window of re-formed values
+            import ctypes
+            self.ws = torch.zeros(api.lib().flashrnn_recompute_workspace_bytes(ctypes.byref(self.desc)), dtype=torch.uint8, device="cuda")
         T, B, NH, D, G, S = w.T, w.B, w.NH, w.D, w.G, w.S
         self.states = torch.empty((T + 1, S, B, NH, D), dtype=torch.float32, device="cuda")
-        self.cache = torch.empty(max(api.flashrnn_gate_cache_bytes(self.desc), 16), dtype=torch.uint8, device="cuda") if w.backward else None
+        self.cache = torch.empty(max(api.flashrnn_gate_cache_bytes(self.desc), 16), dtype=torch.uint8, device="cuda") if (w.backward and not self.recompute) else None
         io_dt = torch.bfloat16 if bf16 else torch.float32
         self.out = None
         if w.backward:
@@ -83,9 +88,11 @@ class Runner:
 
     def step(self):
         w, api = self.w, self.api
-        api.flashrnn_fwd(w.cell, self.Wx, self.R, self.b, self.s0, save_for_backward=w.backward, workspace=self.ws, states=self.states,
-                         gate_cache=self.cache)
-        if w.backward:
+        api.flashrnn_fwd(w.cell, self.Wx, self.R, self.b, self.s0, save_for_backward=w.backward and not self.recompute, workspace=self.ws,
+                         states=self.states, gate_cache=self.cache)
+        if self.recompute:
+            api.flashrnn_bwd_recompute(w.cell, self.Wx, self.R, self.b, self.states, self.dH, None, workspace=self.ws, out=self.out)
+        elif w.backward:
             api.flashrnn_bwd(w.cell, self.R, self.b, self.states, self.cache, self.dH, None, workspace=self.ws, out=self.out)
 
     def run(self, steps, warmup):
@@ -182,6 +189,8 @@ def main():
                          "drawn on the GPU; no oracle timing")
     ap.add_argument("--sweep", action="store_true", help="run the paper's head-size / batch / sequence-length sweeps and print a table")
     ap.add_argument("--sweep-out", type=str, default=None, help="also write the sweep table to this file")
+    ap.add_argument("--recompute", action="store_true",
+                    help="backward pass without saved values (flashrnn_bwd_recompute): forward without a gate cache, the values formed again window by window")
     ap.add_argument("--trace-phases", action="store_true",
                     help="load the trace build of the library and print the mean clocks per time step and phase of the persistent kernels")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -233,7 +242,7 @@ def main():
         tensors = (dev(inp["Wx"], w.dtype), dev(inp["R"], w.dtype), dev(inp["b"], w.dtype), dev(inp["states0"], "f32"), dev(inp["dH"], w.dtype))
     bf16 = w.dtype == "bf16"
     T, B, NH, D, G, S = w.T, w.B, w.NH, w.D, w.G, w.S
-    runner = Runner(w, tensors, api, torch)
+    runner = Runner(w, tensors, api, torch, recompute=args.recompute)
     desc = runner.desc
     ms_per_step, fwd_ms, bwd_ms, launches = runner.run(args.steps, args.warmup)
     value = B * T / (ms_per_step * 1e-3)
@@ -333,7 +342,8 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "config": {"workload": w.name, "cell": synth.CELL_NAMES[w.cell], "B": B, "T": T, "NH": NH, "D": D,
-                   "pass": "fwd+bwd" if w.backward else "fwd", "states_dtype": "f32"},
+                   "pass": ("fwd+bwd (values for the backward pass formed again, none saved)" if (args.recompute and w.backward) else
+                            "fwd+bwd" if w.backward else "fwd"), "states_dtype": "f32"},
         "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(line))

@@ -132,6 +132,23 @@ int flashrnn_bwd(const flashrnn_desc_t* desc, const void* R, const void* b, cons
                  void* dstates0, void* workspace, void* hip_stream);
 
 /*
+ * flashrnn_bwd without the buffer of saved values (Alg. 1 "write out gates for backward pass"; App. F: the memory of
+ * back-propagation through time): call flashrnn_fwd with gate_cache = NULL, keep only `states`, and pass the inputs Wx again
+ * here.  The values the backward pass needs are formed again from Wx, R, b and the states, a window of time steps at a
+ * time -- inside a window all h_{t-1} are known, so its pre-activations are one dense contraction per head -- and the
+ * persistent backward kernel runs window by window from the last step to the first.  Same outputs as flashrnn_bwd
+ * within rounding (the saved values are rounded to the I/O dtype either way).
+ *   Wx          [T,B,G,NH,D] io_dtype  the forward call's inputs
+ *   workspace   flashrnn_recompute_workspace_bytes() bytes: the ordinary workspace, the records of one window (as many
+ *               steps as fit 64 MiB) and two buffers for the state gradients carried between windows
+ *   all other arguments as in flashrnn_bwd
+ */
+size_t flashrnn_recompute_workspace_bytes(const flashrnn_desc_t* desc);
+int flashrnn_bwd_recompute(const flashrnn_desc_t* desc, const void* Wx, const void* R, const void* b, const void* states,
+                           const void* dH, const void* dstates_last, void* dWx, void* dR, void* db, void* dstates0,
+                           void* workspace, void* hip_stream);
+
+/*
  * Reads the error words the kernels of the last forward and the last backward call on this workspace left behind
  * (synchronizes the stream).  A plan that splits a head over several CUs waits for its partners with a bounded poll
  * (2^21 polls); if a wait gives up, every kernel still runs to its end, flashrnn_fwd / flashrnn_bwd have long returned
@@ -144,8 +161,9 @@ int flashrnn_bwd(const flashrnn_desc_t* desc, const void* R, const void* b, cons
  * never wait across CUs (one workgroup per group) cannot time out: the call then only synchronizes the stream.
  * Test hooks: with FLASHRNN_PLAN_OVERRIDES=1 in the environment when the library is first called, the variables
  * FLASHRNN_SPIN_LIMIT (a negative value makes every wait give up at once, which exercises this error path without
- * hanging anything) and FLASHRNN_MULTI, _BT, _NWU, _KS, _GPAR, _EB, _EBK, _KIND (single choices of the launch planner,
- * to force every kernel family onto small shapes) are read on every call; without it the environment is never read.
+ * hanging anything), FLASHRNN_MULTI, _BT, _NWU, _KS, _GPAR, _EB, _EBK, _KIND (single choices of the launch planner,
+ * to force every kernel family onto small shapes) and FLASHRNN_RECOMPUTE_STEPS (window length of flashrnn_bwd_recompute)
+ * are read on every call; without it the environment is never read.
  */
 #define FLASHRNN_STATIC_SCRATCH ((const void*)(size_t)1)
 int flashrnn_check(const flashrnn_desc_t* desc, const void* workspace, void* hip_stream);

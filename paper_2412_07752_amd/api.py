@@ -62,6 +62,10 @@ def lib():
         L.flashrnn_fwd_static_scratch.restype = ctypes.c_int
         L.flashrnn_bwd.argtypes = [dp] + [vp] * 12
         L.flashrnn_bwd.restype = ctypes.c_int
+        L.flashrnn_bwd_recompute.argtypes = [dp] + [vp] * 12
+        L.flashrnn_bwd_recompute.restype = ctypes.c_int
+        L.flashrnn_recompute_workspace_bytes.argtypes = [dp]
+        L.flashrnn_recompute_workspace_bytes.restype = ctypes.c_size_t
         L.flashrnn_check.argtypes = [dp, vp, vp]
         L.flashrnn_check.restype = ctypes.c_int
         L.flashrnn_plan.argtypes = [dp, ctypes.c_int] + [ctypes.POINTER(ctypes.c_int)] * 3
@@ -81,7 +85,7 @@ def lib():
 
 
 EXPORTS = ["flashrnn_num_states", "flashrnn_num_gates", "flashrnn_gate_cache_bytes", "flashrnn_workspace_bytes", "flashrnn_fwd",
-           "flashrnn_fwd_static_scratch", "flashrnn_bwd", "flashrnn_check", "flashrnn_plan", "flashrnn_plan_kernel", "flashrnn_profile_enable", "flashrnn_profile_kernel_ms",
+           "flashrnn_fwd_static_scratch", "flashrnn_bwd", "flashrnn_bwd_recompute", "flashrnn_recompute_workspace_bytes", "flashrnn_check", "flashrnn_plan", "flashrnn_plan_kernel", "flashrnn_profile_enable", "flashrnn_profile_kernel_ms",
            "flashrnn_trace_phases", "flashrnn_status_string"]
 
 
@@ -272,6 +276,36 @@ def flashrnn_bwd(cell, R, b, states, gate_cache, dH, dstates_last=None, workspac
     if rc != FLASHRNN_OK:
         raise FlashRNNError(rc, "flashrnn_bwd")
     return dWx, dR, db, ds0
+
+
+def flashrnn_bwd_recompute(cell, Wx, R, b, states, dH, dstates_last=None, workspace=None, stream=None, out=None, recurrent_grad_clip=0.0):
+    """BPTT without saved values: they are formed again from Wx, R, b and the states, window by window.  Arguments and
+    results as flashrnn_bwd, with Wx[T,B,G,NH,D] in place of the gate cache; `workspace` needs
+    flashrnn_recompute_workspace_bytes() bytes."""
+    T, B, NH, D = dH.shape
+    S, G = flashrnn_num_states(cell), flashrnn_num_gates(cell)
+    dt = dH.dtype
+    desc = make_desc(cell, T, B, NH, D, _io_dtype(dH), recurrent_grad_clip)
+    _chk(Wx, (T, B, G, NH, D), dt, "Wx")
+    _chk(R, (NH, D, G, D), dt, "R")
+    _chk(b, (NH, G, D), dt, "b")
+    _chk(states, (T + 1, S, B, NH, D), torch.float32, "states")
+    _chk(dstates_last, (S, B, NH, D), torch.float32, "dstates_last", optional=True)
+    dev = dH.device
+    if out is None:
+        out = (torch.empty((T, B, G, NH, D), dtype=dt, device=dev), torch.empty((NH, D, G, D), dtype=torch.float32, device=dev),
+               torch.empty((NH, G, D), dtype=torch.float32, device=dev), torch.empty((S, B, NH, D), dtype=torch.float32, device=dev))
+    dWx, dR, db, ds0 = out
+    if workspace is None:
+        n = lib().flashrnn_recompute_workspace_bytes(ctypes.byref(desc))
+        if n == 0:
+            raise FlashRNNError(FLASHRNN_ERR_UNSUPPORTED, "flashrnn_recompute_workspace_bytes")
+        workspace = torch.zeros(n, dtype=torch.uint8, device=dev)
+    rc = lib().flashrnn_bwd_recompute(ctypes.byref(desc), _ptr(Wx), _ptr(R), _ptr(b), _ptr(states), _ptr(dH), _ptr(dstates_last),
+                                      _ptr(dWx), _ptr(dR), _ptr(db), _ptr(ds0), _ptr(workspace), _stream(stream))
+    if rc != FLASHRNN_OK:
+        raise FlashRNNError(rc, "flashrnn_bwd_recompute")
+    return dWx, dR, db, ds0, workspace
 
 
 def flashrnn_check(desc, workspace, stream=None):

@@ -13,6 +13,7 @@
 
 #include "flashrnn_common.h"
 #include "flashrnn_host.h"
+#include "flashrnn_recompute.h"
 
 using namespace flashrnn;
 
@@ -459,6 +460,119 @@ int fwd_impl(const flashrnn_desc_t* d, const void* Wx, const void* R, const void
     return launch_persistent(pf, kp, stream);
 }
 
+// Workspace of flashrnn_bwd_recompute behind the ordinary one: the records of one window of time steps and two buffers
+// for the state gradients carried from window to window.  The window holds as many steps as fit 64 MiB (at least one):
+// small enough to stay in the last-level cache between the kernel that writes it and the one that reads it.
+struct RecomputeLayout { size_t window_off, carry_off, total; int window; };
+RecomputeLayout recompute_layout(const flashrnn_desc_t* d, size_t base_total) {
+    RecomputeLayout rl;
+    const size_t units = (size_t)d->B * d->NH * d->D;
+    const size_t rec_step = units * record_slots(d->cell) * io_size(d->io_dtype);
+    long long steps = (long long)((64ull << 20) / (rec_step ? rec_step : 1));
+    const int forced = env_int("FLASHRNN_RECOMPUTE_STEPS", 0);   // (test hook: windows of this many steps)
+    if (forced > 0) steps = forced;
+    if (steps < 1) steps = 1;
+    if (steps > d->T) steps = d->T > 0 ? d->T : 1;
+    rl.window = (int)steps;
+    rl.window_off = base_total;
+    rl.carry_off = rl.window_off + align_up((size_t)steps * rec_step);
+    rl.total = rl.carry_off + 2 * align_up((size_t)num_states(d->cell) * units * 4);
+    return rl;
+}
+
+// Backward call.  Wx == nullptr: the saved values come from gate_cache (flashrnn_bwd).  Otherwise (flashrnn_bwd_recompute)
+// they are formed again, a window of time steps at a time, into the window buffer behind the ordinary workspace, and the
+// persistent kernel runs window by window from the last step to the first, the gradients of the carried states going from
+// one launch to the next through two buffers in the workspace.
+int bwd_impl(const flashrnn_desc_t* d, const void* Wx, const void* R, const void* b, const void* states, const void* gate_cache,
+             const void* dH, const void* dstates_last, void* dWx, void* dR, void* db, void* dstates0, void* workspace, void* hip_stream) {
+    int rc = validate(d);
+    if (rc != FLASHRNN_OK) return rc;
+    const bool recompute = Wx != nullptr;
+    if (!R || !states || !dR || !db || !dstates0 || (d->T > 0 && ((!recompute && !gate_cache) || !dH || !dWx)) || (recompute && !b)) return FLASHRNN_ERR_NULL;
+    if (!aligned16(R) || !aligned16(states) || !aligned16(gate_cache) || !aligned16(dH) || !aligned16(dstates_last) ||
+        !aligned16(dWx) || !aligned16(dR) || !aligned16(db) || !aligned16(dstates0) || !aligned16(Wx) || !aligned16(b))
+        return FLASHRNN_ERR_UNSUPPORTED;
+    Workspace w;
+    Plan pf, pb;
+    rc = carve(d, &w, &pf, &pb);
+    if (rc != FLASHRNN_OK) return rc;
+    if (!workspace || ((uintptr_t)workspace & (kAlign - 1))) return FLASHRNN_ERR_WORKSPACE;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    char* ws = (char*)workspace;
+    const int G = num_gates(d->cell), S = num_states(d->cell);
+    const bool bf = d->io_dtype == FLASHRNN_BF16;
+    const size_t esz = io_size(d->io_dtype);
+    // The backward copy of R is R itself, padded along (gate, unit) to the kernel's contraction length: without padding
+    // and without cross-CU waits (whose error word the packing kernel clears) the kernel reads R where it is.
+    const bool r_in_place = !pb.e->multi && pb.DK == G * d->D;
+    if (!r_in_place && launch_pack_r(bf, true, R, ws + w.rpack_off, d->NH, d->D, G, pb.DK, (int*)(ws + w.err_off) + 1, stream) != hipSuccess)
+        return FLASHRNN_ERR_LAUNCH;
+    const size_t units = (size_t)d->B * d->NH * d->D;
+    const size_t st_step = (size_t)S * units * 4, io_step = units * esz, rec_step = units * record_slots(d->cell) * esz;
+    const RecomputeLayout rl = recompute_layout(d, w.total);
+    const int window = recompute ? rl.window : (d->T > 0 ? d->T : 1);
+    // windows from the last step to the first; [r0, r1) are 0-based step indices (step r turns states[r] into states[r + 1])
+    for (int r1 = d->T; r1 > 0 || (r1 == 0 && d->T == 0); r1 -= window) {
+        const int r0 = r1 - window > 0 ? r1 - window : 0, steps = r1 - r0;
+        const bool first = r1 == d->T, last = r0 == 0;
+        const void* cache = gate_cache;
+        if (recompute && steps > 0) {
+            RecomputeParams rp;
+            rp.Wx = (const char*)Wx + (size_t)r0 * G * io_step; rp.R = R; rp.bias = b;
+            rp.states = (const float*)((const char*)states + (size_t)r0 * st_step);
+            rp.cache = ws + rl.window_off; rp.steps = steps; rp.B = d->B; rp.NH = d->NH; rp.D = d->D;
+            void* args[] = {&rp};
+            const dim3 grid((unsigned)((steps * d->B + 63) / 64), (unsigned)((d->D + 63) / 64), (unsigned)d->NH);
+            if (hipLaunchKernel(table_for(d->cell, d->io_dtype).recompute, grid, dim3(256), args, 0, stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
+            cache = ws + rl.window_off;
+        } else if (!recompute) {
+            cache = gate_cache;
+        }
+        if (pb.exch_bytes && launch_fill_zero(ws + w.exch_off, align_up(pb.exch_bytes), stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
+        KernelParams kp;
+        memset(&kp, 0, sizeof(kp));
+        kp.R = r_in_place ? R : (const void*)(ws + w.rpack_off);
+        kp.states = (float*)((char*)const_cast<void*>(states) + (size_t)r0 * st_step);
+        kp.cache = const_cast<void*>(cache);
+        kp.dH = (const char*)dH + (size_t)r0 * io_step;
+        kp.dWx = (char*)dWx + (size_t)r0 * G * io_step;
+        kp.dgn = ws + w.dgn_off + (size_t)r0 * io_step;
+        // carried state gradients: in from the caller (first launch) or from the window after this one, out to the caller
+        // (last launch) or to the window before this one; the two carry buffers alternate
+        const int flip = ((d->T - r1) / window) & 1;
+        kp.dlast = first ? (const float*)dstates_last : (const float*)(ws + rl.carry_off + (size_t)(flip ^ 1) * align_up((size_t)S * units * 4));
+        kp.dstates0 = last ? (float*)dstates0 : (float*)(ws + rl.carry_off + (size_t)flip * align_up((size_t)S * units * 4));
+        kp.db_accumulate = first ? 0 : 1;
+        kp.clip = d->recurrent_grad_clip > 0.0f ? d->recurrent_grad_clip : d->recurrent_grad_clip < 0.0f ? 0.0f : __builtin_inff();
+        kp.db_part = (float*)(ws + w.dbpart_off);
+        kp.exch = (uint32_t*)(ws + w.exch_off);
+        kp.err = (int*)(ws + w.err_off) + 1;   // the forward call's word stays as it is: flashrnn_check reports both
+        kp.T = steps; kp.B = d->B; kp.NH = d->NH; kp.D = d->D;
+#ifdef FLASHRNN_TRACE
+        if (pb.grid <= kTraceGrid && first) {
+            kp.trace = (unsigned long long*)(ws + w.trace_off + kTraceBytes);
+            if (launch_fill_zero(kp.trace, kTraceBytes, stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
+        }
+#endif
+        rc = launch_persistent(pb, kp, stream);
+        if (rc != FLASHRNN_OK) return rc;
+        if (d->T == 0) break;
+    }
+    (void)rec_step;
+    // db: sum of the per-row partial sums in row order; dR: GEMM over (t, b)
+    const size_t nb = (size_t)d->NH * G * d->D;
+    if (d->T == 0) {
+        if (launch_sum_slices((const float*)(ws + w.dbpart_off), (float*)db, nb, d->B, nb, stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
+        if (launch_fill_zero(dR, (size_t)d->NH * d->D * G * d->D * 4, stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
+        return FLASHRNN_OK;
+    }
+    if (launch_dr_gemm(bf, (const float*)states, dWx, ws + w.dgn_off, (float*)(ws + w.drpart_off), (float*)dR, d->T, d->B, d->NH, d->D,
+                       G, S, d->cell == FLASHRNN_GRU, (const float*)(ws + w.dbpart_off), (float*)db, stream) != hipSuccess)
+        return FLASHRNN_ERR_LAUNCH;
+    return FLASHRNN_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -520,56 +634,23 @@ int flashrnn_fwd_static_scratch(const flashrnn_desc_t* d, const void* Wx, const 
 int flashrnn_bwd(const flashrnn_desc_t* d, const void* R, const void* b, const void* states, const void* gate_cache,
                  const void* dH, const void* dstates_last, void* dWx, void* dR, void* db, void* dstates0, void* workspace,
                  void* hip_stream) {
-    int rc = validate(d);
-    if (rc != FLASHRNN_OK) return rc;
-    (void)b;
-    if (!R || !states || !dR || !db || !dstates0 || (d->T > 0 && (!gate_cache || !dH || !dWx))) return FLASHRNN_ERR_NULL;
-    if (!aligned16(R) || !aligned16(states) || !aligned16(gate_cache) || !aligned16(dH) || !aligned16(dstates_last) ||
-        !aligned16(dWx) || !aligned16(dR) || !aligned16(db) || !aligned16(dstates0))
-        return FLASHRNN_ERR_UNSUPPORTED;
+    return bwd_impl(d, nullptr, R, b, states, gate_cache, dH, dstates_last, dWx, dR, db, dstates0, workspace, hip_stream);
+}
+
+int flashrnn_bwd_recompute(const flashrnn_desc_t* d, const void* Wx, const void* R, const void* b, const void* states, const void* dH,
+                           const void* dstates_last, void* dWx, void* dR, void* db, void* dstates0, void* workspace, void* hip_stream) {
+    if (d && validate(d) == FLASHRNN_OK && d->T > 0 && !Wx) return FLASHRNN_ERR_NULL;
+    static const char kNoInputs = 0;   // T = 0: nothing to recompute; any non-null pointer selects the windowed path
+    return bwd_impl(d, Wx ? Wx : (d && d->T == 0 ? (const void*)&kNoInputs : nullptr), R, b, states, nullptr, dH, dstates_last, dWx, dR, db, dstates0,
+                    workspace, hip_stream);
+}
+
+size_t flashrnn_recompute_workspace_bytes(const flashrnn_desc_t* d) {
+    if (validate(d) != FLASHRNN_OK) return 0;
     Workspace w;
     Plan pf, pb;
-    rc = carve(d, &w, &pf, &pb);
-    if (rc != FLASHRNN_OK) return rc;
-    if (!workspace || ((uintptr_t)workspace & (kAlign - 1))) return FLASHRNN_ERR_WORKSPACE;
-    hipStream_t stream = (hipStream_t)hip_stream;
-    char* ws = (char*)workspace;
-    const int G = num_gates(d->cell), S = num_states(d->cell);
-    const bool bf = d->io_dtype == FLASHRNN_BF16;
-    if (pb.exch_bytes && launch_fill_zero(ws + w.exch_off, align_up(pb.exch_bytes), stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
-    // The backward copy of R is R itself, padded along (gate, unit) to the kernel's contraction length: without padding
-    // and without cross-CU waits (whose error word the packing kernel clears) the kernel reads R where it is.
-    const bool r_in_place = !pb.e->multi && pb.DK == G * d->D;
-    if (!r_in_place && launch_pack_r(bf, true, R, ws + w.rpack_off, d->NH, d->D, G, pb.DK, (int*)(ws + w.err_off) + 1, stream) != hipSuccess)
-        return FLASHRNN_ERR_LAUNCH;
-    KernelParams kp;
-    memset(&kp, 0, sizeof(kp));
-    kp.R = r_in_place ? R : (const void*)(ws + w.rpack_off); kp.states = (float*)const_cast<void*>(states); kp.cache = const_cast<void*>(gate_cache);
-    kp.dH = dH; kp.dlast = (const float*)dstates_last; kp.dWx = dWx; kp.dgn = ws + w.dgn_off;
-    kp.clip = d->recurrent_grad_clip > 0.0f ? d->recurrent_grad_clip : d->recurrent_grad_clip < 0.0f ? 0.0f : __builtin_inff();
-    kp.dstates0 = (float*)dstates0; kp.db_part = (float*)(ws + w.dbpart_off);
-    kp.exch = (uint32_t*)(ws + w.exch_off);
-    kp.err = (int*)(ws + w.err_off) + 1;   // the forward call's word stays as it is: flashrnn_check reports both
-    kp.T = d->T; kp.B = d->B; kp.NH = d->NH; kp.D = d->D;
-#ifdef FLASHRNN_TRACE
-    if (pb.grid <= kTraceGrid) {
-        kp.trace = (unsigned long long*)(ws + w.trace_off + kTraceBytes);
-        if (launch_fill_zero(kp.trace, kTraceBytes, stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
-    }
-#endif
-    rc = launch_persistent(pb, kp, stream);
-    if (rc != FLASHRNN_OK) return rc;
-    // db: sum of the per-row partial sums in row order; dR: GEMM over (t, b)
-    const size_t nb = (size_t)d->NH * G * d->D;
-    if (d->T == 0) {
-        if (launch_sum_slices((const float*)(ws + w.dbpart_off), (float*)db, nb, d->B, nb, stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
-        if (launch_fill_zero(dR, (size_t)d->NH * d->D * G * d->D * 4, stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
-        return FLASHRNN_OK;
-    }
-    if (launch_dr_gemm(bf, (const float*)states, dWx, ws + w.dgn_off, (float*)(ws + w.drpart_off), (float*)dR, d->T, d->B, d->NH, d->D,
-                       G, S, d->cell == FLASHRNN_GRU, (const float*)(ws + w.dbpart_off), (float*)db, stream) != hipSuccess)
-        return FLASHRNN_ERR_LAUNCH;
-    return FLASHRNN_OK;
+    if (carve(d, &w, &pf, &pb) != FLASHRNN_OK) return 0;
+    return recompute_layout(d, w.total).total;
 }
 
 int flashrnn_check(const flashrnn_desc_t* d, const void* workspace, void* hip_stream) {

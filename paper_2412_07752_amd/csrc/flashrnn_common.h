@@ -140,6 +140,7 @@ struct KernelParams {
     int NG;                // groups in total: NH * batch tiles; group id = tile * NH + head
     int GPAR;              // groups processed concurrently; a workgroup set loops over NG / GPAR of them
     int spin_limit;
+    int db_accumulate;     // bwd: add this launch's per-row db sums to what db_part holds (windowed backward pass)
     int spread;            // several workgroups per group: 0 = a group's members share an XCD, 1 = they are spread over all XCDs
     unsigned long long* trace;   // per-phase clock sums [workgroup][16 waves][8 phases] (trace builds only), or null
     float clip;            // bwd: bound of the recurrent gradient term per value (+inf = not clipped, 0 = cut)

@@ -23,6 +23,7 @@ struct KernelEntry {
 struct KernelTable {
     const KernelEntry* entries;
     int count;
+    const void* recompute;   // recompute_records_kernel of this (cell, I/O dtype)
 };
 
 // tables defined in flashrnn_inst_*.hip

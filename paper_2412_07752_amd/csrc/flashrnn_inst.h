@@ -10,6 +10,7 @@
 #include "flashrnn_host.h"
 #include "flashrnn_kernels.h"
 #include "flashrnn_tile_kernels.h"
+#include "flashrnn_recompute.h"
 
 namespace flashrnn {
 
@@ -60,6 +61,10 @@ static const KernelEntry kEntries[] = {
     FRNN_FB(8, 4, 16, 1, 4)
 #endif
 };
+
+inline KernelTable make_table() {
+    return KernelTable{kEntries, (int)(sizeof(kEntries) / sizeof(kEntries[0])), (const void*)&recompute_records_kernel<FRNN_CELL, (FRNN_BF16 != 0)>};
+}
 
 #undef FRNN_F
 #undef FRNN_B

@@ -5,5 +5,5 @@
 #include "flashrnn_inst.h"
 
 namespace flashrnn {
-KernelTable table_gru4_bf16() { return KernelTable{kEntries, (int)(sizeof(kEntries) / sizeof(kEntries[0]))}; }
+KernelTable table_gru4_bf16() { return make_table(); }
 }  // namespace flashrnn

@@ -5,5 +5,5 @@
 #include "flashrnn_inst.h"
 
 namespace flashrnn {
-KernelTable table_gru_f32() { return KernelTable{kEntries, (int)(sizeof(kEntries) / sizeof(kEntries[0]))}; }
+KernelTable table_gru_f32() { return make_table(); }
 }  // namespace flashrnn

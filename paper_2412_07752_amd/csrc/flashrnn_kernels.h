@@ -964,7 +964,16 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
                 for (int s = 0; s < S; ++s)
                     store_io_r<false, PP>(make_rsrc((char*)p.dstates0 + (size_t)n * D * 4), voff_st + eb * 64, s * st_state, ds[eb][s]);
 #pragma unroll
-                for (int g2 = 0; g2 < G; ++g2) store_f32<PP>(p.db_part, (((size_t)bb * NH + n) * G + g2) * D + e0 + 16 * eb, dbacc[eb][g2]);
+                for (int g2 = 0; g2 < G; ++g2) {
+                    const size_t at = (((size_t)bb * NH + n) * G + g2) * D + e0 + 16 * eb;
+                    if (p.db_accumulate) {   // a later window of a windowed backward pass: on top of the windows before it
+                        float prev[PP];
+                        load_f32<PP>(p.db_part, at, prev);
+#pragma unroll
+                        for (int i = 0; i < PP; ++i) dbacc[eb][g2][i] += prev[i];
+                    }
+                    store_f32<PP>(p.db_part, at, dbacc[eb][g2]);
+                }
             }
         }
     }

@@ -648,7 +648,14 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
             float dbv[PP];
 #pragma unroll
             for (int i = 0; i < PP; ++i) dbv[i] = dbs[((size_t)g * D + i) * BT];
-            store_f32<PP>(p.db_part, (((size_t)bb * NH + n) * G + g) * D + e0, dbv);
+            const size_t at = (((size_t)bb * NH + n) * G + g) * D + e0;
+            if (p.db_accumulate) {   // a later window of a windowed backward pass: on top of the windows before it
+                float prev[PP];
+                load_f32<PP>(p.db_part, at, prev);
+#pragma unroll
+                for (int i = 0; i < PP; ++i) dbv[i] += prev[i];
+            }
+            store_f32<PP>(p.db_part, at, dbv);
         }
     }
 }

@@ -14,7 +14,7 @@ from paper_2412_07752_amd.synth import CELL_ELMAN, CELL_GRU, CELL_GRU4, CELL_LST
 pytestmark = pytest.mark.gpu
 CELLS = [CELL_LSTM, CELL_GRU, CELL_SLSTM, CELL_ELMAN, CELL_GRU4]
 PLAN_ENV = ("FLASHRNN_MULTI", "FLASHRNN_BT", "FLASHRNN_NWU", "FLASHRNN_KS", "FLASHRNN_GPAR", "FLASHRNN_SPIN_LIMIT", "FLASHRNN_EBK",
-            "FLASHRNN_KIND")
+            "FLASHRNN_KIND", "FLASHRNN_RECOMPUTE_STEPS")
 
 
 @pytest.fixture(autouse=True)
@@ -293,6 +293,47 @@ def test_seeded_random_shapes():
         gpu = pu.run_gpu(w, inp, dl, clip=clip)
         pu.assert_close(w, pu.compare(w, gpu, ref, scale_ref=free))
         pu.assert_states_elementwise(w, gpu, ref)
+
+
+RECOMPUTE_CASES = [
+    # (dtype, D, B, T, environment): staged tile kernels, generic kernels, a head split over workgroups, f32; windows of 4 steps
+    # (T = 11: a ragged first window), of one step, and the whole sequence in one window
+    ("bf16", 64, 13, 11, {"FLASHRNN_RECOMPUTE_STEPS": "4"}), ("bf16", 192, 6, 9, {"FLASHRNN_RECOMPUTE_STEPS": "1"}),
+    ("bf16", 96, 19, 11, {"FLASHRNN_RECOMPUTE_STEPS": "4", "FLASHRNN_KIND": "0", "FLASHRNN_BT": "16"}), ("bf16", 256, 7, 11, {"FLASHRNN_RECOMPUTE_STEPS": "3"}),
+    ("bf16", 80, 5, 7, {}), ("f32", 48, 9, 10, {"FLASHRNN_RECOMPUTE_STEPS": "4"}), ("f32", 192, 5, 6, {"FLASHRNN_RECOMPUTE_STEPS": "2"}),
+]
+
+
+@pytest.mark.parametrize("cell", CELLS)
+@pytest.mark.parametrize("dtype,D,B,T,env", RECOMPUTE_CASES)
+def test_backward_with_recomputed_values(cell, dtype, D, B, T, env):
+    """flashrnn_bwd_recompute: forward without a gate cache, backward from Wx and the states alone, window by window
+    (carried state gradients, db sums and the GRU's recurrent-side gradients cross the window boundaries)."""
+    os.environ.update(env)
+    w = Workload(f"recompute_{cell}_{dtype}_D{D}", cell, T, B, 2, D, dtype, True, bias="uniform0.1", init="uniform0.1", seed=D + T)
+    print(f"case {w.name} env={env}", flush=True)
+    inp, dl = synth.make_inputs(w), _dlast(w)
+    ref = pu.run_oracle(w, inp, dl)
+    Wx, R, b, dH = (pu.to_device(inp[k], dtype) for k in ("Wx", "R", "b", "dH"))
+    s0, dlast = pu.to_device(inp["states0"], "f32"), pu.to_device(dl, "f32")
+    states, cache, ws = api.flashrnn_fwd(cell, Wx, R, b, s0, save_for_backward=False)
+    assert cache is None
+    dWx, dR, db, ds0, ws2 = api.flashrnn_bwd_recompute(cell, Wx, R, b, states, dH, dlast)
+    desc = api.make_desc(cell, T, B, 2, D, api.FLASHRNN_BF16 if dtype == "bf16" else api.FLASHRNN_F32)
+    api.flashrnn_check(desc, ws2)
+    gpu = {"states": pu.to_host64(states), "dWx": pu.to_host64(dWx), "dR": pu.to_host64(dR), "db": pu.to_host64(db), "dstates0": pu.to_host64(ds0)}
+    pu.assert_close(w, pu.compare(w, gpu, ref))
+
+
+def test_backward_with_recomputed_values_empty_sequence():
+    w = Workload("recompute_T0", CELL_SLSTM, 0, 5, 2, 32, "bf16", True, bias="uniform0.1", init="uniform0.1")
+    inp, dl = synth.make_inputs(w), _dlast(w)
+    ref = pu.run_oracle(w, inp, dl)
+    Wx, R, b, dH = (pu.to_device(inp[k], "bf16") for k in ("Wx", "R", "b", "dH"))
+    states, _, _ = api.flashrnn_fwd(w.cell, Wx, R, b, pu.to_device(inp["states0"], "f32"), save_for_backward=False)
+    dWx, dR, db, ds0, _ = api.flashrnn_bwd_recompute(w.cell, Wx, R, b, states, dH, pu.to_device(dl, "f32"))
+    gpu = {"states": pu.to_host64(states), "dWx": pu.to_host64(dWx), "dR": pu.to_host64(dR), "db": pu.to_host64(db), "dstates0": pu.to_host64(ds0)}
+    pu.assert_close(w, pu.compare(w, gpu, ref))
 
 
 def test_runs_are_bitwise_reproducible():
