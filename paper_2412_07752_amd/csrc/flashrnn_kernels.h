@@ -386,6 +386,17 @@ __device__ __forceinline__ void publish_tile(__amdgpu_buffer_rsrc_t rs, uint32_t
     publish4<BF16>(rs, row_off, k_wave + 4 * lm.quad, v4, stamp, far);
 }
 
+// One k-step of the B operand out of an LDS row.  Only the batch columns c < BT of a tile carry data: the other lanes
+// do not read at all (an LDS read costs bandwidth per active lane), their operand columns are zero and their results unused.
+// (Worth it where a wave reads long rows: with 8 k-steps per wave the step of a D = 256 head got 14 % shorter; with 6 k-steps
+// per wave, and in the staged tile kernels, whose LDS reads hide behind the MFMAs, the extra branch cost more than it saved.)
+template <int BT, bool MASKED> __device__ __forceinline__ bf16x8 lds_operand_col(const char* p, int c) {
+    if constexpr (!MASKED || BT == 16) return *(const bf16x8*)p;
+    bf16x8 v = __builtin_bit_cast(bf16x8, i32x4{0, 0, 0, 0});
+    if (c < BT) v = *(const bf16x8*)p;
+    return v;
+}
+
 // LDS operand row: element type bf16 (as uint16) or float
 template <bool BF16, int KT>
 __device__ __forceinline__ void read_operand_lds(const char* row, int k0, int quad, typename Operand<BF16>::type (&hB)[KT]) {
@@ -621,7 +632,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
                     op_t hB[KC];
 #pragma unroll
                     for (int j = 0; j < KC; ++j) {
-                        if constexpr (BF16) hB[j] = *(const bf16x8*)(hbuf + lds_rd + (size_t)(k0 + (kc + j) * 32 + lm.quad * 8) * 2);
+                        if constexpr (BF16) hB[j] = lds_operand_col<BT, (KT >= 8)>(hbuf + lds_rd + (size_t)(k0 + (kc + j) * 32 + lm.quad * 8) * 2, lm.c);
                         else hB[j] = *(const float*)(hbuf + lds_rd + (size_t)(k0 + lm.quad * KT + kc + j) * 4);
                     }
 #pragma unroll
@@ -916,7 +927,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
                     op_t gB[KC];
 #pragma unroll
                     for (int j = 0; j < KC; ++j) {
-                        if constexpr (BF16) gB[j] = *(const bf16x8*)(gbuf + lds_row + (size_t)(k0 + (kc + j) * 32 + lm.quad * 8) * 2);
+                        if constexpr (BF16) gB[j] = lds_operand_col<BT, (KT >= 8)>(gbuf + lds_row + (size_t)(k0 + (kc + j) * 32 + lm.quad * 8) * 2, lm.c);
                         else gB[j] = *(const float*)(gbuf + lds_row + (size_t)(k0 + lm.quad * KT + kc + j) * 4);
                     }
 #pragma unroll
