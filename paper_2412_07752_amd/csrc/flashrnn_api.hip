@@ -188,7 +188,10 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
             for (int bi = 0; bi < 3 && !pl.e; ++bi) {
                 const int BT = pass == 0 ? bts[bi] : bts[2 - bi];
                 if (force_bt && BT != force_bt) continue;
-                int cap = cus / kXcds - 2;                       // workgroups of one launch per XCD, with a margin
+                // workgroups of one launch per XCD.  All members of a group must be resident at once; these kernels fit two
+                // workgroups on a CU (registers, LDS), so even a launch that asks for every CU of an XCD has a whole XCD of
+                // slack.  The backward pass keeps a margin of two CUs per XCD on top (its plans rarely want more anyway).
+                int cap = bwd ? cus / kXcds - 2 : cus / kXcds;
                 const int NG = d->NH * ((d->B + BT - 1) / BT);
                 const KernelEntry* best = nullptr;
                 for (int spills_ok = 0; spills_ok < 2 && !best; ++spills_ok)   // a kernel that keeps registers in scratch memory only as a last resort
@@ -212,12 +215,19 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
                 // (at least four waves per workgroup where the shape allows: the workgroup polls the group's rows
                 // together, and with fewer threads that takes more rounds - measured on D = 256 and 768)
                 const int nwu_min = 4 / best->KS > 1 ? 4 / best->KS : 1;
-                for (int p2 = 0; p2 < 2 && !chosen; ++p2)
-                    for (int nwu = p2 == 0 ? nwu_min : 1; nwu <= nwu_max; ++nwu) {
+                // Forward: the most workgroups per group that fit (shortest MFMA and point-wise phase; its rows are short to poll).
+                // Backward: the fewest -- its exchanged rows are G times longer, and a workgroup with more threads strips them
+                // in fewer rounds (measured at D = 256: forward 1.27 / 1.36 / 1.74 ms with 8 / 4 / 2 workgroups per group,
+                // backward 2.70 / 2.88 / 2.38 ms).
+                for (int p2 = 0; p2 < 2 && !chosen; ++p2) {
+                    const int lo = p2 == 0 ? nwu_min : 1;
+                    for (int step = 0; step <= nwu_max - lo; ++step) {
+                        const int nwu = bwd && !force_nwu ? nwu_max - step : lo + step;
                         if (units16 % nwu) continue;
                         const int P = units16 / nwu;
                         if (force_nwu ? nwu == force_nwu : P * slots <= cap) { chosen = nwu; break; }
                     }
+                }
                 int gpar = NG;
                 if (!chosen && pass == 0 && !force_bt) continue;      // not all groups at once with this tile: try a larger one
                 if (!chosen) {

@@ -43,7 +43,7 @@ static const KernelEntry kEntries[] = {
     FRNN_FBE(6, 16, 4, 3) FRNN_FBE(6, 8, 4, 3) FRNN_FBE(6, 4, 4, 3)
 #define FRNN_MULTI_SHAPES(BT) \
     FRNN_FB(2, 1, BT, 1, 4) FRNN_FB(4, 1, BT, 1, 4) FRNN_FB(6, 1, BT, 1, 4) FRNN_FB(1, 4, BT, 1, 4) \
-    FRNN_FB(8, 1, BT, 1, 8) FRNN_FB(12, 1, BT, 1, 8) FRNN_FB(16, 1, BT, 1, 4) FRNN_FB(24, 1, BT, 1, 4) \
+    FRNN_FB(8, 1, BT, 1, 8) FRNN_FB(12, 1, BT, 1, 4) FRNN_FB(16, 1, BT, 1, 4) FRNN_FB(24, 1, BT, 1, 4) \
     FRNN_FB(6, 4, BT, 1, 8) FRNN_FB(8, 4, BT, 1, 8)
     // a head split over workgroups, for batch tiles of 16, 8 and 4 rows (small tiles: more groups, less to exchange)
     FRNN_MULTI_SHAPES(16) FRNN_MULTI_SHAPES(8) FRNN_MULTI_SHAPES(4)
