@@ -405,17 +405,31 @@ hipError_t launch_pack_r(bool bf16, bool bwd, const void* R, void* out, int NH, 
     return hipGetLastError();
 }
 
-// The 128 x 256 tile moves fewer bytes per flop but needs a large problem: with few output tiles it would take so many
-// contraction slices to fill the chip that writing and adding the partial results costs more than it saves (measured:
-// slower on C2 and C3, 28 % faster on C5).
-static bool dr_use_wide(bool bf16, int NH, int D, int G) { return bf16 && NH * ((D + 127) / 128) * ((G * D + 255) / 256) >= 64; }
+// Output tile of the bf16 GEMM.  A larger tile moves fewer operand bytes through L2 and LDS per flop (the 128 x 256 tile,
+// with 64 x 64 outputs per wave, spends more time on its LDS operand reads than on its MFMAs; 256 x 256 with 64 x 128 per
+// wave halves them) but needs a large problem: with few output tiles it would take so many contraction slices to fill
+// the chip that writing and adding the partial results costs more than it saves (measured: the 128 x 256 tile is slower
+// than 64 x 128 on 4 heads x 192 and 8 x 128 units, 28 % faster on 8 x 256; 256 x 256 another 28 % faster there).
+// The 256-row tile is taken only where it pads the unit axis no more than the 128-row one.
+enum DrTile { kDrSmall = 0, kDrWide = 1, kDrSquare = 2 };
+static DrTile dr_tile(bool bf16, int NH, int D, int G) {
+    if (!bf16) return kDrSmall;
+    const int n256 = (G * D + 255) / 256;
+    if ((D + 255) / 256 * 2 == (D + 127) / 128 && NH * ((D + 255) / 256) * n256 >= 32) return kDrSquare;
+    if (NH * ((D + 127) / 128) * n256 >= 64) return kDrWide;
+    return kDrSmall;
+}
+static int dr_tiles(DrTile t, int NH, int D, int G) {
+    const int tm = t == kDrSquare ? 256 : t == kDrWide ? 128 : TM, tn = t == kDrSmall ? TN : 256;
+    return NH * ((D + tm - 1) / tm) * ((G * D + tn - 1) / tn);
+}
 
 int dr_split_k(bool bf16, int T, int B, int NH, int D, int G) {
     const int K = T * B;
     int sk = 1;
-    const int tiles = dr_use_wide(bf16, NH, D, G) ? NH * ((D + 127) / 128) * ((G * D + 255) / 256)
-                                                  : NH * ((D + TM - 1) / TM) * ((G * D + TN - 1) / TN);
-    while (tiles * sk < 512 && K / (sk * 2) >= 4 * TK && sk < 64) sk *= 2;
+    const DrTile t = dr_tile(bf16, NH, D, G);
+    const int tiles = dr_tiles(t, NH, D, G), want = t == kDrSquare ? 256 : 512;   // (the square tile's workgroups fill a CU each)
+    while (tiles * sk < want && K / (sk * 2) >= 4 * TK && sk < 64) sk *= 2;
     return sk;
 }
 
@@ -424,14 +438,16 @@ hipError_t launch_dr_gemm(bool bf16, const float* states, const void* dWx, const
     const int SK = dr_split_k(bf16, T, B, NH, D, G);
     const int GD = G * D;
     float* target = SK == 1 ? dR : part;
-    if (dr_use_wide(bf16, NH, D, G)) {
-        const int grid = (NH * SK + 7) / 8 * 8 * ((D + 127) / 128) * ((GD + 255) / 256);   // (head, K slice) padded to the 8 XCDs
+    const DrTile t = dr_tile(bf16, NH, D, G);
+    const int grid = (NH * SK + 7) / 8 * 8 * (dr_tiles(t, NH, D, G) / NH);   // (head, K slice) padded to the 8 XCDs
+    if (t == kDrSquare)
+        hipLaunchKernelGGL((dr_gemm_tr_kernel<4, 8, 4, 2>), dim3(grid), dim3(512), 0, stream, states, dWx, dgn, target, T, B, NH, D, G, S, SK, gru ? 1 : 0);
+    else if (t == kDrWide)
         hipLaunchKernelGGL((dr_gemm_tr_kernel<4, 4, 2, 4>), dim3(grid), dim3(512), 0, stream, states, dWx, dgn, target, T, B, NH, D, G, S, SK, gru ? 1 : 0);
-    } else {
-        const int grid = (NH * SK + 7) / 8 * 8 * ((D + TM - 1) / TM) * ((GD + TN - 1) / TN);
-        if (bf16) hipLaunchKernelGGL((dr_gemm_tr_kernel<2, 4, 2, 2>), dim3(grid), dim3(256), 0, stream, states, dWx, dgn, target, T, B, NH, D, G, S, SK, gru ? 1 : 0);
-        else hipLaunchKernelGGL(dr_gemm_kernel<false>, dim3(grid), dim3(256), 0, stream, states, dWx, dgn, target, T, B, NH, D, G, S, SK, gru ? 1 : 0);
-    }
+    else if (bf16)
+        hipLaunchKernelGGL((dr_gemm_tr_kernel<2, 4, 2, 2>), dim3(grid), dim3(256), 0, stream, states, dWx, dgn, target, T, B, NH, D, G, S, SK, gru ? 1 : 0);
+    else
+        hipLaunchKernelGGL(dr_gemm_kernel<false>, dim3(grid), dim3(256), 0, stream, states, dWx, dgn, target, T, B, NH, D, G, S, SK, gru ? 1 : 0);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     // split-K partial sums of dR (if any) and the per-row partial sums of db, each added in index order
