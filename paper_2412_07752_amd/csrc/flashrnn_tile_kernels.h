@@ -103,6 +103,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
     const uint32_t voff_c = (row_valid && p.cache != nullptr) ? ((uint32_t)bb * HD + e0) * REC : kDrop;
     const uint32_t lds_row = (uint32_t)lm.bslot * L.hp;
 
+    constexpr bool kLongChain = KT >= 6;   // (see below: how far ahead the inputs are fetched)
     // ---- initial states: slot 0 is written directly (once)
     float st[S][PP];
 #pragma unroll
@@ -124,7 +125,6 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
     __syncthreads();
     // With a short chain a step is shorter than the HBM latency under load: the inputs are fetched two steps ahead
     // there (two register sets in flight), one step ahead with a long chain.
-    constexpr bool kLongChain = KT >= 6;
     i32x4 preA[NCH_IN], preB[NCH_IN];   // short chain: step t fetches into the set t & 1 and parks the other one
     if constexpr (!kLongChain) {
 #pragma unroll
@@ -142,15 +142,24 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
 #pragma unroll
         for (int k2 = 0; k2 < NCH_ST; ++k2) vs[k2] = *(const i32x4*)(img + cst_l[k2]);
     };
+    // The three streams of a step advance by whole time steps: their bases are carried as pointers (a product of the
+    // step index and a 64-bit stride per stream and step is a dozen scalar instructions).
+    const char* wx_ptr = wx_g + (size_t)((kLongChain ? 1 : 2) < T ? (kLongChain ? 1 : 2) : (T > 0 ? T - 1 : 0)) * wx_step;   // Wx of the step fetched next
+    char* st_ptr = st_g;   // state slot of the step before the current one (slot 0 is written directly, not through the image)
+    char* c_ptr = c_g;     // saved values of the current step
     auto copy_out_store = [&](int j, const i32x4 (&vs)[NCH_ST]) {
         const uint32_t none = j < 1 ? kDrop : 0u;
-        const rsrc_t rs_st = make_rsrc(st_g + (size_t)(j < 1 ? 0 : j) * st_step);
+        const rsrc_t rs_st = make_rsrc(st_ptr);
 #pragma unroll
         for (int k2 = 0; k2 < NCH_ST; ++k2) __builtin_amdgcn_raw_buffer_store_b128(vs[k2], rs_st, cst_g[k2] | none, 0, 0);
     };
+    // (trace builds: clocks per wave between 0 the barrier and the top of a step | 2 the top and the issue of the chain's
+    // last MFMA | 3 that and the barrier: compaction, point-wise function, LDS writes)
+    FRNN_TRACE_BEGIN();
     // one time step; PAR = t & 1 as a compile-time constant where it selects a register set
     auto step = [&](auto par_c, const int t) {
         constexpr int PAR = decltype(par_c)::value;
+        FRNN_TRACE_MARK(0);
         // The MFMA chain of the step, k-step by k-step, and the work off the dependency chain: this step's inputs out of
         // their image, the state rows of the previous step on their way to HBM, the next step's inputs into their image
         // (the sched barriers keep the compiler from bunching it all up in front).  With a long chain (KT >= 6) that
@@ -175,8 +184,9 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
         };
         if constexpr (!kLongChain) side_reads();
         {
-            const int ahead = kLongChain ? t : t + 1;   // slot of Wx_{t+1} / Wx_{t+2}
-            const rsrc_t rsn = make_rsrc(wx_g + (size_t)(ahead < T ? ahead : T - 1) * wx_step);
+            const int ahead = kLongChain ? t : t + 1;   // slot of Wx_{t+1} / Wx_{t+2} (the last steps fetch the last slot again)
+            const rsrc_t rsn = make_rsrc(wx_ptr);
+            wx_ptr += ahead < T - 1 ? wx_step : 0;
             if constexpr (kLongChain) {
 #pragma unroll
                 for (int k2 = 0; k2 < NCH_IN; ++k2) pre[k2] = __builtin_amdgcn_raw_buffer_load_b128(rsn, cin_g[k2], 0, 0);
@@ -220,11 +230,14 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
         for (int kt = 3; kt < KT; ++kt)
 #pragma unroll
             for (int g = 0; g < G; ++g) acc[g] = OP::mfma(Rf[g][kt], hB[kt], acc[g]);
+        FRNN_TRACE_MARK(2);
         // ---- point-wise function; the step's outputs go to their image (they leave for HBM during the next step)
 #pragma unroll
         for (int g = 0; g < G; ++g) compact_tile<BT>(acc[g]);
         char* oimg = out_img + (t & 1) * OUT_PITCH;
-        const rsrc_t rs_c = make_rsrc(c_g + (size_t)(t - 1) * c_step);
+        const rsrc_t rs_c = make_rsrc(c_ptr);
+        c_ptr += c_step;
+        st_ptr += st_step;
 #pragma unroll
         for (int i = 0; i < PP; ++i) {
             float wxi[G], ybi[G], sti[S], cvi[NC];
@@ -248,6 +261,10 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
                 else *(i32x4*)(im + cin_l[k2]) = preB[k2];
             }
         }
+#ifdef FLASHRNN_TRACE
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#endif
+        FRNN_TRACE_MARK(3);
         __syncthreads();
     };
     using par0 = std::integral_constant<int, 0>;
@@ -268,6 +285,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
         copy_out_load(T, vs);
         copy_out_store(T, vs);
     }
+    FRNN_TRACE_END(p);
 }
 
 // =============================================================================================
@@ -400,10 +418,19 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
     for (uint32_t j = tid; j < 2 * BUF / 4; j += NT) ((uint32_t*)gbuf)[j] = 0u;
 
     // the image of the inputs of step j: global -> LDS (each wave's 64 chunks back to back), LDS -> this lane's values
+    // (the steps are fetched in the order T, T-1, ..., 1: the three streams' bases are carried as pointers, and so are
+    // those of the outputs -- a product of the step index and a 64-bit stride per stream and step is a dozen scalar
+    // instructions)
+    const ptrdiff_t back = T > 0 ? T - 1 : 0;
+    const char* fc_ptr = c_g + back * (ptrdiff_t)c_step;
+    const char* fst_ptr = st_g + back * (ptrdiff_t)st_step;
+    const char* fdh_ptr = dh_g + back * (ptrdiff_t)dh_step;
+    char* dwx_ptr = dwx_g + back * (ptrdiff_t)wx_step;
+    char* dgn_ptr = dgn_g + back * (ptrdiff_t)dh_step;
     auto fetch = [&](int j) {
-        j = __builtin_amdgcn_readfirstlane(j);   // keeps the clamped time index (a saturating subtract) on the scalar unit
-        const rsrc_t rc = make_rsrc(c_g + (size_t)(j - 1) * c_step), rst = make_rsrc(st_g + (size_t)(j - 1) * st_step),
-                     rdh = make_rsrc(dh_g + (size_t)(j - 1) * dh_step);
+        j = __builtin_amdgcn_readfirstlane(j);
+        const rsrc_t rc = make_rsrc(fc_ptr), rst = make_rsrc(fst_ptr), rdh = make_rsrc(fdh_ptr);
+        fc_ptr -= c_step; fst_ptr -= st_step; fdh_ptr -= dh_step;
         char* img = in_img + (j & 1) * L.in_pitch + (uint32_t)w * 1024;
 #pragma unroll
         for (int k2 = 0; k2 < NCC; ++k2)
@@ -592,9 +619,12 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
                 if (out_real) o = *(const i32x4*)(out_img + (t & 1) * L.out_pitch + cout_l);
                 if (t > 1) { take(t - 1); precompute(); }
                 pin_order();
-                __builtin_amdgcn_raw_buffer_store_b128(o, make_rsrc(dwx_g + (size_t)(t - 1) * wx_step), cout_g, 0, 0);
-                if constexpr (CELL == CELL_GRU)
-                    __builtin_amdgcn_raw_buffer_store_b128(o, make_rsrc(dgn_g + (size_t)(t - 1) * dh_step), cout_n, 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b128(o, make_rsrc(dwx_ptr), cout_g, 0, 0);
+                dwx_ptr -= wx_step;
+                if constexpr (CELL == CELL_GRU) {
+                    __builtin_amdgcn_raw_buffer_store_b128(o, make_rsrc(dgn_ptr), cout_n, 0, 0);
+                    dgn_ptr -= dh_step;
+                }
             }
             pin_order();
         }
