@@ -25,8 +25,12 @@ __device__ __forceinline__ void pin_order() { __builtin_amdgcn_sched_barrier(0);
 // =============================================================================================
 // LDS: [2] operand rows | [2] input image (BT*G bf16 rows) | [2] output image (BT*S f32 rows, then
 // BT*D saved-values records); sizes from tile_lds().
-template <int CELL, int KT, int BT, int MAXW>
-__global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams p) {
+// EXACT: the head has exactly KT * 32 units (the usual case: 32, 64, 128, 192).  Every LDS pitch and image size is then a
+// compile-time constant, and with the step's parity a compile-time constant as well (the time loop is unrolled by two) the
+// LDS addresses of a step are a lane-constant register plus an immediate offset: a dozen vector adds per wave and step
+// less in a loop that is bound by the issue of vector instructions.
+template <int CELL, int KT, int BT, int MAXW, bool EXACT>
+__device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
     using CT = CellTraits<CELL>;
     using OP = Operand<true>;
     constexpr int G = CT::G, S = CT::S, NC = CT::NC;
@@ -41,10 +45,11 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
     extern __shared__ __align__(16) char smem[];
     const int gid = blockIdx.x;
     if (gid >= p.NG) return;
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, tid = threadIdx.x, NT = blockDim.x;
+    const int D = EXACT ? DK : p.D;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, tid = threadIdx.x, NT = 4 * D;   // one wave per block of 16 units
     stagger_waves(w);
     const LaneMap<BT> lm(lane);
-    const int T = p.T, B = p.B, NH = p.NH, D = p.D;
+    const int T = p.T, B = p.B, NH = p.NH;
     const int n = gid % NH, q = gid / NH;
     const int e_wave = w * 16, e0 = e_wave + lm.uoff;
 
@@ -137,8 +142,8 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
     }
 
     // move the image of the states after step j to HBM (slot j)
-    auto copy_out_load = [&](int j, i32x4 (&vs)[NCH_ST]) {
-        const char* img = out_img + (j & 1) * OUT_PITCH;
+    auto copy_out_load = [&](int parity, i32x4 (&vs)[NCH_ST]) {
+        const char* img = out_img + parity * OUT_PITCH;
 #pragma unroll
         for (int k2 = 0; k2 < NCH_ST; ++k2) vs[k2] = *(const i32x4*)(img + cst_l[k2]);
     };
@@ -159,6 +164,10 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
     // one time step; PAR = t & 1 as a compile-time constant where it selects a register set
     auto step = [&](auto par_c, const int t) {
         constexpr int PAR = decltype(par_c)::value;
+        // parity of the step: a compile-time constant where the loop is unrolled by two (always with a short chain, where it
+        // selects a register set; with a long chain only for EXACT heads: with run-time pitches the two sets of addresses
+        // would not fit the registers)
+        const int par = (EXACT || !kLongChain) ? PAR : (t & 1);
         FRNN_TRACE_MARK(0);
         // The MFMA chain of the step, k-step by k-step, and the work off the dependency chain: this step's inputs out of
         // their image, the state rows of the previous step on their way to HBM, the next step's inputs into their image
@@ -166,16 +175,16 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
         // work sits between the k-steps; with a short one all LDS reads go out together at the top of the step (one
         // latency) and the next inputs are parked at its end, where they have had time to arrive (measured both ways).
         bf16x8 hB[KT];
-        const char* hrow = hbuf + ((t - 1) & 1) * BUF + lds_row;
+        const char* hrow = hbuf + (par ^ 1) * BUF + lds_row;
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt) hB[kt] = *(const bf16x8*)(hrow + (size_t)(kt * 32 + lm.quad * 8) * 2);
         i32x4 pre[NCH_IN], vs[NCH_ST];
         float wx[G][PP];
         auto side_reads = [&]() {
-            const char* im = in_img + (t & 1) * L.in_pitch + l_in;
+            const char* im = in_img + par * L.in_pitch + l_in;
 #pragma unroll
             for (int g = 0; g < G; ++g) load_io<true, PP>(im + (uint32_t)g * L.rp_io, 0, wx[g]);
-            copy_out_load(t - 1, vs);
+            copy_out_load(par ^ 1, vs);
 #pragma unroll
             for (int g = 0; g < G; ++g)     // the bias joins the inputs here, off the step's tail (GRU's candidate bias
 #pragma unroll                      // belongs to the recurrent term that sig(r) multiplies: it stays with y)
@@ -221,7 +230,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
             pin_order();
             copy_out_store(t - 1, vs);
             pin_order();
-            char* im = in_img + ((t + 1) & 1) * L.in_pitch;
+            char* im = in_img + (par ^ 1) * L.in_pitch;
 #pragma unroll
             for (int k2 = 0; k2 < NCH_IN; ++k2) *(i32x4*)(im + cin_l[k2]) = pre[k2];
         }
@@ -234,7 +243,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
         // ---- point-wise function; the step's outputs go to their image (they leave for HBM during the next step)
 #pragma unroll
         for (int g = 0; g < G; ++g) compact_tile<BT>(acc[g]);
-        char* oimg = out_img + (t & 1) * OUT_PITCH;
+        char* oimg = out_img + par * OUT_PITCH;
         const rsrc_t rs_c = make_rsrc(c_ptr);
         c_ptr += c_step;
         st_ptr += st_step;
@@ -250,11 +259,11 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
             for (int s = 0; s < S; ++s) st[s][i] = sti[s];
             store_record<true, CT::RS, NC>(rs_c, voff_c + i * REC, 0, cvi);
         }
-        write_operand_lds<true, PP>(hbuf + (t & 1) * BUF + lds_row, e0, st[0]);
+        write_operand_lds<true, PP>(hbuf + par * BUF + lds_row, e0, st[0]);
 #pragma unroll
         for (int s = 0; s < S; ++s) store_io<false, PP>(oimg + l_st + (uint32_t)s * BT * L.rp_st, 0, st[s]);
         if constexpr (!kLongChain) {   // park Wx_{t+1} (fetched during the previous step); Wx_{t+2} stays in flight
-            char* im = in_img + ((t + 1) & 1) * L.in_pitch;
+            char* im = in_img + (par ^ 1) * L.in_pitch;
 #pragma unroll
             for (int k2 = 0; k2 < NCH_IN; ++k2) {
                 if constexpr (PAR == 1) *(i32x4*)(im + cin_l[k2]) = preA[k2];
@@ -269,7 +278,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
     };
     using par0 = std::integral_constant<int, 0>;
     using par1 = std::integral_constant<int, 1>;
-    if constexpr (kLongChain) {
+    if constexpr (kLongChain && !EXACT) {
         for (int t = 1; t <= T; ++t) step(par0{}, t);
     } else {
         int t = 1;
@@ -282,10 +291,16 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
     // ---- drain: outputs of step T
     if (T > 0) {
         i32x4 vs[NCH_ST];
-        copy_out_load(T, vs);
+        copy_out_load(T & 1, vs);
         copy_out_store(T, vs);
     }
     FRNN_TRACE_END(p);
+}
+
+template <int CELL, int KT, int BT, int MAXW>
+__global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams p) {
+    if (p.D == KT * 32) fwd_tile_body<CELL, KT, BT, MAXW, true>(p);
+    else fwd_tile_body<CELL, KT, BT, MAXW, false>(p);
 }
 
 // =============================================================================================
