@@ -102,7 +102,9 @@ class Runner:
             self.step()
         torch.cuda.synchronize()
         api.flashrnn_check(self.desc, self.ws)      # a cross-CU wait that gave up would make the numbers meaningless
-        api.flashrnn_profile_enable(True)           # HIP events on the persistent kernels' own dispatches
+        # HIP events on the persistent kernels' own dispatches, on about 25 calls spread over the timed region (a dispatch
+        # that carries events starts ~5 us late: on every call that would be 1.7 % of the headline step)
+        api.flashrnn_profile_enable(max(1, steps // 25))
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(steps):

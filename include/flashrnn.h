@@ -185,9 +185,11 @@ int flashrnn_plan_kernel(const flashrnn_desc_t* desc, int backward, int* staged,
 
 /*
  * Measurement aid (the only state the library keeps; meant for benchmarks, not thread-hot paths).
- * While enabled, every flashrnn_fwd / flashrnn_bwd call attaches a start and a stop HIP event to the dispatch of
- * its persistent time-loop kernel on the call's stream (up to 256 calls per direction; later calls are not
- * recorded).  flashrnn_profile_enable(on) also resets the record.
+ * flashrnn_profile_enable(n), n > 0: every n-th flashrnn_fwd / flashrnn_bwd call (the first one included) attaches a
+ * start and a stop HIP event to the dispatch of its persistent time-loop kernel on the call's stream (up to 256 calls
+ * per direction; later calls are not recorded); n <= 0 switches it off.  A dispatch that carries events starts a few
+ * microseconds later than one that does not (measured: 5 us per dispatch), hence the stride.  The call also resets
+ * the record.
  * flashrnn_profile_kernel_ms waits for the recorded events and returns the mean duration in
  * milliseconds of the forward (backward = 0) or backward (backward = 1) persistent kernel and the
  * number of launches recorded.

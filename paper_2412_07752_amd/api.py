@@ -133,7 +133,8 @@ def flashrnn_plan_kernel(desc, backward=False):
 
 
 def flashrnn_profile_enable(on):
-    rc = lib().flashrnn_profile_enable(int(bool(on)))
+    """on: False / 0 = off, True / 1 = every call, n = every n-th call of each direction carries the two events."""
+    rc = lib().flashrnn_profile_enable(int(on))
     if rc != FLASHRNN_OK:
         raise FlashRNNError(rc, "flashrnn_profile_enable")
 

@@ -372,7 +372,8 @@ int prepare_kernel(const Plan& pl) {
 // optional bracketing of the persistent kernels with HIP events (flashrnn_profile_*)
 constexpr int kProfSlots = 256;
 struct Profile {
-    bool on = false;
+    int stride = 0;            // 0 = off; n = every n-th call per direction carries events
+    int seen[2] = {0, 0};
     int count[2] = {0, 0};
     hipEvent_t ev[2][kProfSlots][2] = {};
 };
@@ -385,7 +386,7 @@ int launch_persistent(const Plan& pl, KernelParams& kp, hipStream_t stream) {
     {
         std::lock_guard<std::mutex> lock(g_prof_mu);
         const int dir = pl.e->bwd;
-        if (g_prof.on && g_prof.count[dir] < kProfSlots) {
+        if (g_prof.stride > 0 && g_prof.seen[dir]++ % g_prof.stride == 0 && g_prof.count[dir] < kProfSlots) {
             const int i = g_prof.count[dir]++;
             for (int j = 0; j < 2; ++j)
                 if (!g_prof.ev[dir][i][j] && hipEventCreate(&g_prof.ev[dir][i][j]) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
@@ -452,11 +453,13 @@ int fwd_impl(const flashrnn_desc_t* d, const void* Wx, const void* R, const void
     // the exchange words start from zero stamps (a fill kernel, not a memset: the call may be captured into a graph);
     // both error words are cleared by the packing kernel
     if (pf.exch_bytes && launch_fill_zero(ws + w.exch_off, align_up(pf.exch_bytes), stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
-    if (launch_pack_r(d->io_dtype == FLASHRNN_BF16, false, R, ws + w.rpack_off, d->NH, d->D, G, pf.DK, (int*)(ws + w.err_off), stream) != hipSuccess)
+    // (the staged forward kernels read R as it is and clear the error words themselves)
+    const bool r_in_place = pf.e->tile != 0;
+    if (!r_in_place && launch_pack_r(d->io_dtype == FLASHRNN_BF16, false, R, ws + w.rpack_off, d->NH, d->D, G, pf.DK, (int*)(ws + w.err_off), stream) != hipSuccess)
         return FLASHRNN_ERR_LAUNCH;
     KernelParams kp;
     memset(&kp, 0, sizeof(kp));
-    kp.Wx = Wx; kp.R = ws + w.rpack_off; kp.bias = b; kp.states0 = (const float*)states0; kp.states = (float*)states;
+    kp.Wx = Wx; kp.R = r_in_place ? R : (const void*)(ws + w.rpack_off); kp.bias = b; kp.states0 = (const float*)states0; kp.states = (float*)states;
     kp.cache = gate_cache;
     kp.exch = (uint32_t*)(ws + w.exch_off);
     kp.err = (int*)(ws + w.err_off);
@@ -718,7 +721,8 @@ int flashrnn_trace_phases(const flashrnn_desc_t* d, const void* workspace, int b
 
 int flashrnn_profile_enable(int on) {
     std::lock_guard<std::mutex> lock(g_prof_mu);
-    g_prof.on = on != 0;
+    g_prof.stride = on > 0 ? on : 0;
+    g_prof.seen[0] = g_prof.seen[1] = 0;
     g_prof.count[0] = g_prof.count[1] = 0;
     return FLASHRNN_OK;
 }

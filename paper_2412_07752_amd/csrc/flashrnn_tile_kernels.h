@@ -63,15 +63,48 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
     char* in_img = smem + 2 * BUF;
     char* out_img = in_img + 2 * L.in_pitch;
 
-    // ---- R fragments and bias: resident for all T steps
+    // ---- R fragments and bias: resident for all T steps.  p.R is the caller's R[n][k][g][e] (no packed copy: a packing
+    // kernel in front of this one costs its own run time plus a launch gap, together a few percent of a short sequence).
+    // The MFMA A operand of lane (c, quad) is R[k = kt*32 + quad*8 .. +7][g][e_wave + c]: eight values a row pitch apart in
+    // memory.  Each wave moves its [32 k] x [16 units] tile of a (gate, k-step) pair to LDS as it lies (two 16-byte
+    // pieces per row) and reads it back with the transposing LDS load, which hands every lane four consecutive rows of
+    // its column.  The error words of the call are cleared here as well (the kernels of this file never wait on another
+    // workgroup, they never set them).
     bf16x8 Rf[G][KT];
     float bias[G][PP];
+    if (gid == 0 && tid == 0) { p.err[0] = 0; p.err[1] = 0; }
+    {
+        typedef short s16x4 __attribute__((ext_vector_type(4)));
+        typedef short s16x8 __attribute__((ext_vector_type(8)));
+        typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+        char* tile = smem + (uint32_t)w * 1024;                       // this wave's [32][16] bf16 tile
+        const int row = lane >> 1, half = lane & 1;
+        const char* src = (const char*)p.R + ((((size_t)n * D + row) * G) * D + e_wave + half * 8) * ESZ;
+        const uint32_t wr = (uint32_t)row * 32 + half * 16;
+        const uint32_t rd = (uint32_t)(lm.quad * 8 + (lm.c >> 2)) * 32 + (lm.c & 3) * 8;
+        i32x4 raw[G][KT];   // all loads in flight at once; a fragment takes the registers of the rows it was made from
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-        const size_t rrow = (((size_t)n * G + g) * D + e_wave + lm.c) * DK;
+        for (int g = 0; g < G; ++g)
 #pragma unroll
-        for (int kt = 0; kt < KT; ++kt) Rf[g][kt] = *(const bf16x8*)((const uint16_t*)p.R + rrow + kt * 32 + lm.quad * 8);
-        load_io<true, PP>(p.bias, ((size_t)n * G + g) * D + e0, bias[g]);
+            for (int kt = 0; kt < KT; ++kt) {
+                raw[g][kt] = i32x4{0, 0, 0, 0};
+                if (kt * 32 + row < D) raw[g][kt] = *(const i32x4*)(src + ((size_t)kt * 32 * G + g) * D * ESZ);
+            }
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt) {
+                // (a wave's LDS operations run in the order it issues them and the tile is its own: no barrier, only the compiler is held)
+                asm volatile("" ::: "memory");
+                *(i32x4*)(tile + wr) = raw[g][kt];
+                asm volatile("" ::: "memory");
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + rd));
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + rd + 4 * 32));
+                Rf[g][kt] = __builtin_bit_cast(bf16x8, s16x8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]});
+            }
+            load_io<true, PP>(p.bias, ((size_t)n * G + g) * D + e0, bias[g]);
+        }
+        __syncthreads();   // the tiles lie where the operand rows and images are set up next
     }
 
     const int bb_raw = q * BT + lm.bslot;
