@@ -15,17 +15,20 @@
 namespace flashrnn {
 
 #define FRNN_F(KT, KS, BT, MULTI, MAXW, EB) \
-    {FRNN_CELL, FRNN_BF16, 0, KT, KS, BT, MULTI, MAXW, EB, 0, (const void*)&fwd_kernel<FRNN_CELL, (FRNN_BF16 != 0), KT, KS, BT, (MULTI != 0), MAXW, EB>},
+    {FRNN_CELL, FRNN_BF16, 0, KT, KS, BT, MULTI, MAXW, EB, 0, 0, (const void*)&fwd_kernel<FRNN_CELL, (FRNN_BF16 != 0), KT, KS, BT, (MULTI != 0), MAXW, EB>},
 #define FRNN_B(KT, KS, BT, MULTI, MAXW, EB) \
-    {FRNN_CELL, FRNN_BF16, 1, (KT) * FRNN_G, KS, BT, MULTI, MAXW, EB, 0, (const void*)&bwd_kernel<FRNN_CELL, (FRNN_BF16 != 0), (KT) * FRNN_G, KS, BT, (MULTI != 0), MAXW, EB>},
+    {FRNN_CELL, FRNN_BF16, 1, (KT) * FRNN_G, KS, BT, MULTI, MAXW, EB, 0, 0, (const void*)&bwd_kernel<FRNN_CELL, (FRNN_BF16 != 0), (KT) * FRNN_G, KS, BT, (MULTI != 0), MAXW, EB>},
 // forward and backward share the shape list: the backward contraction axis is G times longer
 #define FRNN_FB(KT, KS, BT, MULTI, MAXW) FRNN_F(KT, KS, BT, MULTI, MAXW, 1) FRNN_B(KT, KS, BT, MULTI, MAXW, 1)
 // small batch tiles (bf16, one workgroup per group): forward from the dedicated tile kernel
 #define FRNN_FT(KT, BT, MAXW) \
-    {FRNN_CELL, FRNN_BF16, 0, KT, 1, BT, 0, MAXW, 1, 1, (const void*)&fwd_tile_kernel<FRNN_CELL, KT, BT, MAXW>},
-// ... backward with the contraction split over EBK waves per set of EBK unit blocks
+    {FRNN_CELL, FRNN_BF16, 0, KT, 1, BT, 0, MAXW, 1, 1, 0, (const void*)&fwd_tile_kernel<FRNN_CELL, KT, BT, MAXW>},
+// ... backward with the contraction split over EBK waves per set of EBK unit blocks; one kernel for heads of exactly
+// KT * 32 units (compile-time LDS layout) and one for the sizes below (two kernels, not two paths in one: the backward
+// kernel sits at the register limit of its launch bound, and a spill in either path would disqualify both)
 #define FRNN_BTL(KT, EBK, BT, MAXW) \
-    {FRNN_CELL, FRNN_BF16, 1, (KT) * FRNN_G, 1, BT, 0, MAXW, EBK, 1, (const void*)&bwd_tile_kernel<FRNN_CELL, (KT) * FRNN_G / (EBK), EBK, BT, MAXW>},
+    {FRNN_CELL, FRNN_BF16, 1, (KT) * FRNN_G, 1, BT, 0, MAXW, EBK, 1, 1, (const void*)&bwd_tile_kernel<FRNN_CELL, (KT) * FRNN_G / (EBK), EBK, BT, MAXW, true>}, \
+    {FRNN_CELL, FRNN_BF16, 1, (KT) * FRNN_G, 1, BT, 0, MAXW, EBK, 1, 0, (const void*)&bwd_tile_kernel<FRNN_CELL, (KT) * FRNN_G / (EBK), EBK, BT, MAXW, false>},
 #define FRNN_TILE(KT, EBK, BT, MAXW) FRNN_FT(KT, BT, MAXW) FRNN_B(KT, 1, BT, 0, MAXW, 1) FRNN_BTL(KT, EBK, BT, MAXW)
 // the largest heads: one block of 16 units per workgroup, 4 contraction slices, one wave per SIMD
 #define FRNN_FL(KT, BT) FRNN_F(KT, 4, BT, 1, 4, 1)

@@ -350,7 +350,9 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
 // fetched while step t's MFMAs run, by loads that write their image in LDS directly (no registers are
 // held across the HBM latency), and are read into registers during step t-1's MFMAs; dWx_t leaves
 // during step t's MFMAs.
-template <int CELL, int KTW, int EBK, int BT, int MAXW>
+// EXACT: as in the forward kernel (the head has exactly KTW * EBK * 32 / G units: compile-time LDS pitches, and a
+// compile-time step parity with the time loop unrolled by two).
+template <int CELL, int KTW, int EBK, int BT, int MAXW, bool EXACT>
 __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams p) {
     using CT = CellTraits<CELL>;
     using OP = Operand<true>;
@@ -373,7 +375,8 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
     const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), tid = threadIdx.x;
     const int tg = w / EBK, ks = w % EBK;
     const LaneMap<BT> lm(lane);
-    const int T = p.T, B = p.B, NH = p.NH, D = p.D;
+    const int D = EXACT ? DK / G : p.D;
+    const int T = p.T, B = p.B, NH = p.NH;
     const int NT = 4 * D;
     const int n = gid % NH, q = gid / NH;
     const int e0 = w * 16 + lm.uoff;                 // this lane's units in the point-wise phase: block w
@@ -475,11 +478,10 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
     const char* fdh_ptr = dh_g + back * (ptrdiff_t)dh_step;
     char* dwx_ptr = dwx_g + back * (ptrdiff_t)wx_step;
     char* dgn_ptr = dgn_g + back * (ptrdiff_t)dh_step;
-    auto fetch = [&](int j) {
-        j = __builtin_amdgcn_readfirstlane(j);
+    auto fetch = [&](const int parity) {
         const rsrc_t rc = make_rsrc(fc_ptr), rst = make_rsrc(fst_ptr), rdh = make_rsrc(fdh_ptr);
         fc_ptr -= c_step; fst_ptr -= st_step; fdh_ptr -= dh_step;
-        char* img = in_img + (j & 1) * L.in_pitch + (uint32_t)w * 1024;
+        char* img = in_img + parity * L.in_pitch + (uint32_t)w * 1024;
 #pragma unroll
         for (int k2 = 0; k2 < NCC; ++k2)
             if (c_wave[k2]) load_chunk_to_lds(rc, img + (uint32_t)k2 * NT * 16, cc_g[k2]);
@@ -487,8 +489,8 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
         if (dh_wave) load_chunk_to_lds(rdh, img + L.dh_off, cdh_g);
     };
     float cv[NC][PP], sc[S][PP], sp[S][PP], dh_ext[PP];
-    auto take = [&](int j) {
-        const char* img = in_img + (j & 1) * L.in_pitch;
+    auto take = [&](const int parity) {
+        const char* img = in_img + parity * L.in_pitch;
 #pragma unroll
         for (int i = 0; i < PP; ++i) {
             float rec[NC];
@@ -550,19 +552,22 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
             for (int i = 0; i < PP; ++i) sc[s][i] = 1.0f;
     }
     if (T > 0) {
-        fetch(T);
-        if (T > 1) fetch(T - 1);
+        fetch(T & 1);
+        if (T > 1) fetch((T - 1) & 1);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
     __syncthreads();
-    if (T > 0) { take(T); precompute(); }
+    if (T > 0) { take(T & 1); precompute(); }
 
     float dbv[G][PP];   // the db sums, read back ahead of each point-wise phase
 #pragma unroll
     for (int g = 0; g < G; ++g)
 #pragma unroll
         for (int i = 0; i < PP; ++i) dbv[g][i] = 0.0f;
-    for (int t = T; t >= 1; --t) {
+    // one time step; PAR = t & 1 as a compile-time constant where the loop is unrolled by two
+    constexpr bool kUnroll = true;
+    auto step = [&](auto par_c, const int t) {
+        const int par = (EXACT && kUnroll) ? decltype(par_c)::value : (t & 1);
         // ---- point-wise Jacobians of step t
         {
             float dwx[G][PP], dg[G][PP];
@@ -615,10 +620,10 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
             }
 #pragma unroll
             for (int g = 0; g < G; ++g) {
-                write_operand_lds<true, PP>(gbuf + (t & 1) * BUF + lds_row, g * D + e0, dg[g]);
-                store_io<true, PP>(out_img + (t & 1) * L.out_pitch + l_out + (uint32_t)g * L.rp_io, 0, dwx[g]);
+                write_operand_lds<true, PP>(gbuf + par * BUF + lds_row, g * D + e0, dg[g]);
+                store_io<true, PP>(out_img + par * L.out_pitch + l_out + (uint32_t)g * L.rp_io, 0, dwx[g]);
             }
-            if constexpr (CELL == CELL_GRU) store_io<true, PP>(out_img + (t & 1) * L.out_pitch + l_out + (uint32_t)G * L.rp_io, 0, dg[2]);
+            if constexpr (CELL == CELL_GRU) store_io<true, PP>(out_img + par * L.out_pitch + l_out + (uint32_t)G * L.rp_io, 0, dg[2]);
             if constexpr (!cell_uses_h_prev(CELL)) {
 #pragma unroll
                 for (int s = SB0; s < SB0 + NSB; ++s)
@@ -638,14 +643,14 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
         // The operand is read in chunks of KC k-steps, one chunk ahead of the MFMAs that use it.
         constexpr int KC = 4, NCK = (KTW + KC - 1) / KC;
         bf16x8 gB[NCK][KC];
-        const char* grow = gbuf + (t & 1) * BUF + lds_row + (size_t)(ks * KTW * 32 + lm.quad * 8) * 2;
+        const char* grow = gbuf + par * BUF + lds_row + (size_t)(ks * KTW * 32 + lm.quad * 8) * 2;
         auto read_chunk = [&](int c) {
 #pragma unroll
             for (int k = 0; k < KC; ++k)
                 if (c * KC + k < KTW) gB[c][k] = *(const bf16x8*)(grow + (size_t)(c * KC + k) * 64);
         };
         read_chunk(0);
-        if (t > 2) fetch(t - 2);
+        if (t > 2) fetch(par);
         pin_order();
         f32x4 acc[EBK][NA];
 #pragma unroll
@@ -664,8 +669,8 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
             if (c + 1 < NCK) read_chunk(c + 1);
             if (c == 0) {   // dWx_t out of its image and on its way, step t-1's values out of theirs
                 i32x4 o = i32x4{0, 0, 0, 0};
-                if (out_real) o = *(const i32x4*)(out_img + (t & 1) * L.out_pitch + cout_l);
-                if (t > 1) { take(t - 1); precompute(); }
+                if (out_real) o = *(const i32x4*)(out_img + par * L.out_pitch + cout_l);
+                if (t > 1) { take(par ^ 1); precompute(); }
                 pin_order();
                 __builtin_amdgcn_raw_buffer_store_b128(o, make_rsrc(dwx_ptr), cout_g, 0, 0);
                 dwx_ptr -= wx_step;
@@ -715,6 +720,18 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
 #pragma unroll
                 for (int i = 0; i < PP; ++i) dbv[g][i] = dbs[((size_t)g * D + i) * BT];
         }
+    };
+    using par0 = std::integral_constant<int, 0>;
+    using par1 = std::integral_constant<int, 1>;
+    if constexpr (EXACT && kUnroll) {
+        int t = T;
+        if (t & 1) { step(par1{}, t); --t; }
+        for (; t >= 2; t -= 2) {
+            step(par0{}, t);
+            step(par1{}, t - 1);
+        }
+    } else {
+        for (int t = T; t >= 1; --t) step(par0{}, t);
     }
     // ---- gradients w.r.t. the initial states, per-row partial sums of db
     if (row_valid) {
