@@ -363,6 +363,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
     constexpr int NSB = CELL == CELL_SLSTM ? 2 : CELL == CELL_ELMAN ? 0 : 1;   // state rows the Jacobian needs per time level ...
     constexpr int SB0 = cell_uses_h_prev(CELL) ? 0 : 1;   // ... starting at this state
     constexpr int GO = CELL == CELL_GRU ? G + 1 : G;  // output rows per batch row: dWx (+ the recurrent-side candidate gradient)
+    constexpr bool kOutFromOperand = CELL != CELL_GRU;
     constexpr int NA = EBK == 1 ? 4 : (EBK == 2 ? 2 : 1);   // accumulators per block: independent MFMAs in flight
     constexpr uint32_t kDrop = 0x80000000u;
     constexpr uint32_t REC = CT::RS * ESZ;
@@ -439,7 +440,9 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
             const bool in = row < (uint32_t)BT * GO && brow < (uint32_t)B;
             cout_g = (in && g < (uint32_t)G) ? ((brow * G + g) * HD) * ESZ + ch * 16 : kDrop;
             cout_n = (in && g == (uint32_t)G) ? (brow * HD) * ESZ + ch * 16 : kDrop;
-            cout_l = row * L.rp_io + ch * 16;
+            // Where the input-side gate gradients equal the recurrent-side ones (every cell but the GRU), the rows written
+            // for the MFMA operand are the output rows as well: no second image.
+            cout_l = kOutFromOperand ? (row / G) * L.hp + (row % G) * (uint32_t)D * ESZ + ch * 16 : row * L.rp_io + ch * 16;
             out_real = row < (uint32_t)BT * GO;
         }
     }
@@ -621,7 +624,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
 #pragma unroll
             for (int g = 0; g < G; ++g) {
                 write_operand_lds<true, PP>(gbuf + par * BUF + lds_row, g * D + e0, dg[g]);
-                store_io<true, PP>(out_img + par * L.out_pitch + l_out + (uint32_t)g * L.rp_io, 0, dwx[g]);
+                if constexpr (!kOutFromOperand) store_io<true, PP>(out_img + par * L.out_pitch + l_out + (uint32_t)g * L.rp_io, 0, dwx[g]);
             }
             if constexpr (CELL == CELL_GRU) store_io<true, PP>(out_img + par * L.out_pitch + l_out + (uint32_t)G * L.rp_io, 0, dg[2]);
             if constexpr (!cell_uses_h_prev(CELL)) {
@@ -669,7 +672,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
             if (c + 1 < NCK) read_chunk(c + 1);
             if (c == 0) {   // dWx_t out of its image and on its way, step t-1's values out of theirs
                 i32x4 o = i32x4{0, 0, 0, 0};
-                if (out_real) o = *(const i32x4*)(out_img + par * L.out_pitch + cout_l);
+                if (out_real) o = *(const i32x4*)((kOutFromOperand ? gbuf + par * BUF : out_img + par * L.out_pitch) + cout_l);
                 if (t > 1) { take(par ^ 1); precompute(); }
                 pin_order();
                 __builtin_amdgcn_raw_buffer_store_b128(o, make_rsrc(dwx_ptr), cout_g, 0, 0);
