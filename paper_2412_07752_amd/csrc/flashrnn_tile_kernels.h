@@ -647,10 +647,22 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
         constexpr int KC = 4, NCK = (KTW + KC - 1) / KC;
         bf16x8 gB[NCK][KC];
         const char* grow = gbuf + par * BUF + lds_row + (size_t)(ks * KTW * 32 + lm.quad * 8) * 2;
+        // Only the lanes of the BT valid batch columns read: the backward step is bound by the LDS (busy 62 % of the
+        // step, nearly half of it these reads), and an LDS read costs bandwidth per active lane.  The other lanes' registers
+        // keep whatever they held -- a column of the B operand only reaches the same column of the result, and the
+        // columns c >= BT of a result are never used; the empty asm statements stand for "any value" (without them
+        // the compiler would give the idle lanes a defined value, one move per register and chunk).
         auto read_chunk = [&](int c) {
+            i32x4 raw[KC];
 #pragma unroll
-            for (int k = 0; k < KC; ++k)
-                if (c * KC + k < KTW) gB[c][k] = *(const bf16x8*)(grow + (size_t)(c * KC + k) * 64);
+            for (int k = 0; k < KC; ++k) asm volatile("" : "=v"(raw[k]));
+            if (lm.c < BT) {
+#pragma unroll
+                for (int k = 0; k < KC; ++k)
+                    if (c * KC + k < KTW) raw[k] = *(const i32x4*)(grow + (size_t)(c * KC + k) * 64);
+            }
+#pragma unroll
+            for (int k = 0; k < KC; ++k) gB[c][k] = __builtin_bit_cast(bf16x8, raw[k]);
         };
         read_chunk(0);
         if (t > 2) fetch(par);
