@@ -363,7 +363,6 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
     constexpr int NSB = CELL == CELL_SLSTM ? 2 : CELL == CELL_ELMAN ? 0 : 1;   // state rows the Jacobian needs per time level ...
     constexpr int SB0 = cell_uses_h_prev(CELL) ? 0 : 1;   // ... starting at this state
     constexpr int GO = CELL == CELL_GRU ? G + 1 : G;  // output rows per batch row: dWx (+ the recurrent-side candidate gradient)
-    constexpr bool kOutFromOperand = CELL != CELL_GRU;
     constexpr int NA = EBK == 1 ? 4 : (EBK == 2 ? 2 : 1);   // accumulators per block: independent MFMAs in flight
     constexpr uint32_t kDrop = 0x80000000u;
     constexpr uint32_t REC = CT::RS * ESZ;
@@ -415,7 +414,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
     // ---- chunk roles: global byte offsets (out of range = nothing to move)
     constexpr int NCC = (BT * (int)REC + 63) / 64;   // record chunks per thread: BT rows of D records, NT = 4 D threads
     uint32_t cc_g[NCC], cst_g, cdh_g, cout_g, cout_n, cout_l;
-    bool out_real, c_wave[NCC];
+    bool out_real, cout_img, c_wave[NCC];
     const uint32_t cpr_io = (uint32_t)D / 8;
     const bool st_wave = (uint32_t)w * 64 < (uint32_t)BT * NSB * (D / 4), dh_wave = (uint32_t)w * 64 < (uint32_t)BT * cpr_io;
     {
@@ -440,9 +439,12 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
             const bool in = row < (uint32_t)BT * GO && brow < (uint32_t)B;
             cout_g = (in && g < (uint32_t)G) ? ((brow * G + g) * HD) * ESZ + ch * 16 : kDrop;
             cout_n = (in && g == (uint32_t)G) ? (brow * HD) * ESZ + ch * 16 : kDrop;
-            // Where the input-side gate gradients equal the recurrent-side ones (every cell but the GRU), the rows written
-            // for the MFMA operand are the output rows as well: no second image.
-            cout_l = kOutFromOperand ? (row / G) * L.hp + (row % G) * (uint32_t)D * ESZ + ch * 16 : row * L.rp_io + ch * 16;
+            // Where the input-side gate gradients equal the recurrent-side ones, the rows written for the MFMA operand are
+            // the output rows as well.  That is every gate of every cell but the GRU's candidate, whose input-side gradient
+            // alone goes through an image of its own (one row per batch row; the recurrent-side one is the operand's).
+            const uint32_t og = g == (uint32_t)G ? 2u : g;   // gate segment of the operand row
+            cout_img = CELL == CELL_GRU && g == 2;
+            cout_l = cout_img ? (row / GO) * L.rp_io + ch * 16 : (row / GO) * L.hp + og * (uint32_t)D * ESZ + ch * 16;
             out_real = row < (uint32_t)BT * GO;
         }
     }
@@ -450,7 +452,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
     const uint32_t l_c = ((uint32_t)lm.bslot * D + e0) * REC;
     const uint32_t l_st = L.st_off + ((uint32_t)lm.bslot * D + e0) * 4;
     const uint32_t l_dh = L.dh_off + ((uint32_t)lm.bslot * D + e0) * ESZ;
-    const uint32_t l_out = (uint32_t)lm.bslot * GO * L.rp_io + e0 * ESZ;
+    const uint32_t l_out = (uint32_t)lm.bslot * L.rp_io + e0 * ESZ;
     const uint32_t lds_row = (uint32_t)lm.bslot * L.hp;
 
     // carried state gradients; ds[0] is the part of dh_t that came through R and the direct path
@@ -624,9 +626,8 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
 #pragma unroll
             for (int g = 0; g < G; ++g) {
                 write_operand_lds<true, PP>(gbuf + par * BUF + lds_row, g * D + e0, dg[g]);
-                if constexpr (!kOutFromOperand) store_io<true, PP>(out_img + par * L.out_pitch + l_out + (uint32_t)g * L.rp_io, 0, dwx[g]);
             }
-            if constexpr (CELL == CELL_GRU) store_io<true, PP>(out_img + par * L.out_pitch + l_out + (uint32_t)G * L.rp_io, 0, dg[2]);
+            if constexpr (CELL == CELL_GRU) store_io<true, PP>(out_img + par * L.out_pitch + l_out, 0, dwx[2]);
             if constexpr (!cell_uses_h_prev(CELL)) {
 #pragma unroll
                 for (int s = SB0; s < SB0 + NSB; ++s)
@@ -684,7 +685,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
             if (c + 1 < NCK) read_chunk(c + 1);
             if (c == 0) {   // dWx_t out of its image and on its way, step t-1's values out of theirs
                 i32x4 o = i32x4{0, 0, 0, 0};
-                if (out_real) o = *(const i32x4*)((kOutFromOperand ? gbuf + par * BUF : out_img + par * L.out_pitch) + cout_l);
+                if (out_real) o = *(const i32x4*)(((CELL == CELL_GRU && cout_img) ? out_img + par * L.out_pitch : gbuf + par * BUF) + cout_l);
                 if (t > 1) { take(par ^ 1); precompute(); }
                 pin_order();
                 __builtin_amdgcn_raw_buffer_store_b128(o, make_rsrc(dwx_ptr), cout_g, 0, 0);
