@@ -386,15 +386,26 @@ __device__ __forceinline__ void publish_tile(__amdgpu_buffer_rsrc_t rs, uint32_t
     publish4<BF16>(rs, row_off, k_wave + 4 * lm.quad, v4, stamp, far);
 }
 
-// One k-step of the B operand out of an LDS row.  Only the batch columns c < BT of a tile carry data: the other lanes
-// do not read at all (an LDS read costs bandwidth per active lane), their operand columns are zero and their results unused.
-// (Worth it where a wave reads long rows: with 8 k-steps per wave the step of a D = 256 head got 14 % shorter; with 6 k-steps
-// per wave, and in the staged tile kernels, whose LDS reads hide behind the MFMAs, the extra branch cost more than it saved.)
-template <int BT, bool MASKED> __device__ __forceinline__ bf16x8 lds_operand_col(const char* p, int c) {
-    if constexpr (!MASKED || BT == 16) return *(const bf16x8*)p;
-    bf16x8 v = __builtin_bit_cast(bf16x8, i32x4{0, 0, 0, 0});
-    if (c < BT) v = *(const bf16x8*)p;
-    return v;
+// KC consecutive k-steps (64 bytes apart) of the B operand, read by the lanes of the valid batch columns only, under one
+// execution mask.  The other lanes' registers keep whatever they held: a column of the B operand only reaches the same
+// column of the result, and the columns c >= BT of a result are never used (the empty asm statements stand for "any
+// value": without them the compiler would give the idle lanes a defined value, one move per register).  An LDS read costs
+// bandwidth per active lane, and the backward step of a split group, whose waves read all G * D gate gradients, is bound by the LDS.
+template <int BT, int KC, bool MASKED> __device__ __forceinline__ void lds_operand_chunk(const char* p, int c, bf16x8 (&out)[KC]) {
+    if constexpr (BT == 16 || !MASKED) {
+#pragma unroll
+        for (int j = 0; j < KC; ++j) out[j] = *(const bf16x8*)(p + j * 64);
+    } else {
+        i32x4 raw[KC];
+#pragma unroll
+        for (int j = 0; j < KC; ++j) asm volatile("" : "=v"(raw[j]));
+        if (c < BT) {
+#pragma unroll
+            for (int j = 0; j < KC; ++j) raw[j] = *(const i32x4*)(p + j * 64);
+        }
+#pragma unroll
+        for (int j = 0; j < KC; ++j) out[j] = __builtin_bit_cast(bf16x8, raw[j]);
+    }
 }
 
 // LDS operand row: element type bf16 (as uint16) or float
@@ -630,10 +641,12 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
 #pragma unroll
                 for (int kc = 0; kc < KT; kc += KC) {
                     op_t hB[KC];
+                    if constexpr (BF16) {
+                        // (forward: worth it from 8 k-steps per wave on; with shorter rows the LDS is not what bounds the step)
+                        lds_operand_chunk<BT, KC, (KT >= 8)>(hbuf + lds_rd + (size_t)(k0 + kc * 32 + lm.quad * 8) * 2, lm.c, hB);
+                    } else {
 #pragma unroll
-                    for (int j = 0; j < KC; ++j) {
-                        if constexpr (BF16) hB[j] = lds_operand_col<BT, (KT >= 8)>(hbuf + lds_rd + (size_t)(k0 + (kc + j) * 32 + lm.quad * 8) * 2, lm.c);
-                        else hB[j] = *(const float*)(hbuf + lds_rd + (size_t)(k0 + lm.quad * KT + kc + j) * 4);
+                        for (int j = 0; j < KC; ++j) hB[j] = *(const float*)(hbuf + lds_rd + (size_t)(k0 + lm.quad * KT + kc + j) * 4);
                     }
 #pragma unroll
                     for (int j = 0; j < KC; ++j)
@@ -925,10 +938,11 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
 #pragma unroll
                 for (int kc = 0; kc < KT; kc += KC) {
                     op_t gB[KC];
+                    if constexpr (BF16) {
+                        lds_operand_chunk<BT, KC, true>(gbuf + lds_row + (size_t)(k0 + kc * 32 + lm.quad * 8) * 2, lm.c, gB);
+                    } else {
 #pragma unroll
-                    for (int j = 0; j < KC; ++j) {
-                        if constexpr (BF16) gB[j] = lds_operand_col<BT, (KT >= 8)>(gbuf + lds_row + (size_t)(k0 + (kc + j) * 32 + lm.quad * 8) * 2, lm.c);
-                        else gB[j] = *(const float*)(gbuf + lds_row + (size_t)(k0 + lm.quad * KT + kc + j) * 4);
+                        for (int j = 0; j < KC; ++j) gB[j] = *(const float*)(gbuf + lds_row + (size_t)(k0 + lm.quad * KT + kc + j) * 4);
                     }
 #pragma unroll
                     for (int j = 0; j < KC; ++j) a4[0][(kc + j) % NA] = OP::mfma(Rf[0][kc + j], gB[j], a4[0][(kc + j) % NA]);
