@@ -325,9 +325,10 @@ int carve_uncached(const flashrnn_desc_t* d, Workspace* w, Plan* pf, Plan* pb) {
     w->rpack_off = off; off += align_up(pf->rpack_bytes > pb->rpack_bytes ? pf->rpack_bytes : pb->rpack_bytes);
     w->fwd_total = w->rpack_off + align_up(pf->rpack_bytes);
     w->dgn_off = off; off += align_up(d->cell == FLASHRNN_GRU ? (size_t)d->T * d->B * d->NH * d->D * io_size(d->io_dtype) : 0);
-    w->dbpart_off = off; off += align_up((size_t)d->B * d->NH * G * d->D * 4);
-    w->drpart_off = off;
     const int sk = dr_split_k(d->io_dtype == FLASHRNN_BF16, d->T, d->B, d->NH, d->D, G);
+    // partial sums of db: one row per batch row (from the persistent kernel) or per contraction slice (from the dR GEMM)
+    w->dbpart_off = off; off += align_up((size_t)(d->B > sk ? d->B : sk) * d->NH * G * d->D * 4);
+    w->drpart_off = off;
     off += align_up(sk > 1 ? (size_t)sk * d->NH * d->D * G * d->D * 4 : 0);
     w->trace_off = off;
 #ifdef FLASHRNN_TRACE
@@ -576,14 +577,20 @@ int bwd_impl(const flashrnn_desc_t* d, const void* Wx, const void* R, const void
     }
     (void)rec_step;
     // db: sum of the per-row partial sums in row order; dR: GEMM over (t, b)
+    // (the staged kernels leave db to the GEMM, which reads every gate gradient anyway)
     const size_t nb = (size_t)d->NH * G * d->D;
+    const bool db_from_gemm = pb.e->tile != 0;
     if (d->T == 0) {
-        if (launch_sum_slices((const float*)(ws + w.dbpart_off), (float*)db, nb, d->B, nb, stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
+        if (db_from_gemm) {
+            if (launch_fill_zero(db, nb * 4, stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
+        } else if (launch_sum_slices((const float*)(ws + w.dbpart_off), (float*)db, nb, d->B, nb, stream) != hipSuccess) {
+            return FLASHRNN_ERR_LAUNCH;
+        }
         if (launch_fill_zero(dR, (size_t)d->NH * d->D * G * d->D * 4, stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
         return FLASHRNN_OK;
     }
     if (launch_dr_gemm(bf, (const float*)states, dWx, ws + w.dgn_off, (float*)(ws + w.drpart_off), (float*)dR, d->T, d->B, d->NH, d->D,
-                       G, S, d->cell == FLASHRNN_GRU, (const float*)(ws + w.dbpart_off), (float*)db, stream) != hipSuccess)
+                       G, S, d->cell == FLASHRNN_GRU, (float*)(ws + w.dbpart_off), db_from_gemm, (float*)db, stream) != hipSuccess)
         return FLASHRNN_ERR_LAUNCH;
     return FLASHRNN_OK;
 }
@@ -655,8 +662,8 @@ int flashrnn_bwd(const flashrnn_desc_t* d, const void* R, const void* b, const v
 int flashrnn_bwd_recompute(const flashrnn_desc_t* d, const void* Wx, const void* R, const void* b, const void* states, const void* dH,
                            const void* dstates_last, void* dWx, void* dR, void* db, void* dstates0, void* workspace, void* hip_stream) {
     if (d && validate(d) == FLASHRNN_OK && d->T > 0 && !Wx) return FLASHRNN_ERR_NULL;
-    static const char kNoInputs = 0;   // T = 0: nothing to recompute; any non-null pointer selects the windowed path
-    return bwd_impl(d, Wx ? Wx : (d && d->T == 0 ? (const void*)&kNoInputs : nullptr), R, b, states, nullptr, dH, dstates_last, dWx, dR, db, dstates0,
+    alignas(16) static const char kNoInputs[16] = {0};   // T = 0: nothing to recompute; any non-null, aligned pointer selects the windowed path
+    return bwd_impl(d, Wx ? Wx : (d && d->T == 0 ? (const void*)kNoInputs : nullptr), R, b, states, nullptr, dH, dstates_last, dWx, dR, db, dstates0,
                     workspace, hip_stream);
 }
 

@@ -88,7 +88,6 @@ struct TileLdsBwd {
     uint32_t in_off, in_pitch;   // two input images: records | state rows | dh rows
     uint32_t st_off, dh_off;     // ... offsets of the state rows and the dh rows inside an input image
     uint32_t out_off, out_pitch; // two output images: BT * GO bf16 rows
-    uint32_t db_off;             // per-row bias-gradient sums: [G][D][BT] f32
     uint32_t total;
 };
 __host__ __device__ inline uint32_t round_up(uint32_t a, uint32_t b) { return (a + b - 1) / b * b; }
@@ -105,8 +104,7 @@ __host__ __device__ inline TileLdsBwd tile_lds_bwd(int BT, int GO, int NSB, int 
     L.in_pitch = L.dh_off + round_up((uint32_t)BT * D * 2u, 1024u);
     L.out_off = L.in_off + 2u * L.in_pitch;
     L.out_pitch = (uint32_t)BT * GO * L.rp_io;
-    L.db_off = L.out_off + 2u * L.out_pitch;
-    L.total = L.db_off + (uint32_t)(GO > 3 ? 4 : 3) * D * BT * 4u;
+    L.total = L.out_off + 2u * L.out_pitch;
     return L;
 }
 

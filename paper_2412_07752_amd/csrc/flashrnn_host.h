@@ -41,7 +41,7 @@ KernelTable table_gru4_f32();
 
 int dr_split_k(bool bf16, int T, int B, int NH, int D, int G);
 hipError_t launch_dr_gemm(bool bf16, const float* states, const void* dWx, const void* dgn, float* part, float* dR, int T, int B,
-                          int NH, int D, int G, int S, bool gru, const float* db_part, float* db, hipStream_t stream);
+                          int NH, int D, int G, int S, bool gru, float* db_part, bool db_from_gemm, float* db, hipStream_t stream);
 hipError_t launch_sum_slices(const float* part, float* out, size_t count, int NS, size_t stride, hipStream_t stream);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t stream);
 hipError_t launch_pack_r(bool bf16, bool bwd, const void* R, void* out, int NH, int D, int G, int DK, int* err, hipStream_t stream);

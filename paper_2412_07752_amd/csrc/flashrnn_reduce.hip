@@ -179,10 +179,15 @@ __global__ __launch_bounds__(256) void dr_gemm_kernel(const float* __restrict__ 
 // (width + 16 elements) spreads over all 64 banks twice, the minimum for its 512 bytes.
 // Tile: (16 FM WM) x (16 FN WN) outputs per workgroup of WM x WN waves, 32 contraction rows per round, two LDS buffers
 // (one barrier per round), the next round's global loads in flight during the MFMAs.
-template <int FM, int FN, int WM, int WN>
+// DB: the kernel also sums the gate gradients over (t, b) -- the bias gradient, db[n][g][e] = sum_{t,b} dg_t[b][n][g][e]
+// (Sec. 4): the waves that hold the first 16 output rows of a column block multiply a 16 x 32 block of ones onto every B operand
+// they read anyway, one more MFMA per round and column block and no further memory traffic.  One row of that product per
+// contraction slice goes to dbp[sk][n][g*D + e].  (Used with the staged backward kernels, which have neither the
+// registers to keep those sums while their MFMAs run nor the LDS bandwidth to park them.)
+template <int FM, int FN, int WM, int WN, bool DB>
 __global__ __launch_bounds__(WM * WN * 64) void dr_gemm_tr_kernel(const float* __restrict__ states, const void* __restrict__ dWx,
-                                                                 const void* __restrict__ dgn, float* __restrict__ out, int T, int B, int NH,
-                                                                 int D, int G, int S, int SK, int gru) {
+                                                                 const void* __restrict__ dgn, float* __restrict__ out, float* __restrict__ dbp,
+                                                                 int T, int B, int NH, int D, int G, int S, int SK, int gru) {
     constexpr int TMW = 16 * FM * WM, TNW = 16 * FN * WN, NT = 64 * WM * WN;
     constexpr int PA = TMW + 16, PB = TNW + 16;                   // LDS row pitches in bf16 elements
     constexpr int LA = TK * TMW / 4 / NT, LB = TK * TNW / 8 / NT;   // 16-byte global chunks per thread and round
@@ -210,6 +215,10 @@ __global__ __launch_bounds__(WM * WN * 64) void dr_gemm_tr_kernel(const float* _
     for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    f32x4 accdb[DB ? FN : 1];
+    const bool do_db = DB && tm == 0 && wm == 0;
+#pragma unroll
+    for (int j = 0; j < (DB ? FN : 1); ++j) accdb[j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // ---- loader roles.  A chunk = 4 consecutive d of one contraction row (f32), B chunk = 8 consecutive columns (bf16).
     // Chunk x of a thread: row ra_row[x] of the round, fixed column; the row's position k = (tt, b) is advanced per round
@@ -306,6 +315,24 @@ __global__ __launch_bounds__(WM * WN * 64) void dr_gemm_tr_kernel(const float* _
         for (int i = 0; i < FM; ++i)
 #pragma unroll
             for (int j = 0; j < FN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        if constexpr (DB) {
+            if (do_db) {
+                typedef short s16x8 __attribute__((ext_vector_type(8)));
+                constexpr short one = 0x3F80;   // bf16 1.0
+                const bf16x8 ones = __builtin_bit_cast(bf16x8, s16x8{one, one, one, one, one, one, one, one});
+#pragma unroll
+                for (int j = 0; j < FN; ++j) accdb[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, bfr[j], accdb[j], 0, 0, 0);
+            }
+        }
+    }
+    if constexpr (DB) {
+        if (do_db && quad == 0) {   // every row of the product holds the column sums: row 0 is in the lanes of quad 0
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                const int col = tn * TNW + (wn * FN + j) * 16 + c;
+                if (col < GD) dbp[((size_t)sk * NH + n) * GD + col] = accdb[j][0];
+            }
+        }
     }
     // ---- store: lane holds column c and rows 4*quad + r of each 16x16 tile
     float* dst = out + ((size_t)sk * NH + n) * (size_t)D * GD;
@@ -415,7 +442,9 @@ enum DrTile { kDrSmall = 0, kDrWide = 1, kDrSquare = 2 };
 static DrTile dr_tile(bool bf16, int NH, int D, int G) {
     if (!bf16) return kDrSmall;
     const int n256 = (G * D + 255) / 256;
-    if ((D + 255) / 256 * 2 == (D + 127) / 128 && NH * ((D + 255) / 256) * n256 >= 32) return kDrSquare;
+    // (heads of at most 192 units run the staged backward kernels, whose bias gradient comes from this GEMM: the extra
+    // accumulators do not fit the registers of the square tile)
+    if (D > 192 && (D + 255) / 256 * 2 == (D + 127) / 128 && NH * ((D + 255) / 256) * n256 >= 32) return kDrSquare;
     if (NH * ((D + 127) / 128) * n256 >= 64) return kDrWide;
     return kDrSmall;
 }
@@ -433,19 +462,26 @@ int dr_split_k(bool bf16, int T, int B, int NH, int D, int G) {
     return sk;
 }
 
+// db_from_gemm: db_part is written here, one row of sums per contraction slice (bf16 only); otherwise it holds the
+// persistent kernel's per-batch-row sums.
 hipError_t launch_dr_gemm(bool bf16, const float* states, const void* dWx, const void* dgn, float* part, float* dR, int T, int B,
-                          int NH, int D, int G, int S, bool gru, const float* db_part, float* db, hipStream_t stream) {
+                          int NH, int D, int G, int S, bool gru, float* db_part, bool db_from_gemm, float* db, hipStream_t stream) {
     const int SK = dr_split_k(bf16, T, B, NH, D, G);
     const int GD = G * D;
     float* target = SK == 1 ? dR : part;
     const DrTile t = dr_tile(bf16, NH, D, G);
     const int grid = (NH * SK + 7) / 8 * 8 * (dr_tiles(t, NH, D, G) / NH);   // (head, K slice) padded to the 8 XCDs
+    if (db_from_gemm && (!bf16 || t == kDrSquare)) return hipErrorInvalidValue;
     if (t == kDrSquare)
-        hipLaunchKernelGGL((dr_gemm_tr_kernel<4, 8, 4, 2>), dim3(grid), dim3(512), 0, stream, states, dWx, dgn, target, T, B, NH, D, G, S, SK, gru ? 1 : 0);
+        hipLaunchKernelGGL((dr_gemm_tr_kernel<4, 8, 4, 2, false>), dim3(grid), dim3(512), 0, stream, states, dWx, dgn, target, db_part, T, B, NH, D, G, S, SK, gru ? 1 : 0);
+    else if (t == kDrWide && db_from_gemm)
+        hipLaunchKernelGGL((dr_gemm_tr_kernel<4, 4, 2, 4, true>), dim3(grid), dim3(512), 0, stream, states, dWx, dgn, target, db_part, T, B, NH, D, G, S, SK, gru ? 1 : 0);
     else if (t == kDrWide)
-        hipLaunchKernelGGL((dr_gemm_tr_kernel<4, 4, 2, 4>), dim3(grid), dim3(512), 0, stream, states, dWx, dgn, target, T, B, NH, D, G, S, SK, gru ? 1 : 0);
+        hipLaunchKernelGGL((dr_gemm_tr_kernel<4, 4, 2, 4, false>), dim3(grid), dim3(512), 0, stream, states, dWx, dgn, target, db_part, T, B, NH, D, G, S, SK, gru ? 1 : 0);
+    else if (bf16 && db_from_gemm)
+        hipLaunchKernelGGL((dr_gemm_tr_kernel<2, 4, 2, 2, true>), dim3(grid), dim3(256), 0, stream, states, dWx, dgn, target, db_part, T, B, NH, D, G, S, SK, gru ? 1 : 0);
     else if (bf16)
-        hipLaunchKernelGGL((dr_gemm_tr_kernel<2, 4, 2, 2>), dim3(grid), dim3(256), 0, stream, states, dWx, dgn, target, T, B, NH, D, G, S, SK, gru ? 1 : 0);
+        hipLaunchKernelGGL((dr_gemm_tr_kernel<2, 4, 2, 2, false>), dim3(grid), dim3(256), 0, stream, states, dWx, dgn, target, db_part, T, B, NH, D, G, S, SK, gru ? 1 : 0);
     else
         hipLaunchKernelGGL(dr_gemm_kernel<false>, dim3(grid), dim3(256), 0, stream, states, dWx, dgn, target, T, B, NH, D, G, S, SK, gru ? 1 : 0);
     hipError_t e = hipGetLastError();
@@ -453,7 +489,7 @@ hipError_t launch_dr_gemm(bool bf16, const float* states, const void* dWx, const
     // split-K partial sums of dR (if any) and the per-row partial sums of db, each added in index order
     const size_t count = SK > 1 ? (size_t)NH * D * GD : 0, nb = (size_t)NH * GD;
     hipLaunchKernelGGL(sum_slices2_kernel, dim3((unsigned)(((count + nb) / 4 + 255) / 256)), dim3(256), 0, stream, part, dR, count, SK, (size_t)NH * D * GD,
-                       db_part, db, nb, B, nb);
+                       (const float*)db_part, db, nb, db_from_gemm ? SK : B, nb);
     e = hipGetLastError();
     return e;
 }

@@ -457,7 +457,6 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
 
     // carried state gradients; ds[0] is the part of dh_t that came through R and the direct path
     float ds[S][PP];
-    float* dbs = (float*)(smem + L.db_off) + (size_t)e0 * BT + lm.bslot;   // this lane's bias-gradient sums: [g][unit][slot]
 #pragma unroll
     for (int s = 0; s < S; ++s) {
         if (p.dlast != nullptr && !(CELL == CELL_SLSTM && s == 3))
@@ -466,10 +465,6 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
 #pragma unroll
             for (int i = 0; i < PP; ++i) ds[s][i] = 0.0f;
     }
-#pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int i = 0; i < PP; ++i) dbs[((size_t)g * D + i) * BT] = 0.0f;
 
     for (uint32_t j = tid; j < 2 * BUF / 4; j += NT) ((uint32_t*)gbuf)[j] = 0u;
 
@@ -564,11 +559,8 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
     __syncthreads();
     if (T > 0) { take(T & 1); precompute(); }
 
-    float dbv[G][PP];   // the db sums, read back ahead of each point-wise phase
-#pragma unroll
-    for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int i = 0; i < PP; ++i) dbv[g][i] = 0.0f;
+    // (the bias gradient, the sum of dg over time and batch rows, is formed by the dR GEMM, which reads every dg anyway:
+    // this kernel has neither the registers to keep the sums while its MFMAs run nor LDS bandwidth to spare for them)
     // one time step; PAR = t & 1 as a compile-time constant where the loop is unrolled by two
     constexpr bool kUnroll = true;
     auto step = [&](auto par_c, const int t) {
@@ -618,9 +610,6 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
                 for (int g = 0; g < G; ++g) {
                     dwx[g][i] = dwxi[g];
                     dg[g][i] = dgi[g];
-                    // db sums live in LDS between the point-wise phases (each lane owns its slots): registers are
-                    // what this kernel is short of while the MFMAs run
-                    dbv[g][i] += dgi[g];
                 }
             }
 #pragma unroll
@@ -639,10 +628,6 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
         // they are read after this barrier
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(CELL == CELL_GRU ? 2 : 1) : "memory");
         __syncthreads();
-#pragma unroll
-        for (int g = 0; g < G; ++g)   // (behind the barrier: nobody else reads them)
-#pragma unroll
-            for (int i = 0; i < PP; ++i) dbs[((size_t)g * D + i) * BT] = dbv[g][i];
         // ---- dh_{t-1} += R dg_t; in the shadow of the chain: fetch step t-2, dWx_t out, step t-1's values
         // The operand is read in chunks of KC k-steps, one chunk ahead of the MFMAs that use it.
         constexpr int KC = 4, NCK = (KTW + KC - 1) / KC;
@@ -711,10 +696,6 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
 #pragma unroll
             for (int j = 0; j < EBK; ++j)   // partial sum of block tg*EBK + j from slice ks
                 store_io<false, PP>(red, ((size_t)((tg * EBK + j) * EBK + ks) * 64 + lane) * PP, part[j]);
-#pragma unroll
-            for (int g = 0; g < G; ++g)
-#pragma unroll
-                for (int i = 0; i < PP; ++i) dbv[g][i] = dbs[((size_t)g * D + i) * BT];
             __syncthreads();
             float rec[PP];   // R dg_t of this lane's pairs, summed over the slices
 #pragma unroll
@@ -731,10 +712,6 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
         } else {
 #pragma unroll
             for (int i = 0; i < PP; ++i) ds[0][i] += fminf(fmaxf(part[0][i], -p.clip), p.clip);
-#pragma unroll
-            for (int g = 0; g < G; ++g)
-#pragma unroll
-                for (int i = 0; i < PP; ++i) dbv[g][i] = dbs[((size_t)g * D + i) * BT];
         }
     };
     using par0 = std::integral_constant<int, 0>;
@@ -749,25 +726,11 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
     } else {
         for (int t = T; t >= 1; --t) step(par0{}, t);
     }
-    // ---- gradients w.r.t. the initial states, per-row partial sums of db
+    // ---- gradients w.r.t. the initial states
     if (row_valid) {
 #pragma unroll
         for (int s = 0; s < S; ++s)
             store_io_r<false, PP>(make_rsrc((char*)p.dstates0 + (size_t)n * D * 4), voff_st, s * st_state, ds[s]);
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            float dbv[PP];
-#pragma unroll
-            for (int i = 0; i < PP; ++i) dbv[i] = dbs[((size_t)g * D + i) * BT];
-            const size_t at = (((size_t)bb * NH + n) * G + g) * D + e0;
-            if (p.db_accumulate) {   // a later window of a windowed backward pass: on top of the windows before it
-                float prev[PP];
-                load_f32<PP>(p.db_part, at, prev);
-#pragma unroll
-                for (int i = 0; i < PP; ++i) dbv[i] += prev[i];
-            }
-            store_f32<PP>(p.db_part, at, dbv);
-        }
     }
 }
 
