@@ -4,6 +4,7 @@
 // dense, MFMA-bound contraction of the method and runs outside the sequential loop.  Both operands
 // have the contraction axis as their slow memory axis, so tiles are transposed through LDS.
 // Split-K partial sums are written separately and added in a fixed order (no float atomics).
+#include <type_traits>
 #include "flashrnn_common.h"
 #include "flashrnn_host.h"
 
@@ -184,7 +185,9 @@ __global__ __launch_bounds__(256) void dr_gemm_kernel(const float* __restrict__ 
 // they read anyway, one more MFMA per round and column block and no further memory traffic.  One row of that product per
 // contraction slice goes to dbp[sk][n][g*D + e].  (Used with the staged backward kernels, which have neither the
 // registers to keep those sums while their MFMAs run nor the LDS bandwidth to park them.)
-template <int FM, int FN, int WM, int WN, bool DB>
+// DEPTH: rounds of global loads in flight (register sets).  A round of the small tiles is a few hundred clocks of work
+// against a load latency of a microsecond: two sets in flight nearly halve the time of a short contraction.
+template <int FM, int FN, int WM, int WN, bool DB, int DEPTH>
 __global__ __launch_bounds__(WM * WN * 64) void dr_gemm_tr_kernel(const float* __restrict__ states, const void* __restrict__ dWx,
                                                                  const void* __restrict__ dgn, float* __restrict__ out, float* __restrict__ dbp,
                                                                  int T, int B, int NH, int D, int G, int S, int SK, int gru) {
@@ -258,15 +261,16 @@ __global__ __launch_bounds__(WM * WN * 64) void dr_gemm_tr_kernel(const float* _
         b_rowstride[x] = from_dgn ? (size_t)NH * D : (size_t)G * NH * D;
         b_off[x] = (size_t)(kbeg + b_row[x]) * b_rowstride[x] + (from_dgn ? (size_t)n * D + be : ((size_t)bg * NH + n) * D + be);
     }
-    f32x4 ra[LA];
-    i32x4 rb[LB];
-    int kround = kbeg;   // first contraction row of the round the registers hold
-    auto load_tiles = [&]() __attribute__((always_inline)) {
+    f32x4 ra[DEPTH][LA];
+    i32x4 rb[DEPTH][LB];
+    int kround = kbeg;   // first contraction row of the round the next load fetches
+    auto load_tiles = [&](auto set_c) __attribute__((always_inline)) {
+        constexpr int SET = decltype(set_c)::value;
 #pragma unroll
         for (int x = 0; x < LA; ++x) {
             const bool ok = a_ok[x] && kround + a_row[x] < kend;
-            ra[x] = *(const f32x4*)(states + (ok ? a_off[x] : 0));
-            if (!ok) ra[x] = f32x4{0.f, 0.f, 0.f, 0.f};
+            ra[SET][x] = *(const f32x4*)(states + (ok ? a_off[x] : 0));
+            if (!ok) ra[SET][x] = f32x4{0.f, 0.f, 0.f, 0.f};
             int bb = a_bb[x] + adv_r;
             const bool wrap = bb >= B;
             a_bb[x] = wrap ? bb - B : bb;
@@ -275,18 +279,20 @@ __global__ __launch_bounds__(WM * WN * 64) void dr_gemm_tr_kernel(const float* _
 #pragma unroll
         for (int x = 0; x < LB; ++x) {
             const bool ok = b_ok[x] && kround + b_row[x] < kend;
-            rb[x] = *(const i32x4*)(b_base[x] + (ok ? b_off[x] : 0) * 2);
-            if (!ok) rb[x] = i32x4{0, 0, 0, 0};
+            rb[SET][x] = *(const i32x4*)(b_base[x] + (ok ? b_off[x] : 0) * 2);
+            if (!ok) rb[SET][x] = i32x4{0, 0, 0, 0};
             b_off[x] += (size_t)TK * b_rowstride[x];
         }
         kround += TK;
     };
-    auto park_tiles = [&](int buf) __attribute__((always_inline)) {
+    auto park_tiles = [&](auto set_c, int buf) __attribute__((always_inline)) {
+        constexpr int SET = decltype(set_c)::value;
 #pragma unroll
         for (int x = 0; x < LA; ++x)
-            *(i32x2*)(&ldsA[buf][a_row[x] * PA + a_col[x]]) = i32x2{(int)pack_bf16x2(ra[x][0], ra[x][1]), (int)pack_bf16x2(ra[x][2], ra[x][3])};
+            *(i32x2*)(&ldsA[buf][a_row[x] * PA + a_col[x]]) =
+                i32x2{(int)pack_bf16x2(ra[SET][x][0], ra[SET][x][1]), (int)pack_bf16x2(ra[SET][x][2], ra[SET][x][3])};
 #pragma unroll
-        for (int x = 0; x < LB; ++x) *(i32x4*)(&ldsB[buf][b_row[x] * PB + b_col[x]]) = rb[x];
+        for (int x = 0; x < LB; ++x) *(i32x4*)(&ldsB[buf][b_row[x] * PB + b_col[x]]) = rb[SET][x];
     };
     // this lane's part of a transposing load: row 4 quad + c / 4 (+ 16 for the second half), columns 4 (c % 4) .. + 3 of a 16-column block
     const int tr_row = 4 * quad + (c >> 2), tr_col = 4 * (c & 3);
@@ -300,12 +306,13 @@ __global__ __launch_bounds__(WM * WN * 64) void dr_gemm_tr_kernel(const float* _
         return __builtin_bit_cast(bf16x8, v);
     };
 
-    load_tiles();
-    int buf = 0;
-    for (int kb = kbeg; kb < kend; kb += TK, buf ^= 1) {
-        park_tiles(buf);       // (the buffer was last read two rounds ago: the barrier of the previous round lies in between)
+    using set0 = std::integral_constant<int, 0>;
+    using set1 = std::integral_constant<int, DEPTH - 1>;
+    // one round: the register set `set` goes to LDS buffer buf, is refilled with the round DEPTH rounds ahead, and the MFMAs run
+    auto round = [&](auto set_c, int kb, int buf) __attribute__((always_inline)) {
+        park_tiles(set_c, buf);       // (the buffer was last read two rounds ago: the barrier of the previous round lies in between)
         __syncthreads();
-        if (kb + TK < kend) load_tiles();
+        if (kb + DEPTH * TK < kend) load_tiles(set_c);
         bf16x8 af[FM], bfr[FN];
 #pragma unroll
         for (int i = 0; i < FM; ++i) af[i] = operand(ldsA[buf], PA, (wm * FM + i) * 16);
@@ -324,6 +331,19 @@ __global__ __launch_bounds__(WM * WN * 64) void dr_gemm_tr_kernel(const float* _
                 for (int j = 0; j < FN; ++j) accdb[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, bfr[j], accdb[j], 0, 0, 0);
             }
         }
+    };
+    load_tiles(set0{});
+    if constexpr (DEPTH == 2) {
+        if (kbeg + TK < kend) load_tiles(set1{});
+        int kb = kbeg;
+        for (; kb + TK < kend; kb += 2 * TK) {
+            round(set0{}, kb, 0);
+            round(set1{}, kb + TK, 1);
+        }
+        if (kb < kend) round(set0{}, kb, 0);
+    } else {
+        int buf = 0;
+        for (int kb = kbeg; kb < kend; kb += TK, buf ^= 1) round(set0{}, kb, buf);
     }
     if constexpr (DB) {
         if (do_db && quad == 0) {   // every row of the product holds the column sums: row 0 is in the lanes of quad 0
@@ -473,15 +493,15 @@ hipError_t launch_dr_gemm(bool bf16, const float* states, const void* dWx, const
     const int grid = (NH * SK + 7) / 8 * 8 * (dr_tiles(t, NH, D, G) / NH);   // (head, K slice) padded to the 8 XCDs
     if (db_from_gemm && (!bf16 || t == kDrSquare)) return hipErrorInvalidValue;
     if (t == kDrSquare)
-        hipLaunchKernelGGL((dr_gemm_tr_kernel<4, 8, 4, 2, false>), dim3(grid), dim3(512), 0, stream, states, dWx, dgn, target, db_part, T, B, NH, D, G, S, SK, gru ? 1 : 0);
+        hipLaunchKernelGGL((dr_gemm_tr_kernel<4, 8, 4, 2, false, 1>), dim3(grid), dim3(512), 0, stream, states, dWx, dgn, target, db_part, T, B, NH, D, G, S, SK, gru ? 1 : 0);
     else if (t == kDrWide && db_from_gemm)
-        hipLaunchKernelGGL((dr_gemm_tr_kernel<4, 4, 2, 4, true>), dim3(grid), dim3(512), 0, stream, states, dWx, dgn, target, db_part, T, B, NH, D, G, S, SK, gru ? 1 : 0);
+        hipLaunchKernelGGL((dr_gemm_tr_kernel<4, 4, 2, 4, true, 2>), dim3(grid), dim3(512), 0, stream, states, dWx, dgn, target, db_part, T, B, NH, D, G, S, SK, gru ? 1 : 0);
     else if (t == kDrWide)
-        hipLaunchKernelGGL((dr_gemm_tr_kernel<4, 4, 2, 4, false>), dim3(grid), dim3(512), 0, stream, states, dWx, dgn, target, db_part, T, B, NH, D, G, S, SK, gru ? 1 : 0);
+        hipLaunchKernelGGL((dr_gemm_tr_kernel<4, 4, 2, 4, false, 2>), dim3(grid), dim3(512), 0, stream, states, dWx, dgn, target, db_part, T, B, NH, D, G, S, SK, gru ? 1 : 0);
     else if (bf16 && db_from_gemm)
-        hipLaunchKernelGGL((dr_gemm_tr_kernel<2, 4, 2, 2, true>), dim3(grid), dim3(256), 0, stream, states, dWx, dgn, target, db_part, T, B, NH, D, G, S, SK, gru ? 1 : 0);
+        hipLaunchKernelGGL((dr_gemm_tr_kernel<2, 4, 2, 2, true, 2>), dim3(grid), dim3(256), 0, stream, states, dWx, dgn, target, db_part, T, B, NH, D, G, S, SK, gru ? 1 : 0);
     else if (bf16)
-        hipLaunchKernelGGL((dr_gemm_tr_kernel<2, 4, 2, 2, false>), dim3(grid), dim3(256), 0, stream, states, dWx, dgn, target, db_part, T, B, NH, D, G, S, SK, gru ? 1 : 0);
+        hipLaunchKernelGGL((dr_gemm_tr_kernel<2, 4, 2, 2, false, 2>), dim3(grid), dim3(256), 0, stream, states, dWx, dgn, target, db_part, T, B, NH, D, G, S, SK, gru ? 1 : 0);
     else
         hipLaunchKernelGGL(dr_gemm_kernel<false>, dim3(grid), dim3(256), 0, stream, states, dWx, dgn, target, T, B, NH, D, G, S, SK, gru ? 1 : 0);
     hipError_t e = hipGetLastError();
