@@ -809,6 +809,25 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
         const uint32_t soff_wx = lane_ok ? ((uint32_t)bb * G * HD + e0) * ESZ : kDrop;
         const uint32_t soff_dh = lane_ok ? voff_dh : kDrop;
 
+        // With several workgroups per group the polled rows in LDS are the complete dg_t of the group's batch rows -- which,
+        // for every cell but the GRU, is dWx_t as well: the group's threads move them out as 16-byte chunks (each thread
+        // at most NBO of them, fixed for the group) instead of every lane storing four 2-byte values of its own.
+        constexpr bool kOutRows = MULTI && CELL != CELL_GRU;
+        constexpr int NBO = BF16 ? 2 : 4;
+        uint32_t out_g[NBO], out_l[NBO];   // byte offset inside a step's dWx (dropped if there is no chunk), byte offset in the LDS rows
+        if constexpr (kOutRows) {
+            const uint32_t EPC = 16 / ESZ, cpg = (uint32_t)D / EPC, cprow = (uint32_t)G * cpg, total = (uint32_t)BT * cprow;
+            const uint32_t TG = (uint32_t)p.P * blockDim.x;
+#pragma unroll
+            for (int j = 0; j < NBO; ++j) {
+                const uint32_t ci = (uint32_t)bm.member * blockDim.x + threadIdx.x + (uint32_t)j * TG;
+                const uint32_t r = ci / cprow, rem = ci % cprow, g2 = rem / cpg, ch = rem % cpg, brow = (uint32_t)q * BT + r;
+                const bool ok = ci < total && brow < (uint32_t)B;
+                out_g[j] = ok ? ((brow * G + g2) * HD) * ESZ + ch * 16 : 0x80000000u;
+                out_l[j] = ok ? r * (uint32_t)(HP * ESZ) + rem * 16 : 0u;
+            }
+        }
+
         // carried state gradients; ds[0] is the part of dh_t that came through R and the direct path
         float ds[EB][S][PP];
         float dbacc[EB][G][PP];
@@ -903,8 +922,10 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
                         for (int g2 = 0; g2 < G; ++g2)
                             publish_tile<BF16, BT, PP>(xr, (cnt & 1u) * xbuf + xgroup, XROW, lm, g2 * D + e_wave, dg[g2], cnt + 1u, p.spread != 0);
                     }
+                    if constexpr (!kOutRows) {
 #pragma unroll
-                    for (int g2 = 0; g2 < G; ++g2) store_io_r<BF16, PP>(dwx_t, soff_wx + eb * 16 * ESZ, g2 * wx_gate, dwx[g2]);
+                        for (int g2 = 0; g2 < G; ++g2) store_io_r<BF16, PP>(dwx_t, soff_wx + eb * 16 * ESZ, g2 * wx_gate, dwx[g2]);
+                    }
                     if constexpr (CELL == CELL_GRU)
                         store_io_r<BF16, PP>(make_rsrc(dgn_g + (size_t)(t - 1) * dh_step), soff_dh + eb * 16 * ESZ, 0, dg[2]);
                 }
@@ -935,6 +956,11 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
                 __syncthreads();
                 FRNN_TRACE_MARK(3);
                 if (KS == 1 || ks == 0) load_step(t > 1 ? t - 1 : 1, cvn, scn, spn, dhn);
+                i32x4 out_v[NBO];
+                if constexpr (kOutRows) {
+#pragma unroll
+                    for (int j = 0; j < NBO; ++j) out_v[j] = *(const i32x4*)(gbuf + out_l[j]);
+                }
 #pragma unroll
                 for (int kc = 0; kc < KT; kc += KC) {
                     op_t gB[KC];
@@ -946,6 +972,11 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
                     }
 #pragma unroll
                     for (int j = 0; j < KC; ++j) a4[0][(kc + j) % NA] = OP::mfma(Rf[0][kc + j], gB[j], a4[0][(kc + j) % NA]);
+                }
+                if constexpr (kOutRows) {
+                    const rsrc_t dwx_rows = make_rsrc(dwx_g + (size_t)(t - 1) * wx_step);
+#pragma unroll
+                    for (int j = 0; j < NBO; ++j) __builtin_amdgcn_raw_buffer_store_b128(out_v[j], dwx_rows, out_g[j], 0, 0);
                 }
             }
             f32x4 accs[EB][1];
