@@ -190,10 +190,10 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
             for (int bi = 0; bi < 3 && !pl.e; ++bi) {
                 const int BT = pass == 0 ? bts[bi] : bts[2 - bi];
                 if (force_bt && BT != force_bt) continue;
-                // workgroups of one launch per XCD.  All members of a group must be resident at once; these kernels fit two
-                // workgroups on a CU (registers, LDS), so even a launch that asks for every CU of an XCD has a whole XCD of
-                // slack.  The backward pass keeps a margin of two CUs per XCD on top (its plans rarely want more anyway).
-                int cap = bwd ? cus / kXcds - 2 : cus / kXcds;
+                // workgroups of one launch per XCD: all members of a group must be resident at once, at most one per CU
+                // where a workgroup takes all registers of its CU.  (A head of 1024 units asks for every CU of an XCD, in both
+                // directions: with two CUs kept back the backward pass of such a head fell to one group of 16 rows at 13 us a step.)
+                int cap = cus / kXcds;
                 const int NG = d->NH * ((d->B + BT - 1) / BT);
                 const KernelEntry* best = nullptr;
                 for (int spills_ok = 0; spills_ok < 2 && !best; ++spills_ok)   // a kernel that keeps registers in scratch memory only as a last resort

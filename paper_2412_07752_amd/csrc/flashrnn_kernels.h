@@ -440,16 +440,18 @@ template <bool BF16, int PP> __device__ __forceinline__ void write_operand_lds(c
 
 // partial sums of the KS contraction slices meet in LDS: slices 1.. write, slice 0 adds.  A lane's four values of a tile
 // travel as one 16-byte access (64 lanes x 16 bytes back to back: no bank conflicts, a quarter of the LDS instructions).
-template <int NT, int KS>
+// Only the lanes of the BT valid batch columns take part (the others' sums are never used, and LDS traffic costs per active lane).
+template <int NT, int KS, int BT>
 __device__ __forceinline__ void reduce_slices(float* red, int parity, int ks, int wu, int NWU, int lane, f32x4 (&acc)[NT]) {
     if constexpr (KS > 1) {
-        if (ks > 0) {
+        const bool valid = BT == 16 || (lane & 15) < BT;
+        if (ks > 0 && valid) {
 #pragma unroll
             for (int g = 0; g < NT; ++g)
                 *(f32x4*)(red + (((((size_t)(parity * (KS - 1) + ks - 1) * NWU + wu) * NT + g) * 64 + lane) * 4)) = acc[g];
         }
         __syncthreads();
-        if (ks == 0) {
+        if (ks == 0 && valid) {
 #pragma unroll
             for (int s = 1; s < KS; ++s)
 #pragma unroll
@@ -654,7 +656,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
                         for (int g = 0; g < G; ++g) acc[g] = OP::mfma(Rf[0][g][kc + j], hB[j], acc[g]);
                 }
             }
-            reduce_slices<G, KS>(red, t & 1, ks, wu, p.NWU, lane, acc);
+            reduce_slices<G, KS, BT>(red, t & 1, ks, wu, p.NWU, lane, acc);
 #ifdef FLASHRNN_TRACE
             if constexpr (MULTI) { asm volatile("" : "+v"(acc[0]), "+v"(acc[G - 1]) : : "memory"); FRNN_TRACE_MARK(4); }
 #endif
@@ -985,7 +987,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
                 if constexpr (NA == 4) accs[eb][0] = (a4[eb][0] + a4[eb][1]) + (a4[eb][2] + a4[eb][3]);
                 else accs[eb][0] = a4[eb][0] + a4[eb][1];
             }
-            reduce_slices<1, KS>(red, t & 1, ks, wu, p.NWU, lane, accs[0]);
+            reduce_slices<1, KS, BT>(red, t & 1, ks, wu, p.NWU, lane, accs[0]);
 #ifdef FLASHRNN_TRACE
             if constexpr (MULTI) { asm volatile("" : "+v"(accs[0][0]) : : "memory"); FRNN_TRACE_MARK(4); }
 #endif
