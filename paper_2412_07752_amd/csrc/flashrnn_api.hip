@@ -267,8 +267,9 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
         // Heads beyond what the CUs of one XCD can hold (D > 1024): the group is spread over the CUs of all XCDs, one
         // block of 16 units and 4 contraction slices per workgroup (one wave per SIMD, up to 336 registers of R each),
         // and h / dg cross the XCDs through memory.  The largest batch tile whose kernel neither spills registers nor
-        // overflows the LDS; as many groups at once as fit the chip (with a margin), the rest in turn.
-        const int budget = cus - 16;
+        // overflows the LDS; as many groups at once as fit the chip, the rest in turn.  (No CUs are kept back: a head of 2048
+        // units takes 128 of them, and two of its groups side by side halve the backward pass.)
+        const int budget = cus;
         const int bts[3] = {16, 8, 4};
         for (int spills_ok = 0; spills_ok < 2 && !pl.e; ++spills_ok)   // (a kernel with a few registers in scratch memory only if no tile is free of them)
         for (int bi = 0; bi < 3 && !pl.e; ++bi) {
