@@ -182,7 +182,17 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
     };
     // The three streams of a step advance by whole time steps: their bases are carried as pointers (a product of the
     // step index and a 64-bit stride per stream and step is a dozen scalar instructions).
-    const char* wx_ptr = wx_g + (size_t)((kLongChain ? 1 : 2) < T ? (kLongChain ? 1 : 2) : (T > 0 ? T - 1 : 0)) * wx_step;   // Wx of the step fetched next
+    const char* wx_ptr = wx_g + (size_t)(2 < T ? 2 : (T > 0 ? T - 1 : 0)) * wx_step;   // Wx of the step fetched next (slot 2 = Wx_3)
+    // Long chain: Wx_{t+1} is requested at the end of step t-1, AHEAD of that step's stores in the wave's memory queue.  A
+    // wave's vector memory operations retire in order: a load issued behind the stores of the step before could not be
+    // waited for without waiting for their acknowledgements as well, which tied the step to the write latency of the
+    // memory system (sequences whose buffers outgrow the last-level cache ran 15 % slower per step, the LSTM 25 %).
+    i32x4 pre_next[NCH_IN];
+    if constexpr (kLongChain) {
+        const rsrc_t rs2 = make_rsrc(wx_g + (size_t)(T > 1 ? 1 : 0) * wx_step);
+#pragma unroll
+        for (int k2 = 0; k2 < NCH_IN; ++k2) pre_next[k2] = T > 0 ? __builtin_amdgcn_raw_buffer_load_b128(rs2, cin_g[k2], 0, 0) : i32x4{0, 0, 0, 0};
+    }
     char* st_ptr = st_g;   // state slot of the step before the current one (slot 0 is written directly, not through the image)
     char* c_ptr = c_g;     // saved values of the current step
     auto copy_out_store = [&](int j, const i32x4 (&vs)[NCH_ST]) {
@@ -211,7 +221,7 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
         const char* hrow = hbuf + (par ^ 1) * BUF + lds_row;
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt) hB[kt] = *(const bf16x8*)(hrow + (size_t)(kt * 32 + lm.quad * 8) * 2);
-        i32x4 pre[NCH_IN], vs[NCH_ST];
+        i32x4 vs[NCH_ST];
         float wx[G][PP];
         auto side_reads = [&]() {
             const char* im = in_img + par * L.in_pitch + l_in;
@@ -225,14 +235,11 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
                     if (!(CELL == CELL_GRU && g == 2)) wx[g][i] += bias[g][i];
         };
         if constexpr (!kLongChain) side_reads();
-        {
-            const int ahead = kLongChain ? t : t + 1;   // slot of Wx_{t+1} / Wx_{t+2} (the last steps fetch the last slot again)
+        if constexpr (!kLongChain) {
+            const int ahead = t + 1;   // slot of Wx_{t+2} (the last steps fetch the last slot again)
             const rsrc_t rsn = make_rsrc(wx_ptr);
             wx_ptr += ahead < T - 1 ? wx_step : 0;
-            if constexpr (kLongChain) {
-#pragma unroll
-                for (int k2 = 0; k2 < NCH_IN; ++k2) pre[k2] = __builtin_amdgcn_raw_buffer_load_b128(rsn, cin_g[k2], 0, 0);
-            } else if constexpr (PAR == 1) {
+            if constexpr (PAR == 1) {
 #pragma unroll
                 for (int k2 = 0; k2 < NCH_IN; ++k2) preB[k2] = __builtin_amdgcn_raw_buffer_load_b128(rsn, cin_g[k2], 0, 0);
             } else {
@@ -265,7 +272,7 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
             pin_order();
             char* im = in_img + (par ^ 1) * L.in_pitch;
 #pragma unroll
-            for (int k2 = 0; k2 < NCH_IN; ++k2) *(i32x4*)(im + cin_l[k2]) = pre[k2];
+            for (int k2 = 0; k2 < NCH_IN; ++k2) *(i32x4*)(im + cin_l[k2]) = pre_next[k2];
         }
         pin_order();
 #pragma unroll
@@ -276,6 +283,12 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
         // ---- point-wise function; the step's outputs go to their image (they leave for HBM during the next step)
 #pragma unroll
         for (int g = 0; g < G; ++g) compact_tile<BT>(acc[g]);
+        if constexpr (kLongChain) {   // Wx_{t+2}: slot t + 1 (the last steps fetch the last slot again)
+            const rsrc_t rsn = make_rsrc(wx_ptr);
+            wx_ptr += t + 1 < T - 1 ? wx_step : 0;
+#pragma unroll
+            for (int k2 = 0; k2 < NCH_IN; ++k2) pre_next[k2] = __builtin_amdgcn_raw_buffer_load_b128(rsn, cin_g[k2], 0, 0);
+        }
         char* oimg = out_img + par * OUT_PITCH;
         const rsrc_t rs_c = make_rsrc(c_ptr);
         c_ptr += c_step;
