@@ -540,7 +540,7 @@ int bwd_impl(const flashrnn_desc_t* d, const void* Wx, const void* R, const void
             rp.states = (const float*)((const char*)states + (size_t)r0 * st_step);
             rp.cache = ws + rl.window_off; rp.steps = steps; rp.B = d->B; rp.NH = d->NH; rp.D = d->D;
             void* args[] = {&rp};
-            const dim3 grid((unsigned)((steps * d->B + 63) / 64), (unsigned)((d->D + 63) / 64), (unsigned)d->NH);
+            const dim3 grid((unsigned)((steps * d->B + kRecomputeCols - 1) / kRecomputeCols), (unsigned)((d->D + 63) / 64), (unsigned)d->NH);
             if (hipLaunchKernel(table_for(d->cell, d->io_dtype).recompute, grid, dim3(256), args, 0, stream) != hipSuccess) return FLASHRNN_ERR_LAUNCH;
             cache = ws + rl.window_off;
         } else if (!recompute) {
