@@ -149,6 +149,19 @@ def test_largest_head_takes_a_whole_xcd():
     assert api.flashrnn_plan(d)[0] == 64 and api.flashrnn_plan_kernel(d)[2] == 32
 
 
+def test_backward_groups_take_whole_xcds_and_the_whole_chip_where_they_need_them():
+    """A head of 1024 units needs every CU of an XCD per group in both directions (four 4-row groups of a 16-row batch side by
+    side, not one 16-row group); two 8-row groups of a 2048-unit head need all 256 CUs."""
+    d = api.make_desc(CELL_LSTM, 8, 16, 1, 1024, api.FLASHRNN_BF16)
+    for bwd in (False, True):
+        staged, bt, split = api.flashrnn_plan_kernel(d, bwd)
+        assert (staged, bt, split) == (0, 4, 32) and api.flashrnn_plan(d, bwd)[0] == 128
+    d = api.make_desc(CELL_LSTM, 8, 16, 1, 2048, api.FLASHRNN_BF16)
+    assert api.flashrnn_plan_kernel(d, True)[1:] == (8, 128) and api.flashrnn_plan(d, True)[0] == 256
+    w = Workload("lstm_D1024_B16", CELL_LSTM, 5, 16, 1, 1024, "bf16", True, bias="uniform0.1", init="uniform0.1", seed=10)
+    _check(w, with_dlast=True)
+
+
 @pytest.mark.parametrize("cell,D,B,NH", [(CELL_LSTM, 1040, 5, 1), (CELL_LSTM, 1280, 19, 1), (CELL_LSTM, 1536, 6, 2), (CELL_LSTM, 2048, 9, 1),
                                          (CELL_LSTM, 2688, 5, 1), (CELL_SLSTM, 1536, 7, 1), (CELL_SLSTM, 2048, 16, 1), (CELL_GRU, 1280, 12, 1),
                                          (CELL_GRU, 2688, 3, 1), (CELL_ELMAN, 2048, 4, 1), (CELL_GRU4, 1536, 4, 1)])
