@@ -857,11 +857,29 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
 
         // inputs of a step: saved values, the states the cell's Jacobian needs, external dh
         float cv[EB][NC][PP], sc[EB][S][PP], sp[EB][S][PP], dh_ext[EB][PP];
-        auto load_step = [&](int t, float (&cv_)[EB][NC][PP], float (&sc_)[EB][S][PP], float (&sp_)[EB][S][PP], float (&dh_)[EB][PP]) {
-            const rsrc_t c_t = make_rsrc(c_g + (size_t)(t - 1) * c_step);
-            const rsrc_t st_t = make_rsrc(st_g + (size_t)t * st_step);
-            const rsrc_t st_p = make_rsrc(st_g + (size_t)(t - 1) * st_step);
-            const rsrc_t dh_t = make_rsrc(dh_g + (size_t)(t - 1) * dh_step);
+        // The streams move by whole time steps: their bases are carried as pointers (a product of the step index and a 64-bit
+        // stride per stream and step is a dozen scalar instructions, in a step that is one chain of dependent instructions:
+        // measured 3 % of the step on sLSTM heads of 256 units, 10 % on GRU heads).  The three input
+        // streams point at the step that is loaded next; `more` = a further (earlier) step follows, else step 1 is loaded again.
+        // (Kernels with contraction slices, and those with three waves per SIMD, have no register to spare: they keep forming the bases from the step
+        // index, whose temporaries are short-lived.)
+        constexpr bool kRunning = KS == 1 && MAXW < 12;
+        const int t_last = T > 0 ? T - 1 : 0;
+        const char* c_run = c_g + (size_t)t_last * c_step;      // saved values of that step
+        const char* st_run = st_g + (size_t)t_last * st_step;   // states before it (the states after it: one step further on)
+        const char* dh_run = dh_g + (size_t)t_last * dh_step;
+        char* dwx_run = dwx_g + (size_t)t_last * wx_step;       // dWx (and the GRU's candidate-gate gradient) of the current step
+        char* dgn_run = dgn_g + (size_t)t_last * dh_step;
+        const uint32_t st_after = (uint32_t)st_step;
+        auto load_step = [&](int t, bool more, float (&cv_)[EB][NC][PP], float (&sc_)[EB][S][PP], float (&sp_)[EB][S][PP], float (&dh_)[EB][PP]) {
+            const rsrc_t c_t = make_rsrc(kRunning ? c_run : c_g + (size_t)(t - 1) * c_step);
+            const rsrc_t st_p = make_rsrc(kRunning ? st_run : st_g + (size_t)(t - 1) * st_step);
+            const rsrc_t dh_t = make_rsrc(kRunning ? dh_run : dh_g + (size_t)(t - 1) * dh_step);
+            if constexpr (kRunning) {
+                c_run -= more ? c_step : 0;
+                st_run -= more ? st_step : 0;
+                dh_run -= more ? dh_step : 0;
+            }
 #pragma unroll
             for (int eb = 0; eb < EB; ++eb) {
 #pragma unroll
@@ -873,7 +891,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
             }
 #pragma unroll
             for (int s = 0; s < S; ++s) {
-                if (!cell_uses_h_prev(CELL) && s > 0 && s < 3) load_io_r<false, PP>(st_t, voff_st + eb * 64, s * st_state, sc_[eb][s]);
+                if (!cell_uses_h_prev(CELL) && s > 0 && s < 3) load_io_r<false, PP>(st_p, voff_st + eb * 64, s * st_state + st_after, sc_[eb][s]);
                 else
 #pragma unroll
                     for (int i = 0; i < PP; ++i) sc_[eb][s][i] = 1.0f;
@@ -885,7 +903,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
             load_io_r<BF16, PP>(dh_t, voff_dh + eb * 16 * ESZ, 0, dh_[eb]);
             }
         };
-        if ((KS == 1 || ks == 0) && T > 0) load_step(T, cv, sc, sp, dh_ext);
+        if ((KS == 1 || ks == 0) && T > 0) load_step(T, T > 1, cv, sc, sp, dh_ext);
 
         FRNN_TRACE_RESET();
         for (int t = T; t >= 1; --t) {
@@ -893,9 +911,9 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
             if (KS == 1 || ks == 0) {
                 // ---- prefetch the inputs of the next (earlier) step; they are pinned after the MFMA phase
                 // (with several workgroups per group they are issued behind the poll for dg_t: see the forward kernel)
-                if constexpr (!MULTI) load_step(t > 1 ? t - 1 : 1, cvn, scn, spn, dhn);
+                if constexpr (!MULTI) load_step(t > 1 ? t - 1 : 1, t > 2, cvn, scn, spn, dhn);
                 // ---- point-wise Jacobians
-                const rsrc_t dwx_t = make_rsrc(dwx_g + (size_t)(t - 1) * wx_step);
+                const rsrc_t dwx_t = make_rsrc(kRunning ? dwx_run : dwx_g + (size_t)(t - 1) * wx_step);
 #pragma unroll
                 for (int eb = 0; eb < EB; ++eb) {
                     float dwx[G][PP], dg[G][PP];
@@ -929,7 +947,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
                         for (int g2 = 0; g2 < G; ++g2) store_io_r<BF16, PP>(dwx_t, soff_wx + eb * 16 * ESZ, g2 * wx_gate, dwx[g2]);
                     }
                     if constexpr (CELL == CELL_GRU)
-                        store_io_r<BF16, PP>(make_rsrc(dgn_g + (size_t)(t - 1) * dh_step), soff_dh + eb * 16 * ESZ, 0, dg[2]);
+                        store_io_r<BF16, PP>(make_rsrc(kRunning ? dgn_run : dgn_g + (size_t)(t - 1) * dh_step), soff_dh + eb * 16 * ESZ, 0, dg[2]);
                 }
             }
             // ---- dh_{t-1} += R dg_t on the matrix cores; NA accumulators per unit block break the dependent chain
@@ -957,7 +975,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
                 FRNN_TRACE_SPLIT(7, 2);
                 __syncthreads();
                 FRNN_TRACE_MARK(3);
-                if (KS == 1 || ks == 0) load_step(t > 1 ? t - 1 : 1, cvn, scn, spn, dhn);
+                if (KS == 1 || ks == 0) load_step(t > 1 ? t - 1 : 1, t > 2, cvn, scn, spn, dhn);
                 i32x4 out_v[NBO];
                 if constexpr (kOutRows) {
 #pragma unroll
@@ -976,7 +994,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
                     for (int j = 0; j < KC; ++j) a4[0][(kc + j) % NA] = OP::mfma(Rf[0][kc + j], gB[j], a4[0][(kc + j) % NA]);
                 }
                 if constexpr (kOutRows) {
-                    const rsrc_t dwx_rows = make_rsrc(dwx_g + (size_t)(t - 1) * wx_step);
+                    const rsrc_t dwx_rows = make_rsrc(kRunning ? dwx_run : dwx_g + (size_t)(t - 1) * wx_step);
 #pragma unroll
                     for (int j = 0; j < NBO; ++j) __builtin_amdgcn_raw_buffer_store_b128(out_v[j], dwx_rows, out_g[j], 0, 0);
                 }
@@ -1011,6 +1029,10 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
                     for (int s = 0; s < S; ++s) { sc[eb][s][i] = scn[eb][s][i]; sp[eb][s][i] = spn[eb][s][i]; }
                     dh_ext[eb][i] = dhn[eb][i];
                 }
+            }
+            if constexpr (kRunning) {
+                dwx_run -= wx_step;
+                dgn_run -= dh_step;
             }
             if constexpr (MULTI) FRNN_TRACE_MARK(5);
         }
