@@ -60,6 +60,9 @@ static const KernelEntry kEntries[] = {
     FRNN_BL(10, 4) FRNN_BL(12, 4) FRNN_BL(16, 4) FRNN_BL(20, 4) FRNN_BL(21, 4)
 #else
     FRNN_FB(4, 1, 16, 0, 4) FRNN_FB(8, 1, 16, 0, 4) FRNN_FB(16, 1, 16, 0, 4) FRNN_FB(32, 1, 16, 0, 8)
+    // small batches: tiles of 4 and 8 rows (a quarter / half of the point-wise work and of the lane-wise traffic per workgroup)
+    FRNN_FB(4, 1, 8, 0, 4) FRNN_FB(8, 1, 8, 0, 4) FRNN_FB(16, 1, 8, 0, 4) FRNN_FB(32, 1, 8, 0, 8)
+    FRNN_FB(4, 1, 4, 0, 4) FRNN_FB(8, 1, 4, 0, 4) FRNN_FB(16, 1, 4, 0, 4) FRNN_FB(32, 1, 4, 0, 8)
     FRNN_FB(16, 1, 16, 1, 4) FRNN_FB(32, 1, 16, 1, 4) FRNN_FB(48, 1, 16, 1, 4) FRNN_FB(64, 1, 16, 1, 4)
     FRNN_FB(8, 4, 16, 1, 4)
 #endif

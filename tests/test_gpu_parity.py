@@ -86,6 +86,15 @@ def test_backward_contraction_split_over_waves(cell, D, ebk):
     w = Workload(f"ebk{ebk}_{cell}_D{D}", cell, 8, 10, 2, D, "bf16", True, bias="uniform0.1", init="uniform0.1", seed=D + ebk)
     _check(w, {"FLASHRNN_EBK": str(ebk)}, with_dlast=True)
 
+@pytest.mark.parametrize("cell", CELLS)
+@pytest.mark.parametrize("bt", [16, 8, 4])
+@pytest.mark.parametrize("D", [48, 112])
+def test_batch_tiles_with_f32_io(cell, bt, D):
+    """f32 I/O (f32 MFMA, rel 1e-5): the same three tile heights; 21 rows = ragged last tile, head sizes that pad the contraction axis."""
+    w = Workload(f"f32_bt{bt}_{cell}_D{D}", cell, 10, 21, 2, D, "f32", True, bias="forget3" if cell in (CELL_LSTM, CELL_SLSTM) else "uniform0.1",
+                 init="uniform0.1", seed=bt + D)
+    _check(w, {"FLASHRNN_BT": str(bt)}, with_dlast=True)
+
 
 @pytest.mark.parametrize("cell", CELLS)
 @pytest.mark.parametrize("bt", [8, 4])
