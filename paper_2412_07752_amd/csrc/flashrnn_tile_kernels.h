@@ -430,21 +430,27 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
     bool out_real, cout_img, c_wave[NCC];
     const uint32_t cpr_io = (uint32_t)D / 8;
     const bool st_wave = (uint32_t)w * 64 < (uint32_t)BT * NSB * (D / 4), dh_wave = (uint32_t)w * 64 < (uint32_t)BT * cpr_io;
+    // The input images are plain arrays of rows whose pitch (D records, D floats, D bf16) is a multiple of 256 bytes for the
+    // larger heads: the rows of the batch slots would fall on the same LDS banks, and a wave reads 4 (8) of them with one
+    // instruction.  So the chunks of slot r's row are stored rotated by 4 r chunks (64 r bytes, modulo the row): a thread's
+    // slot in the image is fixed by the loads that write LDS directly, which global chunk it fetches is free.
+    auto rotated = [](uint32_t ch, uint32_t slot, uint32_t cpr) { return (ch + (4u * slot) % cpr) % cpr; };          // row position of chunk ch
+    auto unrotated = [](uint32_t pos, uint32_t slot, uint32_t cpr) { return (pos + cpr - (4u * slot) % cpr) % cpr; }; // chunk at row position pos
+    const uint32_t cpr_c = (uint32_t)D * REC / 16, cpr_st = (uint32_t)D / 4;
     {
-        const uint32_t cpr_c = (uint32_t)D * REC / 16, nch_c = (uint32_t)BT * cpr_c;
+        const uint32_t nch_c = (uint32_t)BT * cpr_c;
 #pragma unroll
         for (int k2 = 0; k2 < NCC; ++k2) {   // records: a row of the image is the D records of one batch row
-            const uint32_t idx = tid + k2 * NT, row = idx / cpr_c, ch = idx % cpr_c, brow = q * BT + row;
+            const uint32_t idx = tid + k2 * NT, row = idx / cpr_c, ch = unrotated(idx % cpr_c, row, cpr_c), brow = q * BT + row;
             cc_g[k2] = (idx < nch_c && brow < (uint32_t)B) ? (brow * HD) * REC + ch * 16 : kDrop;
             c_wave[k2] = (uint32_t)w * 64 + k2 * NT < nch_c;   // (a wave beyond the image must not land zeros behind it)
         }
         {   // state rows: row = state * BT + slot
-            const uint32_t cpr_st = (uint32_t)D / 4;
-            const uint32_t row = tid / cpr_st, ch = tid % cpr_st, sidx = row / BT, brow = q * BT + row % BT;
+            const uint32_t row = tid / cpr_st, ch = unrotated(tid % cpr_st, row % BT, cpr_st), sidx = row / BT, brow = q * BT + row % BT;
             cst_g = (row < (uint32_t)BT * NSB && brow < (uint32_t)B) ? (SB0 + sidx) * st_state + (brow * HD) * 4 + ch * 16 : kDrop;
         }
         {   // dh rows: row = slot
-            const uint32_t row = tid / cpr_io, ch = tid % cpr_io, brow = q * BT + row;
+            const uint32_t row = tid / cpr_io, ch = unrotated(tid % cpr_io, row, cpr_io), brow = q * BT + row;
             cdh_g = (row < (uint32_t)BT && brow < (uint32_t)B) ? (brow * HD) * ESZ + ch * 16 : kDrop;
         }
         {   // output rows: row = slot * GO + g; g < G goes to dWx, g == G to the candidate-gradient buffer
@@ -462,9 +468,14 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
         }
     }
     // this lane's places in the images
-    const uint32_t l_c = ((uint32_t)lm.bslot * D + e0) * REC;
-    const uint32_t l_st = L.st_off + ((uint32_t)lm.bslot * D + e0) * 4;
-    const uint32_t l_dh = L.dh_off + ((uint32_t)lm.bslot * D + e0) * ESZ;
+    // (byte o of slot r's row lies in the chunk at row position rotated(o / 16); a lane's PP values of a state or of dh share
+    // a chunk, its PP records need not)
+    auto in_row = [&](uint32_t o, uint32_t cpr) { return rotated(o / 16, (uint32_t)lm.bslot, cpr) * 16 + o % 16; };
+    uint32_t l_c[PP];
+#pragma unroll
+    for (int i = 0; i < PP; ++i) l_c[i] = (uint32_t)lm.bslot * D * REC + in_row((e0 + i) * REC, cpr_c);
+    const uint32_t l_st = L.st_off + (uint32_t)lm.bslot * D * 4 + in_row(e0 * 4, cpr_st);
+    const uint32_t l_dh = L.dh_off + (uint32_t)lm.bslot * D * ESZ + in_row(e0 * ESZ, cpr_io);
     const uint32_t l_out = (uint32_t)lm.bslot * L.rp_io + e0 * ESZ;
     const uint32_t lds_row = (uint32_t)lm.bslot * L.hp;
 
@@ -507,7 +518,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
 #pragma unroll
         for (int i = 0; i < PP; ++i) {
             float rec[NC];
-            take_record_lds<CT::RS, NC>(img + l_c + i * REC, rec);
+            take_record_lds<CT::RS, NC>(img + l_c[i], rec);
 #pragma unroll
             for (int c2 = 0; c2 < NC; ++c2) cv[c2][i] = rec[c2];
         }
