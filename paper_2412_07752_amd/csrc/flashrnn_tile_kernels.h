@@ -124,7 +124,9 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
             const uint32_t idx = tid + k2 * NT, row = idx / cpr_io, ch = idx % cpr_io, brow = q * BT + row / G, g = row % G;
             const bool in = row < (uint32_t)BT * G;
             cin_g[k2] = (in && brow < (uint32_t)B) ? ((brow * G + g) * HD) * ESZ + ch * 16 : kDrop;
-            cin_l[k2] = in ? row * L.rp_io + ch * 16 : L.in_bytes + tid16 + k2 * NT16;
+            // (image rows in the order gate, slot: the rows that one instruction reads -- one gate, all slots -- are then one
+            // pitch apart, 16 banks; in memory order, slot * G + gate, they would be G pitches apart: the same banks for G = 4)
+            cin_l[k2] = in ? (g * BT + row / G) * L.rp_io + ch * 16 : L.in_bytes + tid16 + k2 * NT16;
         }
 #pragma unroll
         for (int k2 = 0; k2 < NCH_ST; ++k2) {
@@ -134,9 +136,9 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
             cst_l[k2] = in ? row * L.rp_st + ch * 16 : L.st_bytes + tid16 + k2 * NT16;
         }
     }
-    // this lane's places: inputs row = slot*G + g, states row = s*BT + slot; the saved-values records (16 bytes per
+    // this lane's places: inputs row = g*BT + slot, states row = s*BT + slot; the saved-values records (16 bytes per
     // lane, 256 contiguous bytes per batch row and wave) go to HBM straight from the lanes
-    const uint32_t l_in = (uint32_t)lm.bslot * G * L.rp_io + e0 * ESZ;
+    const uint32_t l_in = (uint32_t)lm.bslot * L.rp_io + e0 * ESZ;
     const uint32_t l_st = (uint32_t)lm.bslot * L.rp_st + e0 * 4;
     const uint32_t voff_c = (row_valid && p.cache != nullptr) ? ((uint32_t)bb * HD + e0) * REC : kDrop;
     const uint32_t lds_row = (uint32_t)lm.bslot * L.hp;
@@ -226,7 +228,7 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
         auto side_reads = [&]() {
             const char* im = in_img + par * L.in_pitch + l_in;
 #pragma unroll
-            for (int g = 0; g < G; ++g) load_io<true, PP>(im + (uint32_t)g * L.rp_io, 0, wx[g]);
+            for (int g = 0; g < G; ++g) load_io<true, PP>(im + (uint32_t)g * BT * L.rp_io, 0, wx[g]);
             copy_out_load(par ^ 1, vs);
 #pragma unroll
             for (int g = 0; g < G; ++g)     // the bias joins the inputs here, off the step's tail (GRU's candidate bias
