@@ -378,7 +378,10 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
     constexpr int NSB = CELL == CELL_SLSTM ? 2 : CELL == CELL_ELMAN ? 0 : 1;   // state rows the Jacobian needs per time level ...
     constexpr int SB0 = cell_uses_h_prev(CELL) ? 0 : 1;   // ... starting at this state
     constexpr int GO = CELL == CELL_GRU ? G + 1 : G;  // output rows per batch row: dWx (+ the recurrent-side candidate gradient)
-    constexpr int NA = EBK == 1 ? 4 : (EBK == 2 ? 2 : 1);   // accumulators per block: independent MFMAs in flight
+    // accumulators per block: independent MFMAs in flight.  A wave that has its SIMD to itself (heads of up to 64 units) issues
+    // an MFMA every 16 clocks, so two chains keep dependent ones 32 apart, which a 4-pass MFMA allows; four chains cost eight
+    // more additions and eight more register moves per step there (12 x 64 backward: -6 %).  With two waves per SIMD four measured 1 % better.
+    constexpr int NA = EBK == 1 ? (MAXW <= 4 ? 2 : 4) : (EBK == 2 ? 2 : 1);
     constexpr uint32_t kDrop = 0x80000000u;
     constexpr uint32_t REC = CT::RS * ESZ;
     static_assert(BT == 4 || BT == 8, "batch tiles of 4 or 8 rows");
