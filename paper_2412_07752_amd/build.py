@@ -14,8 +14,11 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 OUT = os.path.join(HERE, "libflashrnn.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+# -amdgpu-mfma-vgpr-form: MFMA results go to ordinary VGPRs.  Left to itself the compiler puts the accumulators of kernels with
+# few waves into AGPRs and copies every result out again (16 moves per time step in the small tile kernels), and the kernels that
+# hold R in all 512 registers spill less with it.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-I", INCLUDE, "-I", CSRC]
+         "-mllvm", "-amdgpu-mfma-vgpr-form", "-I", INCLUDE, "-I", CSRC]
 
 
 def sources():

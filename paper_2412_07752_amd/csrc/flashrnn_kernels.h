@@ -870,11 +870,13 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
         const char* dh_run = dh_g + (size_t)t_last * dh_step;
         char* dwx_run = dwx_g + (size_t)t_last * wx_step;       // dWx (and the GRU's candidate-gate gradient) of the current step
         char* dgn_run = dgn_g + (size_t)t_last * dh_step;
-        const uint32_t st_after = (uint32_t)st_step;
         auto load_step = [&](int t, bool more, float (&cv_)[EB][NC][PP], float (&sc_)[EB][S][PP], float (&sp_)[EB][S][PP], float (&dh_)[EB][PP]) {
             const rsrc_t c_t = make_rsrc(kRunning ? c_run : c_g + (size_t)(t - 1) * c_step);
             const rsrc_t st_p = make_rsrc(kRunning ? st_run : st_g + (size_t)(t - 1) * st_step);
             const rsrc_t dh_t = make_rsrc(kRunning ? dh_run : dh_g + (size_t)(t - 1) * dh_step);
+            // the states after the step: one step further on -- as a uniform offset on the same base where the bases are carried
+            const rsrc_t st_t = kRunning ? st_p : make_rsrc(st_g + (size_t)t * st_step);
+            const uint32_t st_after = kRunning ? (uint32_t)st_step : 0u;
             if constexpr (kRunning) {
                 c_run -= more ? c_step : 0;
                 st_run -= more ? st_step : 0;
@@ -891,7 +893,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_kernel(const KernelParams p) {
             }
 #pragma unroll
             for (int s = 0; s < S; ++s) {
-                if (!cell_uses_h_prev(CELL) && s > 0 && s < 3) load_io_r<false, PP>(st_p, voff_st + eb * 64, s * st_state + st_after, sc_[eb][s]);
+                if (!cell_uses_h_prev(CELL) && s > 0 && s < 3) load_io_r<false, PP>(st_t, voff_st + eb * 64, s * st_state + st_after, sc_[eb][s]);
                 else
 #pragma unroll
                     for (int i = 0; i < PP; ++i) sc_[eb][s][i] = 1.0f;
