@@ -124,12 +124,12 @@ def flashrnn_plan(desc, backward=False):
 
 
 def flashrnn_plan_kernel(desc, backward=False):
-    """(staged, batch tile rows, workgroups per group) of the kernel that plan uses."""
+    """(staged: 0 / 1 / 2 = staged with the deep fetch, batch tile rows, workgroups per group) of the kernel that plan uses."""
     a, b, c = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
     rc = lib().flashrnn_plan_kernel(ctypes.byref(desc), int(bool(backward)), ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
     if rc != FLASHRNN_OK:
         raise FlashRNNError(rc, "flashrnn_plan_kernel")
-    return bool(a.value), b.value, c.value
+    return a.value, b.value, c.value
 
 
 def flashrnn_profile_enable(on):

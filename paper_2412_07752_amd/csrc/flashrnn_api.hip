@@ -126,6 +126,11 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
     const int force_kind = env_int("FLASHRNN_KIND", -1);     // kernel family (KernelEntry::tile)
     const int force_eb = env_int("FLASHRNN_EB", 0);          // blocks of 16 units per wave (one workgroup per group)      // groups in flight when groups are split (testing the group loop)
     Plan pl;
+    // What the backward pass reads and writes per (t, row, unit): saved values, states, dH, dWx.  Beyond the last-level cache
+    // (256 MB; the forward pass has just written most of it) its inputs come from HBM, and small heads take the kernels that fetch deeper.
+    const double bwd_bytes = ((double)record_slots(d->cell) * io_size(d->io_dtype) + (double)num_states(d->cell) * 4 + (double)(1 + G) * io_size(d->io_dtype)) *
+                             (double)d->T * d->B * d->NH * d->D;
+    const bool deep = bwd && env_int("FLASHRNN_DEEP_FETCH", bwd_bytes > 224.0 * 1024 * 1024 ? 1 : 0) != 0;
 
     if (force_multi < 1) {
         // Every (batch tile, kernel) pair that can run the shape gets a cost: rounds of workgroups over the CUs
@@ -146,6 +151,7 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
             if (force_ebk && bwd && e.tile == 1 && e.eb != force_ebk) continue;
             const int dk = e.KT * kstep, nw = e.tile == 1 ? units16 : units16 / e.eb;
             if (e.exact && dk != kdim) continue;
+            if ((e.exact == 2) && !deep) continue;
             size_t smem = (size_t)2 * e.BT * (dk + (bf ? 8 : 4)) * (bf ? 2 : 4);
             if (e.tile == 1 && bwd) {
                 const int nsb = d->cell == FLASHRNN_SLSTM ? 2 : d->cell == FLASHRNN_ELMAN ? 0 : 1, go = d->cell == FLASHRNN_GRU ? G + 1 : G;
@@ -164,6 +170,7 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
             if (e.tile == 0) rel *= 1.0 + 0.05 * (e.eb - 1);       // thin waves overlap better
             rel *= 1.0 + 0.02 * (dk - kdim) / (double)kstep;       // padded k-steps are wasted MFMAs
             if (e.exact) rel *= 0.99;                              // compile-time LDS layout: fewer address instructions
+            if (e.exact == 2) rel *= 0.9;                          // (only a candidate when the inputs come from HBM: -10 % there)
             const double cost = rounds * rel;
             if (!best || cost < best_cost) { best = &e; best_cost = cost; best_smem = smem; }
         }
@@ -634,7 +641,7 @@ int flashrnn_plan_kernel(const flashrnn_desc_t* d, int backward, int* staged, in
     Plan pl;
     rc = make_plan(d, backward ? 1 : 0, &pl);
     if (rc != FLASHRNN_OK) return rc;
-    if (staged) *staged = pl.e->tile != 0;
+    if (staged) *staged = pl.e->tile != 0 ? (pl.e->exact == 2 ? 2 : 1) : 0;
     if (batch_tile) *batch_tile = pl.e->BT;
     if (split) *split = pl.P;
     return FLASHRNN_OK;

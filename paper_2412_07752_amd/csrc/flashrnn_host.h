@@ -17,7 +17,8 @@ struct KernelEntry {
     int maxw;   // launch bound in waves
     int eb;     // blocks of 16 units per wave
     int tile;   // 0: generic kernel, 1: staged tile kernel (bf16, one workgroup per group, BT < 16)
-    int exact;  // 1: only for heads of exactly the kernel's contraction length (compile-time LDS layout)
+    int exact;  // 1: only for heads of exactly the kernel's contraction length (compile-time LDS layout); 2: such a kernel that
+                // fetches its inputs four steps ahead (for inputs that come from HBM)
     const void* fn;
 };
 

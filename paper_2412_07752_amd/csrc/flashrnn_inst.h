@@ -29,6 +29,10 @@ namespace flashrnn {
 #define FRNN_BTL(KT, EBK, BT, MAXW) \
     {FRNN_CELL, FRNN_BF16, 1, (KT) * FRNN_G, 1, BT, 0, MAXW, EBK, 1, 1, (const void*)&bwd_tile_kernel<FRNN_CELL, (KT) * FRNN_G / (EBK), EBK, BT, MAXW, true>}, \
     {FRNN_CELL, FRNN_BF16, 1, (KT) * FRNN_G, 1, BT, 0, MAXW, EBK, 1, 0, (const void*)&bwd_tile_kernel<FRNN_CELL, (KT) * FRNN_G / (EBK), EBK, BT, MAXW, false>},
+// ... and, for heads of exactly 32 or 64 units, a third one that requests its inputs four steps ahead through registers
+// (taken when they will come from HBM; KernelEntry::exact = 2)
+#define FRNN_BTLD(KT, EBK, BT, MAXW) \
+    {FRNN_CELL, FRNN_BF16, 1, (KT) * FRNN_G, 1, BT, 0, MAXW, EBK, 1, 2, (const void*)&bwd_tile_kernel<FRNN_CELL, (KT) * FRNN_G / (EBK), EBK, BT, MAXW, true, true>},
 #define FRNN_TILE(KT, EBK, BT, MAXW) FRNN_FT(KT, BT, MAXW) FRNN_B(KT, 1, BT, 0, MAXW, 1) FRNN_BTL(KT, EBK, BT, MAXW)
 // the largest heads: one block of 16 units per workgroup, 4 contraction slices, one wave per SIMD
 #define FRNN_FL(KT, BT) FRNN_F(KT, 4, BT, 1, 4, 1)
@@ -38,8 +42,8 @@ namespace flashrnn {
 
 static const KernelEntry kEntries[] = {
 #if FRNN_BF16
-    FRNN_FB(1, 1, 16, 0, 4) FRNN_TILE(1, 1, 8, 4) FRNN_TILE(1, 1, 4, 4)
-    FRNN_FB(2, 1, 16, 0, 4) FRNN_TILE(2, 2, 8, 4) FRNN_TILE(2, 2, 4, 4) FRNN_BTL(2, 1, 8, 4) FRNN_BTL(2, 1, 4, 4)
+    FRNN_FB(1, 1, 16, 0, 4) FRNN_TILE(1, 1, 8, 4) FRNN_TILE(1, 1, 4, 4) FRNN_BTLD(1, 1, 8, 4) FRNN_BTLD(1, 1, 4, 4)
+    FRNN_FB(2, 1, 16, 0, 4) FRNN_TILE(2, 2, 8, 4) FRNN_TILE(2, 2, 4, 4) FRNN_BTL(2, 1, 8, 4) FRNN_BTL(2, 1, 4, 4) FRNN_BTLD(2, 1, 8, 4) FRNN_BTLD(2, 1, 4, 4)
     FRNN_FB(4, 1, 16, 0, 8) FRNN_TILE(4, 2, 8, 8) FRNN_TILE(4, 2, 4, 8) FRNN_BTL(4, 1, 8, 8) FRNN_BTL(4, 1, 4, 8) FRNN_BTL(4, 4, 8, 8) FRNN_BTL(4, 4, 4, 8)
     FRNN_FB(6, 1, 16, 0, 12) FRNN_TILE(6, 3, 8, 12) FRNN_TILE(6, 3, 4, 12) FRNN_BTL(6, 1, 8, 12) FRNN_BTL(6, 1, 4, 12)
     FRNN_FBE(4, 16, 4, 2) FRNN_FBE(4, 8, 4, 2) FRNN_FBE(4, 4, 4, 2)
@@ -80,6 +84,7 @@ inline KernelTable make_table() {
 #undef FRNN_BL
 #undef FRNN_FT
 #undef FRNN_BTL
+#undef FRNN_BTLD
 #undef FRNN_TILE
 
 }  // namespace flashrnn

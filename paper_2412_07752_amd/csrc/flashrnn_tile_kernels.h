@@ -367,7 +367,7 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
 // during step t's MFMAs.
 // EXACT: as in the forward kernel (the head has exactly KTW * EBK * 32 / G units: compile-time LDS pitches, and a
 // compile-time step parity with the time loop unrolled by two).
-template <int CELL, int KTW, int EBK, int BT, int MAXW, bool EXACT>
+template <int CELL, int KTW, int EBK, int BT, int MAXW, bool EXACT, bool DEEP = false>
 __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams p) {
     using CT = CellTraits<CELL>;
     using OP = Operand<true>;
@@ -517,6 +517,35 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
         if (st_wave) load_chunk_to_lds(rst, img + L.st_off, cst_g);
         if (dh_wave) load_chunk_to_lds(rdh, img + L.dh_off, cdh_g);
     };
+    // DEEP (a kernel of its own for heads of up to 64 units, steps of 0.4 us; the host takes it when the inputs exceed the
+    // last-level cache and will come from HBM): the same chunks through registers instead, requested FOUR steps before their
+    // step and written into the image two steps later.  With the loads that write LDS directly the request can only go out
+    // once its image is free, two steps before the data is used -- less than the latency of HBM, which these short steps then
+    // wait for (12 x 64, B = 16: 0.40 us per step up to T = 512, 0.54 us from T = 1024 on; through registers 0.48 us).  While
+    // the inputs still come from the cache the direct loads are the faster way (0.40 against 0.44 us).  Two register sets
+    // alternate by the parity of the step (the time loop of these kernels is unrolled by two).  Both ways in one kernel, chosen
+    // by a flag, measured slower than either: where the branches join the compiler waits for the requests just issued.
+    static_assert(!DEEP || (EXACT && MAXW <= 4), "the deep fetch: exact heads of up to 64 units");
+    constexpr bool kRegFetch = DEEP;
+    struct Held { i32x4 c[NCC], st, dh; };
+    Held held0, held1;   // the chunks of a step of even / odd index
+    auto request = [&](Held& h) {
+        const rsrc_t rc = make_rsrc(fc_ptr), rst = make_rsrc(fst_ptr), rdh = make_rsrc(fdh_ptr);
+        fc_ptr -= c_step; fst_ptr -= st_step; fdh_ptr -= dh_step;
+#pragma unroll
+        for (int k2 = 0; k2 < NCC; ++k2)
+            if (c_wave[k2]) h.c[k2] = __builtin_amdgcn_raw_buffer_load_b128(rc, cc_g[k2], 0, 0);
+        if (st_wave) h.st = __builtin_amdgcn_raw_buffer_load_b128(rst, cst_g, 0, 0);
+        if (dh_wave) h.dh = __builtin_amdgcn_raw_buffer_load_b128(rdh, cdh_g, 0, 0);
+    };
+    auto park = [&](const Held& h, const int parity) {   // (the places the direct loads would have written)
+        char* img = in_img + parity * L.in_pitch + (uint32_t)w * 1024 + (uint32_t)lane * 16;
+#pragma unroll
+        for (int k2 = 0; k2 < NCC; ++k2)
+            if (c_wave[k2]) *(i32x4*)(img + (uint32_t)k2 * NT * 16) = h.c[k2];
+        if (st_wave) *(i32x4*)(img + L.st_off) = h.st;
+        if (dh_wave) *(i32x4*)(img + L.dh_off) = h.dh;
+    };
     float cv[NC][PP], sc[S][PP], sp[S][PP], dh_ext[PP];
     auto take = [&](const int parity) {
         const char* img = in_img + parity * L.in_pitch;
@@ -584,6 +613,10 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
         fetch(T & 1);
         if (T > 1) fetch((T - 1) & 1);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    if constexpr (kRegFetch) {   // steps T-2 and T-3 into the sets of their parities
+        if (T & 1) { if (T > 2) request(held1); if (T > 3) request(held0); }
+        else { if (T > 2) request(held0); if (T > 3) request(held1); }
     }
     __syncthreads();
     if (T > 0) { take(T & 1); precompute(); }
@@ -655,7 +688,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
         }
         // the chunks fetched during the previous step are in LDS once only that step's stores are younger;
         // they are read after this barrier
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(CELL == CELL_GRU ? 2 : 1) : "memory");
+        if constexpr (!kRegFetch) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(CELL == CELL_GRU ? 2 : 1) : "memory");
         __syncthreads();
         // ---- dh_{t-1} += R dg_t; in the shadow of the chain: fetch step t-2, dWx_t out, step t-1's values
         // The operand is read in chunks of KC k-steps, one chunk ahead of the MFMAs that use it.
@@ -680,7 +713,14 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
             for (int k = 0; k < KC; ++k) gB[c][k] = __builtin_bit_cast(bf16x8, raw[k]);
         };
         read_chunk(0);
-        if (t > 2) fetch(par);
+        if constexpr (kRegFetch) {
+            // step t-2's chunks (requested two steps ago) into the image that step t's have left; then the request for step t-4
+            constexpr int PAR = decltype(par_c)::value;
+            if (t > 2) park(PAR ? held1 : held0, PAR);
+            if (t > 4) request(PAR ? held1 : held0);
+        } else {
+            if (t > 2) fetch(par);
+        }
         pin_order();
         f32x4 acc[EBK][NA];
 #pragma unroll

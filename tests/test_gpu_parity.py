@@ -13,7 +13,7 @@ from paper_2412_07752_amd.synth import CELL_ELMAN, CELL_GRU, CELL_GRU4, CELL_LST
 
 pytestmark = pytest.mark.gpu
 CELLS = [CELL_LSTM, CELL_GRU, CELL_SLSTM, CELL_ELMAN, CELL_GRU4]
-PLAN_ENV = ("FLASHRNN_MULTI", "FLASHRNN_BT", "FLASHRNN_NWU", "FLASHRNN_KS", "FLASHRNN_GPAR", "FLASHRNN_SPIN_LIMIT", "FLASHRNN_EBK",
+PLAN_ENV = ("FLASHRNN_MULTI", "FLASHRNN_BT", "FLASHRNN_NWU", "FLASHRNN_KS", "FLASHRNN_GPAR", "FLASHRNN_SPIN_LIMIT", "FLASHRNN_EBK", "FLASHRNN_DEEP_FETCH",
             "FLASHRNN_KIND", "FLASHRNN_RECOMPUTE_STEPS")
 
 
@@ -94,6 +94,17 @@ def test_batch_tiles_with_f32_io(cell, bt, D):
     w = Workload(f"f32_bt{bt}_{cell}_D{D}", cell, 10, 21, 2, D, "f32", True, bias="forget3" if cell in (CELL_LSTM, CELL_SLSTM) else "uniform0.1",
                  init="uniform0.1", seed=bt + D)
     _check(w, {"FLASHRNN_BT": str(bt)}, with_dlast=True)
+
+
+@pytest.mark.parametrize("cell", CELLS)
+@pytest.mark.parametrize("D,bt", [(32, 4), (32, 8), (64, 4), (64, 8)])
+@pytest.mark.parametrize("T", [1, 2, 3, 4, 5, 6, 13])
+def test_backward_kernels_that_fetch_four_steps_ahead(cell, D, bt, T):
+    """The backward kernels for inputs that come from HBM (taken by themselves only for sequences beyond the last-level cache):
+    forced here on short sequences, every length around the depth of their pipeline."""
+    w = Workload(f"deep_{cell}_D{D}_bt{bt}_T{T}", cell, T, 11, 2, D, "bf16", True, bias="uniform0.1", init="uniform0.1", seed=T + D + bt)
+    _check(w, {"FLASHRNN_DEEP_FETCH": "1", "FLASHRNN_BT": str(bt)}, with_dlast=True)
+    assert api.flashrnn_plan_kernel(api.make_desc(cell, T, 11, 2, D, api.FLASHRNN_BF16), True)[0] == 2   # (that variant ran)
 
 
 @pytest.mark.parametrize("cell", CELLS)
