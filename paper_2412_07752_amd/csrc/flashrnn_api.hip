@@ -150,8 +150,9 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
             if (force_kind >= 0 && e.tile != force_kind) continue;
             if (force_ebk && bwd && e.tile == 1 && e.eb != force_ebk) continue;
             const int dk = e.KT * kstep, nw = e.tile == 1 ? units16 : units16 / e.eb;
-            if (e.exact && dk != kdim) continue;
-            if ((e.exact == 2) && !deep) continue;
+            const bool exact_only = e.exact == 1 || e.exact == 2;
+            if (exact_only && dk != kdim) continue;
+            if (e.exact >= 2 && !deep) continue;
             size_t smem = (size_t)2 * e.BT * (dk + (bf ? 8 : 4)) * (bf ? 2 : 4);
             if (e.tile == 1 && bwd) {
                 const int nsb = d->cell == FLASHRNN_SLSTM ? 2 : d->cell == FLASHRNN_ELMAN ? 0 : 1, go = d->cell == FLASHRNN_GRU ? G + 1 : G;
@@ -169,8 +170,8 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
             if (e.tile == 1 && bwd && ((e.eb > 1) != (e.KT * units16 >= 256))) rel *= 1.05;
             if (e.tile == 0) rel *= 1.0 + 0.05 * (e.eb - 1);       // thin waves overlap better
             rel *= 1.0 + 0.02 * (dk - kdim) / (double)kstep;       // padded k-steps are wasted MFMAs
-            if (e.exact) rel *= 0.99;                              // compile-time LDS layout: fewer address instructions
-            if (e.exact == 2) rel *= 0.9;                          // (only a candidate when the inputs come from HBM: -10 % there)
+            if (exact_only) rel *= 0.99;                           // compile-time LDS layout: fewer address instructions
+            if (e.exact >= 2) rel *= 0.9;                          // (only a candidate when the inputs come from HBM: -10 % there)
             const double cost = rounds * rel;
             if (!best || cost < best_cost) { best = &e; best_cost = cost; best_smem = smem; }
         }
@@ -641,7 +642,7 @@ int flashrnn_plan_kernel(const flashrnn_desc_t* d, int backward, int* staged, in
     Plan pl;
     rc = make_plan(d, backward ? 1 : 0, &pl);
     if (rc != FLASHRNN_OK) return rc;
-    if (staged) *staged = pl.e->tile != 0 ? (pl.e->exact == 2 ? 2 : 1) : 0;
+    if (staged) *staged = pl.e->tile != 0 ? (pl.e->exact >= 2 ? 2 : 1) : 0;
     if (batch_tile) *batch_tile = pl.e->BT;
     if (split) *split = pl.P;
     return FLASHRNN_OK;

@@ -29,10 +29,11 @@ namespace flashrnn {
 #define FRNN_BTL(KT, EBK, BT, MAXW) \
     {FRNN_CELL, FRNN_BF16, 1, (KT) * FRNN_G, 1, BT, 0, MAXW, EBK, 1, 1, (const void*)&bwd_tile_kernel<FRNN_CELL, (KT) * FRNN_G / (EBK), EBK, BT, MAXW, true>}, \
     {FRNN_CELL, FRNN_BF16, 1, (KT) * FRNN_G, 1, BT, 0, MAXW, EBK, 1, 0, (const void*)&bwd_tile_kernel<FRNN_CELL, (KT) * FRNN_G / (EBK), EBK, BT, MAXW, false>},
-// ... and, for heads of exactly 32 or 64 units, a third one that requests its inputs four steps ahead through registers
-// (taken when they will come from HBM; KernelEntry::exact = 2)
+// ... and, for heads of up to 64 units, two more that request their inputs four steps ahead through registers
+// (taken when they will come from HBM; KernelEntry::exact = 2: heads of exactly 32 or 64 units, 3: the sizes below)
 #define FRNN_BTLD(KT, EBK, BT, MAXW) \
-    {FRNN_CELL, FRNN_BF16, 1, (KT) * FRNN_G, 1, BT, 0, MAXW, EBK, 1, 2, (const void*)&bwd_tile_kernel<FRNN_CELL, (KT) * FRNN_G / (EBK), EBK, BT, MAXW, true, true>},
+    {FRNN_CELL, FRNN_BF16, 1, (KT) * FRNN_G, 1, BT, 0, MAXW, EBK, 1, 2, (const void*)&bwd_tile_kernel<FRNN_CELL, (KT) * FRNN_G / (EBK), EBK, BT, MAXW, true, true>}, \
+    {FRNN_CELL, FRNN_BF16, 1, (KT) * FRNN_G, 1, BT, 0, MAXW, EBK, 1, 3, (const void*)&bwd_tile_kernel<FRNN_CELL, (KT) * FRNN_G / (EBK), EBK, BT, MAXW, false, true>},
 #define FRNN_TILE(KT, EBK, BT, MAXW) FRNN_FT(KT, BT, MAXW) FRNN_B(KT, 1, BT, 0, MAXW, 1) FRNN_BTL(KT, EBK, BT, MAXW)
 // the largest heads: one block of 16 units per workgroup, 4 contraction slices, one wave per SIMD
 #define FRNN_FL(KT, BT) FRNN_F(KT, 4, BT, 1, 4, 1)

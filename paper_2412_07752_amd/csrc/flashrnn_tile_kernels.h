@@ -525,7 +525,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
     // the inputs still come from the cache the direct loads are the faster way (0.40 against 0.44 us).  Two register sets
     // alternate by the parity of the step (the time loop of these kernels is unrolled by two).  Both ways in one kernel, chosen
     // by a flag, measured slower than either: where the branches join the compiler waits for the requests just issued.
-    static_assert(!DEEP || (EXACT && MAXW <= 4), "the deep fetch: exact heads of up to 64 units");
+    static_assert(!DEEP || MAXW <= 4, "the deep fetch: heads of up to 64 units");
     constexpr bool kRegFetch = DEEP;
     struct Held { i32x4 c[NCC], st, dh; };
     Held held0, held1;   // the chunks of a step of even / odd index
@@ -626,7 +626,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
     // one time step; PAR = t & 1 as a compile-time constant where the loop is unrolled by two
     constexpr bool kUnroll = true;
     auto step = [&](auto par_c, const int t) {
-        const int par = (EXACT && kUnroll) ? decltype(par_c)::value : (t & 1);
+        const int par = ((EXACT || DEEP) && kUnroll) ? decltype(par_c)::value : (t & 1);
         // ---- point-wise Jacobians of step t
         {
             float dwx[G][PP], dg[G][PP];
@@ -785,7 +785,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
     };
     using par0 = std::integral_constant<int, 0>;
     using par1 = std::integral_constant<int, 1>;
-    if constexpr (EXACT && kUnroll) {
+    if constexpr ((EXACT || DEEP) && kUnroll) {
         int t = T;
         if (t & 1) { step(par1{}, t); --t; }
         for (; t >= 2; t -= 2) {

@@ -97,7 +97,7 @@ def test_batch_tiles_with_f32_io(cell, bt, D):
 
 
 @pytest.mark.parametrize("cell", CELLS)
-@pytest.mark.parametrize("D,bt", [(32, 4), (32, 8), (64, 4), (64, 8)])
+@pytest.mark.parametrize("D,bt", [(32, 4), (32, 8), (64, 4), (64, 8), (16, 4), (48, 8), (48, 4)])
 @pytest.mark.parametrize("T", [1, 2, 3, 4, 5, 6, 13])
 def test_backward_kernels_that_fetch_four_steps_ahead(cell, D, bt, T):
     """The backward kernels for inputs that come from HBM (taken by themselves only for sequences beyond the last-level cache):
