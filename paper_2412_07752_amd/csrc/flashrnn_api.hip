@@ -135,7 +135,7 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
     if (force_multi < 1) {
         // Every (batch tile, kernel) pair that can run the shape gets a cost: rounds of workgroups over the CUs
         // times a relative time per step.  The relative times are measured ones (D = 192 and 128, MI355X): the
-        // staged tile kernels run a step of 4 rows in 1.0, of 8 rows in about 1.5; the generic kernels, whose
+        // staged tile kernels run a step of 4 rows in 1.0, of 8 rows in 1.45 to 2.7 (below); the generic kernels, whose
         // lanes access global memory themselves, need about 1.8 / 3.0 / 6.0 for 4 / 8 / 16 rows.  A kernel that
         // spills registers or whose images do not fit the LDS is not a candidate.
         const KernelEntry* best = nullptr;
@@ -164,7 +164,10 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
             if (e.tile == 1 && kernel_spills(e.fn)) continue;
             const int ng = d->NH * ((d->B + e.BT - 1) / e.BT);
             const int rounds = (ng + cus - 1) / cus;
-            double rel = e.tile == 1 ? (e.BT == 4 ? 1.0 : 1.5) : (e.BT == 4 ? 1.8 : e.BT == 8 ? 3.0 : 6.0);
+            // (8-row staged tiles, measured at 12 x 64 with 128 and 256 rows: backward 1.45 of a 4-row step, forward 1.6, the
+            // sLSTM's forward step, whose point-wise function is the longest, 2.7)
+            const double rel8 = bwd ? 1.45 : (d->cell == FLASHRNN_SLSTM ? 2.7 : 1.6);
+            double rel = e.tile == 1 ? (e.BT == 4 ? 1.0 : rel8) : (e.BT == 4 ? 1.8 : e.BT == 8 ? 3.0 : 6.0);
             // the backward tile kernel splits the contraction over its waves only when the operand reads are
             // many (k-steps x waves); otherwise the second barrier costs more than it saves
             if (e.tile == 1 && bwd && ((e.eb > 1) != (e.KT * units16 >= 256))) rel *= 1.05;
