@@ -44,12 +44,18 @@ PEAK_HBM_GBS = 8000.0
 DEVICE_CUS = 256
 
 
+def plan_call(bwd, backward):
+    """Which call's plan to ask the library for: the backward call (1), the forward call of a workload with a backward pass
+    (0: it saves its values) or the forward call of a forward-only workload (2: it saves nothing)."""
+    return 1 if bwd else (0 if backward else 2)
+
+
 def plan_signature(api, desc, backward):
     """One line that names the launch plans of a descriptor: what a counters file must match to be quoted."""
     parts = []
     for bwd in ([False, True] if backward else [False]):
-        wgs, per_head, waves = api.flashrnn_plan(desc, bwd)
-        staged, bt, split = api.flashrnn_plan_kernel(desc, bwd)
+        wgs, per_head, waves = api.flashrnn_plan(desc, plan_call(bwd, backward))
+        staged, bt, split = api.flashrnn_plan_kernel(desc, plan_call(bwd, backward))
         parts.append(f"{'bwd' if bwd else 'fwd'}:wgs={wgs},waves={waves},staged={int(staged)},bt={bt},split={split}")
     return " ".join(parts)
 
@@ -257,7 +263,8 @@ def main():
                "fwd_kernel_ms": round(fwd_ms, 4), "bwd_kernel_ms": round(bwd_ms, 4)}
         for bwd in ([False, True] if w.backward else [False]):
             clocks, waves = api.flashrnn_trace_phases(desc, runner.ws, bwd)
-            groups_per_wg = max(1, -(-(NH * -(-B // api.flashrnn_plan_kernel(desc, bwd)[1])) // max(1, api.flashrnn_plan(desc, bwd)[0] // api.flashrnn_plan_kernel(desc, bwd)[2])))
+            pc = plan_call(bwd, w.backward)
+            groups_per_wg = max(1, -(-(NH * -(-B // api.flashrnn_plan_kernel(desc, pc)[1])) // max(1, api.flashrnn_plan(desc, pc)[0] // api.flashrnn_plan_kernel(desc, pc)[2])))
             per = {n: round(c / (T * groups_per_wg), 1) for n, c in zip(names[bwd], clocks) if n != "-"}
             per["sum"] = round(sum(per.values()), 1)
             per["waves_recorded"] = waves
@@ -284,8 +291,8 @@ def main():
     for name, bwd, ms in (("fwd", False, fwd_ms), ("bwd", True, bwd_ms)):
         if bwd and not w.backward:
             continue
-        wgs, per_head, waves = api.flashrnn_plan(desc, bwd)
-        staged, bt, split = api.flashrnn_plan_kernel(desc, bwd)
+        wgs, per_head, waves = api.flashrnn_plan(desc, plan_call(bwd, w.backward))
+        staged, bt, split = api.flashrnn_plan_kernel(desc, plan_call(bwd, w.backward))
         nbytes = algorithmic_bytes(w, esz, bwd, w.backward)
         tfl = flops_launch / (ms * 1e-3) / 1e12 if ms > 0 else 0.0
         gbs = nbytes / (ms * 1e-3) / 1e9 if ms > 0 else 0.0

@@ -171,7 +171,9 @@ int flashrnn_check(const flashrnn_desc_t* desc, const void* workspace, void* hip
 /*
  * Launch plan the library would use for `desc`, for reporting: number of workgroups (= CUs kept
  * busy) of the forward / backward persistent kernel, workgroups that share one head, waves per
- * workgroup.  Any out pointer may be NULL.  Returns a status.
+ * workgroup.  backward = 0: the forward call that saves its values (gate_cache given), 1: the backward call, 2: the
+ * forward call that saves nothing (it may take another batch tile; other values: FLASHRNN_ERR_SHAPE).  Any out pointer
+ * may be NULL.  Returns a status.
  */
 int flashrnn_plan(const flashrnn_desc_t* desc, int backward, int* workgroups, int* cus_per_head, int* waves_per_wg);
 

@@ -115,9 +115,10 @@ def flashrnn_workspace_bytes(desc):
 
 
 def flashrnn_plan(desc, backward=False):
-    """(workgroups, CUs per head, waves per workgroup) of the launch the library would use."""
+    """(workgroups, CUs per head, waves per workgroup) of the launch the library would use.
+    backward: False / 0 the forward call that saves its values, True / 1 the backward call, 2 the forward call that saves nothing."""
     a, b, c = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
-    rc = lib().flashrnn_plan(ctypes.byref(desc), int(bool(backward)), ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
+    rc = lib().flashrnn_plan(ctypes.byref(desc), int(backward), ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
     if rc != FLASHRNN_OK:
         raise FlashRNNError(rc, "flashrnn_plan")
     return a.value, b.value, c.value
@@ -126,7 +127,7 @@ def flashrnn_plan(desc, backward=False):
 def flashrnn_plan_kernel(desc, backward=False):
     """(staged: 0 / 1 / 2 = staged with the deep fetch, batch tile rows, workgroups per group) of the kernel that plan uses."""
     a, b, c = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
-    rc = lib().flashrnn_plan_kernel(ctypes.byref(desc), int(bool(backward)), ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
+    rc = lib().flashrnn_plan_kernel(ctypes.byref(desc), int(backward), ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
     if rc != FLASHRNN_OK:
         raise FlashRNNError(rc, "flashrnn_plan_kernel")
     return a.value, b.value, c.value

@@ -109,7 +109,9 @@ bool kernel_spills(const void* fn) {
 // Launch plan.  One workgroup per group whenever the head's R fits one CU's registers with 16 units
 // per wave (no cross-CU traffic at all); then small batch tiles spread the point-wise work over more
 // CUs.  Otherwise a group is split over P workgroups of one XCD that exchange h / dg every step.
-int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
+// mode 0: forward call that saves its values, 1: backward call, 2: forward call that saves nothing.
+int make_plan(const flashrnn_desc_t* d, int mode, Plan* out) {
+    const int bwd = mode == 1 ? 1 : 0;
     const int G = num_gates(d->cell);
     const bool bf = d->io_dtype == FLASHRNN_BF16;
     const int kstep = bf ? 32 : 4;
@@ -164,9 +166,10 @@ int make_plan(const flashrnn_desc_t* d, int bwd, Plan* out) {
             if (e.tile == 1 && kernel_spills(e.fn)) continue;
             const int ng = d->NH * ((d->B + e.BT - 1) / e.BT);
             const int rounds = (ng + cus - 1) / cus;
-            // (8-row staged tiles, measured at 12 x 64 with 128 and 256 rows: backward 1.45 of a 4-row step, forward 1.6, the
-            // sLSTM's forward step, whose point-wise function is the longest, 2.7)
-            const double rel8 = bwd ? 1.45 : (d->cell == FLASHRNN_SLSTM ? 2.7 : 1.6);
+            // (8-row staged tiles, measured at 12 x 64 with 128 and 256 rows: backward 1.45 of a 4-row step, forward 1.6 --
+            // 1.4 when the call saves nothing and writes a third of the bytes --, the sLSTM's forward step, whose point-wise
+            // function is the longest, 2.7)
+            const double rel8 = bwd ? 1.45 : (d->cell == FLASHRNN_SLSTM ? 2.7 : (mode == 2 ? 1.4 : 1.6));
             double rel = e.tile == 1 ? (e.BT == 4 ? 1.0 : rel8) : (e.BT == 4 ? 1.8 : e.BT == 8 ? 3.0 : 6.0);
             // the backward tile kernel splits the contraction over its waves only when the operand reads are
             // many (k-steps x waves); otherwise the second barrier costs more than it saves
@@ -325,11 +328,14 @@ struct Workspace {
     size_t fwd_total;   // bytes a forward call touches: error words, exchange buffers, the forward copy of R
 };
 
-int carve_uncached(const flashrnn_desc_t* d, Workspace* w, Plan* pf, Plan* pb) {
+int carve_uncached(const flashrnn_desc_t* d, Workspace* w, Plan* pf, Plan* pb, Plan* pfn) {
     int rc = make_plan(d, 0, pf);
     if (rc != FLASHRNN_OK) return rc;
     rc = make_plan(d, 1, pb);
     if (rc != FLASHRNN_OK) return rc;
+    // A forward call that saves nothing may take another batch tile of the staged kernels (they use no workspace beyond the
+    // error words, so the layout below does not depend on it); everywhere else it runs the plan of the saving call.
+    if (make_plan(d, 2, pfn) != FLASHRNN_OK || pfn->e->tile == 0 || pf->e->tile == 0) *pfn = *pf;
     const int G = num_gates(d->cell);
     size_t off = 0;
     w->err_off = off; off += kAlign;   // word 0: forward kernels, word 1: backward kernels
@@ -353,8 +359,8 @@ int carve_uncached(const flashrnn_desc_t* d, Workspace* w, Plan* pf, Plan* pb) {
 // Plans and workspace layout of a descriptor.  A thread that calls with the same descriptor again (the usual case:
 // forward, backward, forward, ...) gets the last answer back instead of planning anew; the answer depends on the
 // descriptor and the device only (and on the override variables, which switch this memo off).
-int carve(const flashrnn_desc_t* d, Workspace* w, Plan* pf, Plan* pb) {
-    struct Memo { bool valid = false; flashrnn_desc_t d; int dev; int rc; Workspace w; Plan pf, pb; };
+int carve(const flashrnn_desc_t* d, Workspace* w, Plan* pf, Plan* pb, Plan* pfn = nullptr) {
+    struct Memo { bool valid = false; flashrnn_desc_t d; int dev; int rc; Workspace w; Plan pf, pb, pfn; };
     static thread_local Memo memo;
     int dev = -1;
     (void)hipGetDevice(&dev);
@@ -362,10 +368,13 @@ int carve(const flashrnn_desc_t* d, Workspace* w, Plan* pf, Plan* pb) {
     key.recurrent_grad_clip = 0.0f;   // does not enter the plan
     if (!overrides_enabled() && memo.valid && memo.dev == dev && memcmp(&memo.d, &key, sizeof(key)) == 0) {
         *w = memo.w; *pf = memo.pf; *pb = memo.pb;
+        if (pfn) *pfn = memo.pfn;
         return memo.rc;
     }
-    const int rc = carve_uncached(d, w, pf, pb);
-    memo.valid = true; memo.d = key; memo.dev = dev; memo.rc = rc; memo.w = *w; memo.pf = *pf; memo.pb = *pb;
+    Plan nosave;
+    const int rc = carve_uncached(d, w, pf, pb, &nosave);
+    memo.valid = true; memo.d = key; memo.dev = dev; memo.rc = rc; memo.w = *w; memo.pf = *pf; memo.pb = *pb; memo.pfn = nosave;
+    if (pfn) *pfn = nosave;
     return rc;
 }
 
@@ -457,9 +466,10 @@ int fwd_impl(const flashrnn_desc_t* d, const void* Wx, const void* R, const void
     if (!aligned16(Wx) || !aligned16(R) || !aligned16(b) || !aligned16(states0) || !aligned16(states) || !aligned16(gate_cache))
         return FLASHRNN_ERR_UNSUPPORTED;
     Workspace w;
-    Plan pf, pb;
-    rc = carve(d, &w, &pf, &pb);
+    Plan pf, pb, pfn;
+    rc = carve(d, &w, &pf, &pb, &pfn);
     if (rc != FLASHRNN_OK) return rc;
+    if (!gate_cache) pf = pfn;
     if (!workspace || ((uintptr_t)workspace & (kAlign - 1))) return FLASHRNN_ERR_WORKSPACE;
     if (ws_limit && w.fwd_total > ws_limit) return FLASHRNN_ERR_SCRATCH;
     hipStream_t stream = (hipStream_t)hip_stream;
@@ -627,11 +637,24 @@ size_t flashrnn_workspace_bytes(const flashrnn_desc_t* d) {
     return w.total;
 }
 
+namespace {
+// The plan a call runs: which = 0 forward call that saves its values, 1 backward call, 2 forward call that saves nothing.
+int plan_of_call(const flashrnn_desc_t* d, int which, Plan* pl) {
+    if (which < 0 || which > 2) return FLASHRNN_ERR_SHAPE;
+    Workspace w;
+    Plan pf, pb, pfn;
+    const int rc = carve(d, &w, &pf, &pb, &pfn);
+    if (rc != FLASHRNN_OK) return rc;
+    *pl = which == 0 ? pf : (which == 1 ? pb : pfn);
+    return FLASHRNN_OK;
+}
+}  // namespace
+
 int flashrnn_plan(const flashrnn_desc_t* d, int backward, int* workgroups, int* cus_per_head, int* waves_per_wg) {
     int rc = validate(d);
     if (rc != FLASHRNN_OK) return rc;
     Plan pl;
-    rc = make_plan(d, backward ? 1 : 0, &pl);
+    rc = plan_of_call(d, backward, &pl);
     if (rc != FLASHRNN_OK) return rc;
     if (workgroups) *workgroups = (pl.GPAR < pl.NG ? pl.GPAR : pl.NG) * pl.P;
     if (cus_per_head) *cus_per_head = pl.P * ((d->B + pl.e->BT - 1) / pl.e->BT);
@@ -643,7 +666,7 @@ int flashrnn_plan_kernel(const flashrnn_desc_t* d, int backward, int* staged, in
     int rc = validate(d);
     if (rc != FLASHRNN_OK) return rc;
     Plan pl;
-    rc = make_plan(d, backward ? 1 : 0, &pl);
+    rc = plan_of_call(d, backward, &pl);
     if (rc != FLASHRNN_OK) return rc;
     if (staged) *staged = pl.e->tile != 0 ? (pl.e->exact >= 2 ? 2 : 1) : 0;
     if (batch_tile) *batch_tile = pl.e->BT;

@@ -141,7 +141,7 @@ def main():
                 if "SQ_INSTS_VALU" in m and m.get("SQ_INSTS_MFMA"):
                     out.append(f"dr_gemm_valu_per_mfma_instruction: {m['SQ_INSTS_VALU'] / m['SQ_INSTS_MFMA']:.2f}")
                 continue
-            wgs, _, waves = api.flashrnn_plan(desc, kind == "bwd")
+            wgs, _, waves = api.flashrnn_plan(desc, bench.plan_call(kind == "bwd", w.backward))
             nw, simds = wgs * waves, wgs * min(4, waves)
             if "SQ_WAVE_CYCLES" in m:
                 clocks = m["SQ_WAVE_CYCLES"] * 4 / nw      # mean lifetime of a wave in clocks
@@ -171,7 +171,7 @@ def main():
         if kind not in avg_ns:
             continue
         s = avg_ns[kind] * 1e-9
-        wgs = api.flashrnn_plan(desc, bwd)[0]
+        wgs = api.flashrnn_plan(desc, bench.plan_call(bwd, w.backward))[0]
         nb = bench.algorithmic_bytes(w, esz, bwd, w.backward)
         out.append(f"{kind}_mfma_frac_whole_device: {flops / s / 1e12 / peak:.5f}")
         out.append(f"{kind}_useful_mfma_frac_of_occupied_cus: {flops / s / 1e12 / (peak * min(wgs, 256) / 256):.5f}   # {min(wgs, 256)} CUs")

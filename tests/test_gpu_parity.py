@@ -122,6 +122,18 @@ def test_forward_only_small_batch_tile(cell):
     _check(w)
 
 
+@pytest.mark.parametrize("cell", [CELL_LSTM, CELL_GRU, CELL_SLSTM])
+def test_forward_calls_with_and_without_saved_values_plan_apart(cell):
+    """More groups than CUs (12 x 64 with 256 rows): the forward call that saves its values takes 4-row tiles, the one that
+    saves nothing 8-row tiles (the sLSTM 4 rows either way); both against the oracle."""
+    d = api.make_desc(cell, 3, 256, 12, 64, api.FLASHRNN_BF16)
+    assert api.flashrnn_plan_kernel(d, 0)[:2] == (1, 4) and api.flashrnn_plan_kernel(d, 2)[:2] == (1, 4 if cell == CELL_SLSTM else 8)
+    with pytest.raises(api.FlashRNNError):
+        api.flashrnn_plan_kernel(d, 3)
+    for backward in (False, True):
+        _check(Workload(f"twoplans_{cell}_{int(backward)}", cell, 3, 256, 12, 64, "bf16", backward, bias="uniform0.1", init="uniform0.1", seed=91))
+
+
 @pytest.mark.parametrize("cell", CELLS)
 @pytest.mark.parametrize("clip", [0.0, 0.02, 1e6])
 @pytest.mark.parametrize("dtype,D,env", [("bf16", 64, {}), ("bf16", 192, {}), ("bf16", 96, {"FLASHRNN_KIND": "0"}), ("f32", 32, {}),
