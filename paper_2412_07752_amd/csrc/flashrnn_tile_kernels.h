@@ -163,16 +163,23 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
         for (int k2 = 0; k2 < NCH_IN; ++k2) *(i32x4*)(in_img + L.in_pitch + cin_l[k2]) = __builtin_amdgcn_raw_buffer_load_b128(rs1, cin_g[k2], 0, 0);
     }
     __syncthreads();
-    // With a short chain a step is shorter than the HBM latency under load: the inputs are fetched two steps ahead
-    // there (two register sets in flight), one step ahead with a long chain.
-    i32x4 preA[NCH_IN], preB[NCH_IN];   // short chain: step t fetches into the set t & 1 and parks the other one
+    // With a short chain a step is shorter than the HBM latency under load (0.4 us against 1 us and more once most CUs
+    // stream): the inputs are fetched four steps ahead there, in four register sets of one chunk per thread (Wx_j travels
+    // in set j mod 4: requested at the top of step j - 4, parked in its image at the end of step j - 1), one step ahead with a
+    // long chain.  Requests beyond the last step fetch the last step's inputs again.
+    i32x4 pre[4][NCH_IN];
     if constexpr (!kLongChain) {
 #pragma unroll
-        for (int k2 = 0; k2 < NCH_IN; ++k2) preA[k2] = preB[k2] = i32x4{0, 0, 0, 0};
-        if (T > 0) {   // (with T = 0 there is no Wx to touch)
-            const rsrc_t rs2 = make_rsrc(wx_g + (size_t)(T > 1 ? 1 : 0) * wx_step);
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int k2 = 0; k2 < NCH_IN; ++k2) preA[k2] = __builtin_amdgcn_raw_buffer_load_b128(rs2, cin_g[k2], 0, 0);   // Wx_2, parked at the end of step 1
+            for (int k2 = 0; k2 < NCH_IN; ++k2) pre[j][k2] = i32x4{0, 0, 0, 0};
+        if (T > 0) {   // (with T = 0 there is no Wx to touch)
+#pragma unroll
+            for (int j = 2; j <= 4; ++j) {   // Wx_2, Wx_3, Wx_4: slots 1, 2, 3
+                const rsrc_t rsj = make_rsrc(wx_g + (size_t)(j - 1 < T ? j - 1 : T - 1) * wx_step);
+#pragma unroll
+                for (int k2 = 0; k2 < NCH_IN; ++k2) pre[j & 3][k2] = __builtin_amdgcn_raw_buffer_load_b128(rsj, cin_g[k2], 0, 0);
+            }
         }
     }
 
@@ -184,7 +191,8 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
     };
     // The three streams of a step advance by whole time steps: their bases are carried as pointers (a product of the
     // step index and a 64-bit stride per stream and step is a dozen scalar instructions).
-    const char* wx_ptr = wx_g + (size_t)(2 < T ? 2 : (T > 0 ? T - 1 : 0)) * wx_step;   // Wx of the step fetched next (slot 2 = Wx_3)
+    constexpr int kFirstAhead = kLongChain ? 2 : 4;   // slot of the first request made inside the time loop (long chain: slot 2 = Wx_3)
+    const char* wx_ptr = wx_g + (size_t)(kFirstAhead < T ? kFirstAhead : (T > 0 ? T - 1 : 0)) * wx_step;   // Wx of the step fetched next
     // Long chain: Wx_{t+1} is requested at the end of step t-1, AHEAD of that step's stores in the wave's memory queue.  A
     // wave's vector memory operations retire in order: a load issued behind the stores of the step before could not be
     // waited for without waiting for their acknowledgements as well, which tied the step to the write latency of the
@@ -206,9 +214,10 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
     // (trace builds: clocks per wave between 0 the barrier and the top of a step | 2 the top and the issue of the chain's
     // last MFMA | 3 that and the barrier: compaction, point-wise function, LDS writes)
     FRNN_TRACE_BEGIN();
-    // one time step; PAR = t & 1 as a compile-time constant where it selects a register set
-    auto step = [&](auto par_c, const int t) {
-        constexpr int PAR = decltype(par_c)::value;
+    // one time step; PH = t & 3 as a compile-time constant where it selects a register set (short chain), PAR = t & 1
+    auto step = [&](auto ph_c, const int t) {
+        constexpr int PH = decltype(ph_c)::value;
+        constexpr int PAR = PH & 1;
         // parity of the step: a compile-time constant where the loop is unrolled by two (always with a short chain, where it
         // selects a register set; with a long chain only for EXACT heads: with run-time pitches the two sets of addresses
         // would not fit the registers)
@@ -238,16 +247,11 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
         };
         if constexpr (!kLongChain) side_reads();
         if constexpr (!kLongChain) {
-            const int ahead = t + 1;   // slot of Wx_{t+2} (the last steps fetch the last slot again)
+            const int ahead = t + 3;   // slot of Wx_{t+4} (the last steps fetch the last slot again)
             const rsrc_t rsn = make_rsrc(wx_ptr);
             wx_ptr += ahead < T - 1 ? wx_step : 0;
-            if constexpr (PAR == 1) {
 #pragma unroll
-                for (int k2 = 0; k2 < NCH_IN; ++k2) preB[k2] = __builtin_amdgcn_raw_buffer_load_b128(rsn, cin_g[k2], 0, 0);
-            } else {
-#pragma unroll
-                for (int k2 = 0; k2 < NCH_IN; ++k2) preA[k2] = __builtin_amdgcn_raw_buffer_load_b128(rsn, cin_g[k2], 0, 0);
-            }
+            for (int k2 = 0; k2 < NCH_IN; ++k2) pre[PH][k2] = __builtin_amdgcn_raw_buffer_load_b128(rsn, cin_g[k2], 0, 0);
         }
         pin_order();
         f32x4 acc[G];
@@ -310,13 +314,10 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
         write_operand_lds<true, PP>(hbuf + par * BUF + lds_row, e0, st[0]);
 #pragma unroll
         for (int s = 0; s < S; ++s) store_io<false, PP>(oimg + l_st + (uint32_t)s * BT * L.rp_st, 0, st[s]);
-        if constexpr (!kLongChain) {   // park Wx_{t+1} (fetched during the previous step); Wx_{t+2} stays in flight
+        if constexpr (!kLongChain) {   // park Wx_{t+1} (requested three steps ago); Wx_{t+2} .. Wx_{t+4} stay in flight
             char* im = in_img + (par ^ 1) * L.in_pitch;
 #pragma unroll
-            for (int k2 = 0; k2 < NCH_IN; ++k2) {
-                if constexpr (PAR == 1) *(i32x4*)(im + cin_l[k2]) = preA[k2];
-                else *(i32x4*)(im + cin_l[k2]) = preB[k2];
-            }
+            for (int k2 = 0; k2 < NCH_IN; ++k2) *(i32x4*)(im + cin_l[k2]) = pre[(PH + 1) & 3][k2];
         }
 #ifdef FLASHRNN_TRACE
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -324,17 +325,30 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
         FRNN_TRACE_MARK(3);
         __syncthreads();
     };
-    using par0 = std::integral_constant<int, 0>;
-    using par1 = std::integral_constant<int, 1>;
+    using ph0 = std::integral_constant<int, 0>;
+    using ph1 = std::integral_constant<int, 1>;
+    using ph2 = std::integral_constant<int, 2>;
+    using ph3 = std::integral_constant<int, 3>;
     if constexpr (kLongChain && !EXACT) {
-        for (int t = 1; t <= T; ++t) step(par0{}, t);
-    } else {
+        for (int t = 1; t <= T; ++t) step(ph0{}, t);
+    } else if constexpr (kLongChain) {
         int t = 1;
         for (; t + 1 <= T; t += 2) {
-            step(par1{}, t);
-            step(par0{}, t + 1);
+            step(ph1{}, t);
+            step(ph0{}, t + 1);
         }
-        if (t <= T) step(par1{}, t);
+        if (t <= T) step(ph1{}, t);
+    } else {
+        int t = 1;
+        for (; t + 3 <= T; t += 4) {
+            step(ph1{}, t);
+            step(ph2{}, t + 1);
+            step(ph3{}, t + 2);
+            step(ph0{}, t + 3);
+        }
+        if (t <= T) step(ph1{}, t);
+        if (t + 1 <= T) step(ph2{}, t + 1);
+        if (t + 2 <= T) step(ph3{}, t + 2);
     }
     // ---- drain: outputs of step T
     if (T > 0) {
