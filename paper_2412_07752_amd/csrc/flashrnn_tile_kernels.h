@@ -532,17 +532,17 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
         if (dh_wave) load_chunk_to_lds(rdh, img + L.dh_off, cdh_g);
     };
     // DEEP (a kernel of its own for heads of up to 64 units, steps of 0.4 us; the host takes it when the inputs exceed the
-    // last-level cache and will come from HBM): the same chunks through registers instead, requested FOUR steps before their
-    // step and written into the image two steps later.  With the loads that write LDS directly the request can only go out
+    // last-level cache and will come from HBM): the same chunks through registers instead, requested SIX steps before their
+    // step and written into the image four steps later.  With the loads that write LDS directly the request can only go out
     // once its image is free, two steps before the data is used -- less than the latency of HBM, which these short steps then
     // wait for (12 x 64, B = 16: 0.40 us per step up to T = 512, 0.54 us from T = 1024 on; through registers 0.48 us).  While
-    // the inputs still come from the cache the direct loads are the faster way (0.40 against 0.44 us).  Two register sets
-    // alternate by the parity of the step (the time loop of these kernels is unrolled by two).  Both ways in one kernel, chosen
+    // the inputs still come from the cache the direct loads are the faster way (0.40 against 0.44 us).  Four register sets
+    // take turns by the step index modulo 4 (the time loop of these kernels is unrolled by four).  Both ways in one kernel, chosen
     // by a flag, measured slower than either: where the branches join the compiler waits for the requests just issued.
     static_assert(!DEEP || MAXW <= 4, "the deep fetch: heads of up to 64 units");
     constexpr bool kRegFetch = DEEP;
     struct Held { i32x4 c[NCC], st, dh; };
-    Held held0, held1;   // the chunks of a step of even / odd index
+    Held held[4];   // the chunks of the steps t = 0, 1, 2, 3 modulo 4
     auto request = [&](Held& h) {
         const rsrc_t rc = make_rsrc(fc_ptr), rst = make_rsrc(fst_ptr), rdh = make_rsrc(fdh_ptr);
         fc_ptr -= c_step; fst_ptr -= st_step; fdh_ptr -= dh_step;
@@ -628,19 +628,26 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
         if (T > 1) fetch((T - 1) & 1);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
-    if constexpr (kRegFetch) {   // steps T-2 and T-3 into the sets of their parities
-        if (T & 1) { if (T > 2) request(held1); if (T > 3) request(held0); }
-        else { if (T > 2) request(held0); if (T > 3) request(held1); }
+    if constexpr (kRegFetch) {   // steps T-2 .. T-5 into their sets
+#pragma unroll
+        for (int j = 2; j <= 5; ++j)
+            if (T > j) {
+                const int set = (T - j) & 3;
+                if (set == 0) request(held[0]);
+                else if (set == 1) request(held[1]);
+                else if (set == 2) request(held[2]);
+                else request(held[3]);
+            }
     }
     __syncthreads();
     if (T > 0) { take(T & 1); precompute(); }
 
     // (the bias gradient, the sum of dg over time and batch rows, is formed by the dR GEMM, which reads every dg anyway:
     // this kernel has neither the registers to keep the sums while its MFMAs run nor LDS bandwidth to spare for them)
-    // one time step; PAR = t & 1 as a compile-time constant where the loop is unrolled by two
+    // one time step; PH = t & 3 (DEEP) or t & 1 as a compile-time constant where the loop is unrolled by four or two
     constexpr bool kUnroll = true;
-    auto step = [&](auto par_c, const int t) {
-        const int par = ((EXACT || DEEP) && kUnroll) ? decltype(par_c)::value : (t & 1);
+    auto step = [&](auto ph_c, const int t) {
+        const int par = ((EXACT || DEEP) && kUnroll) ? (decltype(ph_c)::value & 1) : (t & 1);
         // ---- point-wise Jacobians of step t
         {
             float dwx[G][PP], dg[G][PP];
@@ -728,10 +735,10 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
         };
         read_chunk(0);
         if constexpr (kRegFetch) {
-            // step t-2's chunks (requested two steps ago) into the image that step t's have left; then the request for step t-4
-            constexpr int PAR = decltype(par_c)::value;
-            if (t > 2) park(PAR ? held1 : held0, PAR);
-            if (t > 4) request(PAR ? held1 : held0);
+            // step t-2's chunks (requested four steps ago) into the image that step t's have left; then the request for step t-6
+            constexpr int PH = decltype(ph_c)::value, SET = (PH + 2) & 3;
+            if (t > 2) park(held[SET], PH & 1);
+            if (t > 6) request(held[SET]);
         } else {
             if (t > 2) fetch(par);
         }
@@ -797,17 +804,30 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
             for (int i = 0; i < PP; ++i) ds[0][i] += fminf(fmaxf(part[0][i], -p.clip), p.clip);
         }
     };
-    using par0 = std::integral_constant<int, 0>;
-    using par1 = std::integral_constant<int, 1>;
-    if constexpr ((EXACT || DEEP) && kUnroll) {
+    using ph0 = std::integral_constant<int, 0>;
+    using ph1 = std::integral_constant<int, 1>;
+    using ph2 = std::integral_constant<int, 2>;
+    using ph3 = std::integral_constant<int, 3>;
+    if constexpr (DEEP && kUnroll) {
         int t = T;
-        if (t & 1) { step(par1{}, t); --t; }
+        if ((t & 3) == 3) { step(ph3{}, t); --t; }
+        if ((t & 3) == 2) { step(ph2{}, t); --t; }
+        if ((t & 3) == 1) { step(ph1{}, t); --t; }
+        for (; t >= 4; t -= 4) {
+            step(ph0{}, t);
+            step(ph3{}, t - 1);
+            step(ph2{}, t - 2);
+            step(ph1{}, t - 3);
+        }
+    } else if constexpr (EXACT && kUnroll) {
+        int t = T;
+        if (t & 1) { step(ph1{}, t); --t; }
         for (; t >= 2; t -= 2) {
-            step(par0{}, t);
-            step(par1{}, t - 1);
+            step(ph0{}, t);
+            step(ph1{}, t - 1);
         }
     } else {
-        for (int t = T; t >= 1; --t) step(par0{}, t);
+        for (int t = T; t >= 1; --t) step(ph0{}, t);
     }
     // ---- gradients w.r.t. the initial states
     if (row_valid) {

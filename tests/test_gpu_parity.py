@@ -98,8 +98,8 @@ def test_batch_tiles_with_f32_io(cell, bt, D):
 
 @pytest.mark.parametrize("cell", CELLS)
 @pytest.mark.parametrize("D,bt", [(32, 4), (32, 8), (64, 4), (64, 8), (16, 4), (48, 8), (48, 4)])
-@pytest.mark.parametrize("T", [1, 2, 3, 4, 5, 6, 13])
-def test_backward_kernels_that_fetch_four_steps_ahead(cell, D, bt, T):
+@pytest.mark.parametrize("T", [1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 13])
+def test_backward_kernels_that_fetch_deep(cell, D, bt, T):
     """The backward kernels for inputs that come from HBM (taken by themselves only for sequences beyond the last-level cache):
     forced here on short sequences, every length around the depth of their pipeline."""
     w = Workload(f"deep_{cell}_D{D}_bt{bt}_T{T}", cell, T, 11, 2, D, "bf16", True, bias="uniform0.1", init="uniform0.1", seed=T + D + bt)
