@@ -18,7 +18,7 @@ struct KernelEntry {
     int eb;     // blocks of 16 units per wave
     int tile;   // 0: generic kernel, 1: staged tile kernel (bf16, one workgroup per group, BT < 16)
     int exact;  // 1: only for heads of exactly the kernel's contraction length (compile-time LDS layout); 2: such a kernel that
-                // fetches its inputs four steps ahead (for inputs that come from HBM); 3: the same for the sizes below
+                // fetches its inputs six steps ahead (for inputs that come from HBM); 3: the same for the sizes below
     const void* fn;
 };
 

@@ -29,8 +29,8 @@ namespace flashrnn {
 #define FRNN_BTL(KT, EBK, BT, MAXW) \
     {FRNN_CELL, FRNN_BF16, 1, (KT) * FRNN_G, 1, BT, 0, MAXW, EBK, 1, 1, (const void*)&bwd_tile_kernel<FRNN_CELL, (KT) * FRNN_G / (EBK), EBK, BT, MAXW, true>}, \
     {FRNN_CELL, FRNN_BF16, 1, (KT) * FRNN_G, 1, BT, 0, MAXW, EBK, 1, 0, (const void*)&bwd_tile_kernel<FRNN_CELL, (KT) * FRNN_G / (EBK), EBK, BT, MAXW, false>},
-// ... and, for heads of up to 64 units, two more that request their inputs four steps ahead through registers
-// (taken when they will come from HBM; KernelEntry::exact = 2: heads of exactly 32 or 64 units, 3: the sizes below)
+// ... and, for heads of up to 128 units, two more that request their inputs six steps ahead through registers
+// (taken when they will come from HBM; KernelEntry::exact = 2: heads of exactly 32, 64 or 128 units, 3: the sizes below)
 #define FRNN_BTLD(KT, EBK, BT, MAXW) \
     {FRNN_CELL, FRNN_BF16, 1, (KT) * FRNN_G, 1, BT, 0, MAXW, EBK, 1, 2, (const void*)&bwd_tile_kernel<FRNN_CELL, (KT) * FRNN_G / (EBK), EBK, BT, MAXW, true, true>}, \
     {FRNN_CELL, FRNN_BF16, 1, (KT) * FRNN_G, 1, BT, 0, MAXW, EBK, 1, 3, (const void*)&bwd_tile_kernel<FRNN_CELL, (KT) * FRNN_G / (EBK), EBK, BT, MAXW, false, true>},
@@ -45,7 +45,7 @@ static const KernelEntry kEntries[] = {
 #if FRNN_BF16
     FRNN_FB(1, 1, 16, 0, 4) FRNN_TILE(1, 1, 8, 4) FRNN_TILE(1, 1, 4, 4) FRNN_BTLD(1, 1, 8, 4) FRNN_BTLD(1, 1, 4, 4)
     FRNN_FB(2, 1, 16, 0, 4) FRNN_TILE(2, 2, 8, 4) FRNN_TILE(2, 2, 4, 4) FRNN_BTL(2, 1, 8, 4) FRNN_BTL(2, 1, 4, 4) FRNN_BTLD(2, 1, 8, 4) FRNN_BTLD(2, 1, 4, 4)
-    FRNN_FB(4, 1, 16, 0, 8) FRNN_TILE(4, 2, 8, 8) FRNN_TILE(4, 2, 4, 8) FRNN_BTL(4, 1, 8, 8) FRNN_BTL(4, 1, 4, 8) FRNN_BTL(4, 4, 8, 8) FRNN_BTL(4, 4, 4, 8)
+    FRNN_FB(4, 1, 16, 0, 8) FRNN_TILE(4, 2, 8, 8) FRNN_TILE(4, 2, 4, 8) FRNN_BTL(4, 1, 8, 8) FRNN_BTL(4, 1, 4, 8) FRNN_BTL(4, 4, 8, 8) FRNN_BTL(4, 4, 4, 8) FRNN_BTLD(4, 1, 8, 8) FRNN_BTLD(4, 1, 4, 8)
     FRNN_FB(6, 1, 16, 0, 12) FRNN_TILE(6, 3, 8, 12) FRNN_TILE(6, 3, 4, 12) FRNN_BTL(6, 1, 8, 12) FRNN_BTL(6, 1, 4, 12)
     FRNN_FBE(4, 16, 4, 2) FRNN_FBE(4, 8, 4, 2) FRNN_FBE(4, 4, 4, 2)
     FRNN_FBE(6, 16, 4, 3) FRNN_FBE(6, 8, 4, 3) FRNN_FBE(6, 4, 4, 3)

@@ -539,7 +539,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
     // the inputs still come from the cache the direct loads are the faster way (0.40 against 0.44 us).  Four register sets
     // take turns by the step index modulo 4 (the time loop of these kernels is unrolled by four).  Both ways in one kernel, chosen
     // by a flag, measured slower than either: where the branches join the compiler waits for the requests just issued.
-    static_assert(!DEEP || MAXW <= 4, "the deep fetch: heads of up to 64 units");
+    static_assert(!DEEP || MAXW <= 8, "the deep fetch: heads of up to 128 units");
     constexpr bool kRegFetch = DEEP;
     struct Held { i32x4 c[NCC], st, dh; };
     Held held[4];   // the chunks of the steps t = 0, 1, 2, 3 modulo 4

@@ -347,7 +347,7 @@ RECOMPUTE_CASES = [
     ("bf16", 64, 13, 11, {"FLASHRNN_RECOMPUTE_STEPS": "4"}), ("bf16", 192, 6, 9, {"FLASHRNN_RECOMPUTE_STEPS": "1"}),
     ("bf16", 96, 19, 11, {"FLASHRNN_RECOMPUTE_STEPS": "4", "FLASHRNN_KIND": "0", "FLASHRNN_BT": "16"}), ("bf16", 256, 7, 11, {"FLASHRNN_RECOMPUTE_STEPS": "3"}),
     ("bf16", 80, 5, 7, {}), ("f32", 48, 9, 10, {"FLASHRNN_RECOMPUTE_STEPS": "4"}), ("f32", 192, 5, 6, {"FLASHRNN_RECOMPUTE_STEPS": "2"}),
-    # ... and the backward kernels that fetch four steps ahead, in windows of 5 steps (a ragged first window of 3)
+    # ... and the backward kernels that fetch deep, in windows of 5 steps (a ragged first window of 3)
     ("bf16", 64, 13, 13, {"FLASHRNN_RECOMPUTE_STEPS": "5", "FLASHRNN_DEEP_FETCH": "1"}),
 ]
 
