@@ -191,7 +191,12 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
     };
     // The three streams of a step advance by whole time steps: their bases are carried as pointers (a product of the
     // step index and a 64-bit stride per stream and step is a dozen scalar instructions).
-    constexpr int kFirstAhead = kLongChain ? 2 : 4;   // slot of the first request made inside the time loop (long chain: slot 2 = Wx_3)
+    // Long chain: one register set, Wx_{t+2} requested at the tail of step t and parked a third into step t+1 -- or, with the
+    // step's parity a compile-time constant (EXACT), two sets that alternate: Wx_{t+3} requested at the tail of step t into the
+    // set that Wx_{t+1} has just left, parked a third into step t+2 (1.6 steps of lead instead of 0.6: with a hundred and more
+    // CUs streaming the latency of HBM exceeds a step).
+    constexpr bool kTwoSets = kLongChain && EXACT;
+    constexpr int kFirstAhead = kLongChain ? (kTwoSets ? 3 : 2) : 4;   // slot of the first request made inside the time loop (slot 2 = Wx_3)
     const char* wx_ptr = wx_g + (size_t)(kFirstAhead < T ? kFirstAhead : (T > 0 ? T - 1 : 0)) * wx_step;   // Wx of the step fetched next
     // Long chain: Wx_{t+1} is requested at the end of step t-1, AHEAD of that step's stores in the wave's memory queue.  A
     // wave's vector memory operations retire in order: a load issued behind the stores of the step before could not be
@@ -202,6 +207,14 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
         const rsrc_t rs2 = make_rsrc(wx_g + (size_t)(T > 1 ? 1 : 0) * wx_step);
 #pragma unroll
         for (int k2 = 0; k2 < NCH_IN; ++k2) pre_next[k2] = T > 0 ? __builtin_amdgcn_raw_buffer_load_b128(rs2, cin_g[k2], 0, 0) : i32x4{0, 0, 0, 0};
+        if constexpr (kTwoSets) {   // Wx_2 travels in set 0, Wx_3 in set 1
+            const rsrc_t rs3 = make_rsrc(wx_g + (size_t)(T > 2 ? 2 : (T > 0 ? T - 1 : 0)) * wx_step);
+#pragma unroll
+            for (int k2 = 0; k2 < NCH_IN; ++k2) {
+                pre[0][k2] = pre_next[k2];
+                pre[1][k2] = T > 0 ? __builtin_amdgcn_raw_buffer_load_b128(rs3, cin_g[k2], 0, 0) : i32x4{0, 0, 0, 0};
+            }
+        }
     }
     char* st_ptr = st_g;   // state slot of the step before the current one (slot 0 is written directly, not through the image)
     char* c_ptr = c_g;     // saved values of the current step
@@ -278,7 +291,7 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
             pin_order();
             char* im = in_img + (par ^ 1) * L.in_pitch;
 #pragma unroll
-            for (int k2 = 0; k2 < NCH_IN; ++k2) *(i32x4*)(im + cin_l[k2]) = pre_next[k2];
+            for (int k2 = 0; k2 < NCH_IN; ++k2) *(i32x4*)(im + cin_l[k2]) = kTwoSets ? pre[PAR ^ 1][k2] : pre_next[k2];
         }
         pin_order();
 #pragma unroll
@@ -289,11 +302,14 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
         // ---- point-wise function; the step's outputs go to their image (they leave for HBM during the next step)
 #pragma unroll
         for (int g = 0; g < G; ++g) compact_tile<BT>(acc[g]);
-        if constexpr (kLongChain) {   // Wx_{t+2}: slot t + 1 (the last steps fetch the last slot again)
+        if constexpr (kLongChain) {   // Wx_{t+2}: slot t + 1, or with two sets Wx_{t+3} (the last steps fetch the last slot again)
             const rsrc_t rsn = make_rsrc(wx_ptr);
-            wx_ptr += t + 1 < T - 1 ? wx_step : 0;
+            wx_ptr += t + (kTwoSets ? 2 : 1) < T - 1 ? wx_step : 0;
 #pragma unroll
-            for (int k2 = 0; k2 < NCH_IN; ++k2) pre_next[k2] = __builtin_amdgcn_raw_buffer_load_b128(rsn, cin_g[k2], 0, 0);
+            for (int k2 = 0; k2 < NCH_IN; ++k2) {
+                if constexpr (kTwoSets) pre[PAR ^ 1][k2] = __builtin_amdgcn_raw_buffer_load_b128(rsn, cin_g[k2], 0, 0);
+                else pre_next[k2] = __builtin_amdgcn_raw_buffer_load_b128(rsn, cin_g[k2], 0, 0);
+            }
         }
         char* oimg = out_img + par * OUT_PITCH;
         const rsrc_t rs_c = make_rsrc(c_ptr);
