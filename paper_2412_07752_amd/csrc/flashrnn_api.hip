@@ -132,7 +132,9 @@ int make_plan(const flashrnn_desc_t* d, int mode, Plan* out) {
     // (256 MB; the forward pass has just written most of it) its inputs come from HBM, and small heads take the kernels that fetch deeper.
     const double bwd_bytes = ((double)record_slots(d->cell) * io_size(d->io_dtype) + (double)num_states(d->cell) * 4 + (double)(1 + G) * io_size(d->io_dtype)) *
                              (double)d->T * d->B * d->NH * d->D;
-    const bool deep = bwd && env_int("FLASHRNN_DEEP_FETCH", bwd_bytes > 224.0 * 1024 * 1024 ? 1 : 0) != 0;
+    // (measured at 12 x 64, T = 1024: up to 165 MB -- LSTM with 8 rows, sLSTM with 5 -- the direct loads are 10 % faster, from
+    // 184 MB on -- LSTM with 9 rows -- the deep fetch is)
+    const bool deep = bwd && env_int("FLASHRNN_DEEP_FETCH", bwd_bytes > 172.0 * 1024 * 1024 ? 1 : 0) != 0;
 
     if (force_multi < 1) {
         // Every (batch tile, kernel) pair that can run the shape gets a cost: rounds of workgroups over the CUs
