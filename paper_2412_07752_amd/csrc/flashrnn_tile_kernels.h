@@ -179,6 +179,13 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
                 const rsrc_t rsj = make_rsrc(wx_g + (size_t)(j - 1 < T ? j - 1 : T - 1) * wx_step);
 #pragma unroll
                 for (int k2 = 0; k2 < NCH_IN; ++k2) pre[j & 3][k2] = __builtin_amdgcn_raw_buffer_load_b128(rsj, cin_g[k2], 0, 0);
+                // Each request is followed by at least as many stores as a step issues behind its own, all of them out of range (the
+                // memory pipeline drops them).  The compiler waits for a request by counting the memory operations issued
+                // after it, and where two paths meet -- this prologue and the loop's back edge, at the loop's head -- it
+                // takes the smaller count: without the padding three of the four steps of the loop waited for requests only
+                // one and two steps old (wait counts 5, 7, 9, 11 instead of 11 four times).
+#pragma unroll
+                for (int x = 0; x < NCH_ST + 2 * PP; ++x) __builtin_amdgcn_raw_buffer_store_b128(i32x4{0, 0, 0, 0}, rsj, kDrop, 0, 0);
             }
         }
     }
