@@ -544,9 +544,21 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
     const char* fdh_ptr = dh_g + back * (ptrdiff_t)dh_step;
     char* dwx_ptr = dwx_g + back * (ptrdiff_t)wx_step;
     char* dgn_ptr = dgn_g + back * (ptrdiff_t)dh_step;
+    // (DEEP: every step requests, also the last ones, whose requests have no step left to serve: the pointers stop at step 1,
+    // whose inputs are then fetched again)
+    int fleft = T;   // steps not yet fetched or requested
+    auto advance = [&]() {
+        if constexpr (DEEP) {
+            const bool more = fleft > 1;
+            fc_ptr -= more ? c_step : 0; fst_ptr -= more ? st_step : 0; fdh_ptr -= more ? dh_step : 0;
+            fleft -= more ? 1 : 0;
+        } else {
+            fc_ptr -= c_step; fst_ptr -= st_step; fdh_ptr -= dh_step;
+        }
+    };
     auto fetch = [&](const int parity) {
         const rsrc_t rc = make_rsrc(fc_ptr), rst = make_rsrc(fst_ptr), rdh = make_rsrc(fdh_ptr);
-        fc_ptr -= c_step; fst_ptr -= st_step; fdh_ptr -= dh_step;
+        advance();
         char* img = in_img + parity * L.in_pitch + (uint32_t)w * 1024;
 #pragma unroll
         for (int k2 = 0; k2 < NCC; ++k2)
@@ -566,14 +578,17 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
     constexpr bool kRegFetch = DEEP;
     struct Held { i32x4 c[NCC], st, dh; };
     Held held[4];   // the chunks of the steps t = 0, 1, 2, 3 modulo 4
+    // (Every wave issues every load, every step: the offsets of a wave without chunks of a kind are out of range, its loads
+    // are dropped.  The compiler waits for a request by counting the memory operations issued after it; a load or a request
+    // under a condition makes it count the path with the fewest, and the wait for a request four steps old becomes a wait for
+    // the one of the step before.)
     auto request = [&](Held& h) {
         const rsrc_t rc = make_rsrc(fc_ptr), rst = make_rsrc(fst_ptr), rdh = make_rsrc(fdh_ptr);
-        fc_ptr -= c_step; fst_ptr -= st_step; fdh_ptr -= dh_step;
+        advance();
 #pragma unroll
-        for (int k2 = 0; k2 < NCC; ++k2)
-            if (c_wave[k2]) h.c[k2] = __builtin_amdgcn_raw_buffer_load_b128(rc, cc_g[k2], 0, 0);
-        if (st_wave) h.st = __builtin_amdgcn_raw_buffer_load_b128(rst, cst_g, 0, 0);
-        if (dh_wave) h.dh = __builtin_amdgcn_raw_buffer_load_b128(rdh, cdh_g, 0, 0);
+        for (int k2 = 0; k2 < NCC; ++k2) h.c[k2] = __builtin_amdgcn_raw_buffer_load_b128(rc, cc_g[k2], 0, 0);
+        h.st = __builtin_amdgcn_raw_buffer_load_b128(rst, cst_g, 0, 0);
+        h.dh = __builtin_amdgcn_raw_buffer_load_b128(rdh, cdh_g, 0, 0);
     };
     auto park = [&](const Held& h, const int parity) {   // (the places the direct loads would have written)
         char* img = in_img + parity * L.in_pitch + (uint32_t)w * 1024 + (uint32_t)lane * 16;
@@ -646,28 +661,32 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
 #pragma unroll
             for (int i = 0; i < PP; ++i) sc[s][i] = 1.0f;
     }
+    // (DEEP: images and register sets take turns by the distance T - t from the first step, not by t: the first step
+    // then has phase 0 whatever T is, and the time loop needs no steps peeled off in front of it)
+    auto par_of = [&](const int t) { return DEEP ? ((T - t) & 1) : (t & 1); };
     if (T > 0) {
-        fetch(T & 1);
-        if (T > 1) fetch((T - 1) & 1);
+        fetch(par_of(T));
+        if (T > 1) fetch(par_of(T - 1));
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
-    if constexpr (kRegFetch) {   // steps T-2 .. T-5 into their sets
+    if constexpr (kRegFetch) {
+        if (T > 0) {   // steps T-2 .. T-5 into the sets 2, 3, 0, 1
 #pragma unroll
-        for (int j = 2; j <= 5; ++j)
-            if (T > j) {
-                const int set = (T - j) & 3;
-                if (set == 0) request(held[0]);
-                else if (set == 1) request(held[1]);
-                else if (set == 2) request(held[2]);
-                else request(held[3]);
+            for (int j = 2; j <= 5; ++j) {
+                request(held[j & 3]);
+                // (as many dropped stores behind each request as a step issues at most: the wait counts at the head of the time
+                // loop are the smaller of what this prologue and the loop's back edge leave behind)
+                __builtin_amdgcn_raw_buffer_store_b128(i32x4{0, 0, 0, 0}, make_rsrc(dwx_g), kDrop, 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b128(i32x4{0, 0, 0, 0}, make_rsrc(dwx_g), kDrop, 0, 0);
             }
+        }
     }
     __syncthreads();
-    if (T > 0) { take(T & 1); precompute(); }
+    if (T > 0) { take(par_of(T)); precompute(); }
 
     // (the bias gradient, the sum of dg over time and batch rows, is formed by the dR GEMM, which reads every dg anyway:
     // this kernel has neither the registers to keep the sums while its MFMAs run nor LDS bandwidth to spare for them)
-    // one time step; PH = t & 3 (DEEP) or t & 1 as a compile-time constant where the loop is unrolled by four or two
+    // one time step; PH = (T - t) & 3 (DEEP) or t & 1 as a compile-time constant where the loop is unrolled by four or two
     constexpr bool kUnroll = true;
     auto step = [&](auto ph_c, const int t) {
         const int par = ((EXACT || DEEP) && kUnroll) ? (decltype(ph_c)::value & 1) : (t & 1);
@@ -759,9 +778,10 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
         read_chunk(0);
         if constexpr (kRegFetch) {
             // step t-2's chunks (requested four steps ago) into the image that step t's have left; then the request for step t-6
+            // (both also in the last steps, where nobody reads what they bring: no condition, see request)
             constexpr int PH = decltype(ph_c)::value, SET = (PH + 2) & 3;
-            if (t > 2) park(held[SET], PH & 1);
-            if (t > 6) request(held[SET]);
+            park(held[SET], PH & 1);
+            request(held[SET]);
         } else {
             if (t > 2) fetch(par);
         }
@@ -833,15 +853,15 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
     using ph3 = std::integral_constant<int, 3>;
     if constexpr (DEEP && kUnroll) {
         int t = T;
-        if ((t & 3) == 3) { step(ph3{}, t); --t; }
-        if ((t & 3) == 2) { step(ph2{}, t); --t; }
-        if ((t & 3) == 1) { step(ph1{}, t); --t; }
         for (; t >= 4; t -= 4) {
             step(ph0{}, t);
-            step(ph3{}, t - 1);
+            step(ph1{}, t - 1);
             step(ph2{}, t - 2);
-            step(ph1{}, t - 3);
+            step(ph3{}, t - 3);
         }
+        if (t >= 1) step(ph0{}, t);
+        if (t >= 2) step(ph1{}, t - 1);
+        if (t >= 3) step(ph2{}, t - 2);
     } else if constexpr (EXACT && kUnroll) {
         int t = T;
         if (t & 1) { step(ph1{}, t); --t; }
