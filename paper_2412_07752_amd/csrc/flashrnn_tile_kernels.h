@@ -211,15 +211,26 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
     // memory system (sequences whose buffers outgrow the last-level cache ran 15 % slower per step, the LSTM 25 %).
     i32x4 pre_next[NCH_IN];
     if constexpr (kLongChain) {
-        const rsrc_t rs2 = make_rsrc(wx_g + (size_t)(T > 1 ? 1 : 0) * wx_step);
+        // (behind each request of the prologue the stores that follow a request in the time loop, dropped ones: see the short chain)
+        auto dropped_stores = [&](const rsrc_t rs, const int count) {
+            for (int x = 0; x < count; ++x) __builtin_amdgcn_raw_buffer_store_b128(i32x4{0, 0, 0, 0}, rs, kDrop, 0, 0);
+        };
 #pragma unroll
-        for (int k2 = 0; k2 < NCH_IN; ++k2) pre_next[k2] = T > 0 ? __builtin_amdgcn_raw_buffer_load_b128(rs2, cin_g[k2], 0, 0) : i32x4{0, 0, 0, 0};
-        if constexpr (kTwoSets) {   // Wx_2 travels in set 0, Wx_3 in set 1
-            const rsrc_t rs3 = make_rsrc(wx_g + (size_t)(T > 2 ? 2 : (T > 0 ? T - 1 : 0)) * wx_step);
+        for (int k2 = 0; k2 < NCH_IN; ++k2) pre_next[k2] = pre[0][k2] = pre[1][k2] = i32x4{0, 0, 0, 0};
+        if (T > 0) {
+            const rsrc_t rs2 = make_rsrc(wx_g + (size_t)(T > 1 ? 1 : 0) * wx_step);
+            if constexpr (kTwoSets) {   // Wx_2 travels in set 0, Wx_3 in set 1
+                const rsrc_t rs3 = make_rsrc(wx_g + (size_t)(T > 2 ? 2 : T - 1) * wx_step);
 #pragma unroll
-            for (int k2 = 0; k2 < NCH_IN; ++k2) {
-                pre[0][k2] = pre_next[k2];
-                pre[1][k2] = T > 0 ? __builtin_amdgcn_raw_buffer_load_b128(rs3, cin_g[k2], 0, 0) : i32x4{0, 0, 0, 0};
+                for (int k2 = 0; k2 < NCH_IN; ++k2) pre[0][k2] = __builtin_amdgcn_raw_buffer_load_b128(rs2, cin_g[k2], 0, 0);
+                dropped_stores(rs2, 2 * PP + NCH_ST);
+#pragma unroll
+                for (int k2 = 0; k2 < NCH_IN; ++k2) pre[1][k2] = __builtin_amdgcn_raw_buffer_load_b128(rs3, cin_g[k2], 0, 0);
+                dropped_stores(rs3, 2 * PP);
+            } else {
+#pragma unroll
+                for (int k2 = 0; k2 < NCH_IN; ++k2) pre_next[k2] = __builtin_amdgcn_raw_buffer_load_b128(rs2, cin_g[k2], 0, 0);
+                dropped_stores(rs2, 2 * PP);
             }
         }
     }
