@@ -596,10 +596,14 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
     auto request = [&](Held& h) {
         const rsrc_t rc = make_rsrc(fc_ptr), rst = make_rsrc(fst_ptr), rdh = make_rsrc(fdh_ptr);
         advance();
+        // (eight waves: the dropped loads -- 17 of 24 per step at 128 units -- cost more issue slots than the exact counts
+        // bring; there only the waves that have chunks of a kind request them, as the direct loads do)
+        constexpr bool kAllWaves = MAXW <= 4;
 #pragma unroll
-        for (int k2 = 0; k2 < NCC; ++k2) h.c[k2] = __builtin_amdgcn_raw_buffer_load_b128(rc, cc_g[k2], 0, 0);
-        h.st = __builtin_amdgcn_raw_buffer_load_b128(rst, cst_g, 0, 0);
-        h.dh = __builtin_amdgcn_raw_buffer_load_b128(rdh, cdh_g, 0, 0);
+        for (int k2 = 0; k2 < NCC; ++k2)
+            if (kAllWaves || c_wave[k2]) h.c[k2] = __builtin_amdgcn_raw_buffer_load_b128(rc, cc_g[k2], 0, 0);
+        if (kAllWaves || st_wave) h.st = __builtin_amdgcn_raw_buffer_load_b128(rst, cst_g, 0, 0);
+        if (kAllWaves || dh_wave) h.dh = __builtin_amdgcn_raw_buffer_load_b128(rdh, cdh_g, 0, 0);
     };
     auto park = [&](const Held& h, const int parity) {   // (the places the direct loads would have written)
         char* img = in_img + parity * L.in_pitch + (uint32_t)w * 1024 + (uint32_t)lane * 16;
