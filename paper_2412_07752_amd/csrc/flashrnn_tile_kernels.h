@@ -415,6 +415,13 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_tile_kernel(const KernelParams 
 // during step t's MFMAs.
 // EXACT: as in the forward kernel (the head has exactly KTW * EBK * 32 / G units: compile-time LDS pitches, and a
 // compile-time step parity with the time loop unrolled by two).
+// 1 KB pieces of an input image of the backward kernel (records | state rows | dh rows, each part rounded up to whole
+// pieces as in tile_lds_bwd) per wave of a head of D units
+constexpr int deep_pieces_per_wave(int BT, int D, int rec_bytes, int nsb) {
+    const int pieces = (BT * D * rec_bytes + 1023) / 1024 + (BT * nsb * D * 4 + 1023) / 1024 + (BT * D * 2 + 1023) / 1024;
+    return (pieces + D / 16 - 1) / (D / 16);
+}
+
 template <int CELL, int KTW, int EBK, int BT, int MAXW, bool EXACT, bool DEEP = false>
 __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams p) {
     using CT = CellTraits<CELL>;
@@ -520,6 +527,39 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
             out_real = row < (uint32_t)BT * GO;
         }
     }
+    // DEEP: the same image filled through registers, by loads that every wave issues in the same number every step (the
+    // compiler counts the memory operations behind a request to wait for it: see request below).  Either every wave issues
+    // the loads of all three kinds, those of a wave without chunks of a kind out of range and dropped (NCC + 2 per wave
+    // and step), or -- kPieces: where the image, a run of 1 KB pieces of 64 chunks, has no more pieces than the
+    // workgroup has waves (heads of exactly 64 or 128 units, 4-row tiles, every cell but the sLSTM) -- wave w moves piece w:
+    // one load per wave and step, at most one of them dropped.  (With two pieces per wave the first way measured faster.)
+    constexpr bool kPieces = EXACT && DEEP && deep_pieces_per_wave(BT, DK / G, (int)REC, NSB) == 1;
+    constexpr int NSL = kPieces ? 1 : NCC + 2;
+    int sl_kind[NSL];        // 0 records, 1 state rows, 2 dh rows, 3 none (wave-uniform)
+    uint32_t sl_g[NSL];      // global byte offset of this lane's chunk of the piece
+    uint32_t sl_l[NSL];      // LDS byte offset of the piece inside the image
+    if constexpr (kPieces) {
+        const uint32_t NW = (uint32_t)D / 16;
+#pragma unroll
+        for (int j = 0; j < NSL; ++j) {
+            const uint32_t off = ((uint32_t)w + j * NW) * 1024u;
+            sl_l[j] = off;
+            sl_kind[j] = off < L.st_off ? 0 : (off < L.dh_off ? 1 : (off < L.in_pitch ? 2 : 3));
+            const uint32_t idx = (off - (sl_kind[j] == 1 ? L.st_off : (sl_kind[j] == 2 ? L.dh_off : 0u))) / 16 + lane;
+            uint32_t g = kDrop;
+            if (sl_kind[j] == 0) {
+                const uint32_t row = idx / cpr_c, ch = unrotated(idx % cpr_c, row, cpr_c), brow = q * BT + row;
+                if (idx < (uint32_t)BT * cpr_c && brow < (uint32_t)B) g = (brow * HD) * REC + ch * 16;
+            } else if (sl_kind[j] == 1) {
+                const uint32_t row = idx / cpr_st, ch = unrotated(idx % cpr_st, row % BT, cpr_st), sidx = row / BT, brow = q * BT + row % BT;
+                if (row < (uint32_t)BT * NSB && brow < (uint32_t)B) g = (SB0 + sidx) * st_state + (brow * HD) * 4 + ch * 16;
+            } else if (sl_kind[j] == 2) {
+                const uint32_t row = idx / cpr_io, ch = unrotated(idx % cpr_io, row, cpr_io), brow = q * BT + row;
+                if (row < (uint32_t)BT && brow < (uint32_t)B) g = (brow * HD) * ESZ + ch * 16;
+            }
+            sl_g[j] = g;
+        }
+    }
     // this lane's places in the images
     // (byte o of slot r's row lies in the chunk at row position rotated(o / 16); a lane's PP values of a state or of dh share
     // a chunk, its PP records need not)
@@ -577,7 +617,7 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
         if (st_wave) load_chunk_to_lds(rst, img + L.st_off, cst_g);
         if (dh_wave) load_chunk_to_lds(rdh, img + L.dh_off, cdh_g);
     };
-    // DEEP (a kernel of its own for heads of up to 64 units, steps of 0.4 us; the host takes it when the inputs exceed the
+    // DEEP (a kernel of its own for heads of up to 128 units, steps of 0.4 to 0.6 us; the host takes it when the inputs exceed the
     // last-level cache and will come from HBM): the same chunks through registers instead, requested SIX steps before their
     // step and written into the image four steps later.  With the loads that write LDS directly the request can only go out
     // once its image is free, two steps before the data is used -- less than the latency of HBM, which these short steps then
@@ -587,31 +627,45 @@ __global__ __launch_bounds__(MAXW * 64) void bwd_tile_kernel(const KernelParams 
     // by a flag, measured slower than either: where the branches join the compiler waits for the requests just issued.
     static_assert(!DEEP || MAXW <= 8, "the deep fetch: heads of up to 128 units");
     constexpr bool kRegFetch = DEEP;
-    struct Held { i32x4 c[NCC], st, dh; };
-    Held held[4];   // the chunks of the steps t = 0, 1, 2, 3 modulo 4
-    // (Every wave issues every load, every step: the offsets of a wave without chunks of a kind are out of range, its loads
-    // are dropped.  The compiler waits for a request by counting the memory operations issued after it; a load or a request
-    // under a condition makes it count the path with the fewest, and the wait for a request four steps old becomes a wait for
-    // the one of the step before.)
+    struct Held { i32x4 v[NSL]; };
+    Held held[4];   // the chunks of the steps t = T, T-1, T-2, T-3 modulo 4
+    // (Every wave issues NSL loads, every step.  The compiler waits for a request by counting the memory operations issued
+    // after it; a load or a request under a condition makes it count the path with the fewest, and the wait for a request four
+    // steps old becomes a wait for the one of the step before.)
     auto request = [&](Held& h) {
-        const rsrc_t rc = make_rsrc(fc_ptr), rst = make_rsrc(fst_ptr), rdh = make_rsrc(fdh_ptr);
-        advance();
-        // (eight waves: the dropped loads -- 17 of 24 per step at 128 units -- cost more issue slots than the exact counts
-        // bring; there only the waves that have chunks of a kind request them, as the direct loads do)
-        constexpr bool kAllWaves = MAXW <= 4;
+        if constexpr (kPieces) {
 #pragma unroll
-        for (int k2 = 0; k2 < NCC; ++k2)
-            if (kAllWaves || c_wave[k2]) h.c[k2] = __builtin_amdgcn_raw_buffer_load_b128(rc, cc_g[k2], 0, 0);
-        if (kAllWaves || st_wave) h.st = __builtin_amdgcn_raw_buffer_load_b128(rst, cst_g, 0, 0);
-        if (kAllWaves || dh_wave) h.dh = __builtin_amdgcn_raw_buffer_load_b128(rdh, cdh_g, 0, 0);
+            for (int j = 0; j < NSL; ++j) {
+                const char* base = sl_kind[j] == 0 ? fc_ptr : (sl_kind[j] == 1 ? fst_ptr : fdh_ptr);
+                h.v[j] = __builtin_amdgcn_raw_buffer_load_b128(make_rsrc(base), sl_g[j], 0, 0);
+            }
+        } else {
+            const rsrc_t rc = make_rsrc(fc_ptr), rst = make_rsrc(fst_ptr), rdh = make_rsrc(fdh_ptr);
+            // (eight waves: the dropped loads -- 17 of 24 per step at 128 units -- cost more issue slots than the exact counts
+            // bring; there only the waves that have chunks of a kind request them, as the direct loads do)
+            constexpr bool kAllWaves = MAXW <= 4;
+#pragma unroll
+            for (int k2 = 0; k2 < NCC; ++k2)
+                if (kAllWaves || c_wave[k2]) h.v[k2] = __builtin_amdgcn_raw_buffer_load_b128(rc, cc_g[k2], 0, 0);
+            if (kAllWaves || st_wave) h.v[NCC] = __builtin_amdgcn_raw_buffer_load_b128(rst, cst_g, 0, 0);
+            if (kAllWaves || dh_wave) h.v[NCC + 1] = __builtin_amdgcn_raw_buffer_load_b128(rdh, cdh_g, 0, 0);
+        }
+        advance();
     };
     auto park = [&](const Held& h, const int parity) {   // (the places the direct loads would have written)
-        char* img = in_img + parity * L.in_pitch + (uint32_t)w * 1024 + (uint32_t)lane * 16;
+        char* img = in_img + parity * L.in_pitch + (uint32_t)lane * 16;
+        if constexpr (kPieces) {
 #pragma unroll
-        for (int k2 = 0; k2 < NCC; ++k2)
-            if (c_wave[k2]) *(i32x4*)(img + (uint32_t)k2 * NT * 16) = h.c[k2];
-        if (st_wave) *(i32x4*)(img + L.st_off) = h.st;
-        if (dh_wave) *(i32x4*)(img + L.dh_off) = h.dh;
+            for (int j = 0; j < NSL; ++j)
+                if (sl_kind[j] != 3) *(i32x4*)(img + sl_l[j]) = h.v[j];
+        } else {
+            img += (uint32_t)w * 1024;
+#pragma unroll
+            for (int k2 = 0; k2 < NCC; ++k2)
+                if (c_wave[k2]) *(i32x4*)(img + (uint32_t)k2 * NT * 16) = h.v[k2];
+            if (st_wave) *(i32x4*)(img + L.st_off) = h.v[NCC];
+            if (dh_wave) *(i32x4*)(img + L.dh_off) = h.v[NCC + 1];
+        }
     };
     float cv[NC][PP], sc[S][PP], sp[S][PP], dh_ext[PP];
     auto take = [&](const int parity) {
