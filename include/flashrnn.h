@@ -181,7 +181,8 @@ int flashrnn_plan(const flashrnn_desc_t* desc, int backward, int* workgroups, in
  * Which kernel family that plan uses, for reports and regression tests: *staged = 1 for the kernels that move
  * global traffic as 16-byte chunks through LDS images (small batch tiles, bf16), 2 for the variant of those that requests
  * its inputs six steps ahead (backward pass of heads of up to 128 units whose inputs exceed the last-level cache; test
- * hook FLASHRNN_DEEP_FETCH = 1 / 0 forces / forbids it), 0 for the kernels whose lanes access global memory themselves; *batch_tile = rows of a batch tile (16, 8 or 4); *split = workgroups per group
+ * hook FLASHRNN_DEEP_FETCH = 1 / 0 allows it whatever the size of the inputs / forbids it, 2 takes it also where the planner's
+ * rules on the number of workgroups exclude it), 0 for the kernels whose lanes access global memory themselves; *batch_tile = rows of a batch tile (16, 8 or 4); *split = workgroups per group
  * (> 1: the head is split over CUs that exchange h / dg every step).  Any out pointer may be NULL.
  */
 int flashrnn_plan_kernel(const flashrnn_desc_t* desc, int backward, int* staged, int* batch_tile, int* split);

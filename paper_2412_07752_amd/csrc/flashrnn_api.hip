@@ -134,7 +134,8 @@ int make_plan(const flashrnn_desc_t* d, int mode, Plan* out) {
                              (double)d->T * d->B * d->NH * d->D;
     // (measured at 12 x 64, T = 1024: up to 165 MB -- LSTM with 8 rows, sLSTM with 5 -- the direct loads are 10 % faster, from
     // 184 MB on -- LSTM with 9 rows -- the deep fetch is)
-    const bool deep = bwd && env_int("FLASHRNN_DEEP_FETCH", bwd_bytes > 172.0 * 1024 * 1024 ? 1 : 0) != 0;
+    const int deep_mode = bwd ? env_int("FLASHRNN_DEEP_FETCH", bwd_bytes > 172.0 * 1024 * 1024 ? 1 : 0) : 0;   // (2: also where the rules below exclude it)
+    const bool deep = deep_mode != 0;
 
     if (force_multi < 1) {
         // Every (batch tile, kernel) pair that can run the shape gets a cost: rounds of workgroups over the CUs
@@ -159,10 +160,10 @@ int make_plan(const flashrnn_desc_t* d, int mode, Plan* out) {
             if (e.exact >= 2 && !deep) continue;
             // (heads of 128 units: the deeper fetch pays only once half of the CUs stream -- GRU 8 x 128 with 64 rows backward
             // -6 %, LSTM 6 x 128 with 128 rows -5 %, with 16 rows +10 %)
-            if (e.exact >= 2 && e.maxw > 4 && d->NH * ((d->B + e.BT - 1) / e.BT) < cus / 2) continue;
+            if (e.exact >= 2 && deep_mode != 2 && e.maxw > 4 && d->NH * ((d->B + e.BT - 1) / e.BT) < cus / 2) continue;
             // (three and more workgroups per CU: they hide each other's latency and the call runs at the bandwidth of HBM; the
             // direct loads are then 4 to 9 % faster -- 12 x 64 with 512 rows, 24 x 32 with 256)
-            if (e.exact >= 2 && d->NH * ((d->B + e.BT - 1) / e.BT) > 2 * cus) continue;
+            if (e.exact >= 2 && deep_mode != 2 && d->NH * ((d->B + e.BT - 1) / e.BT) > 2 * cus) continue;
             size_t smem = (size_t)2 * e.BT * (dk + (bf ? 8 : 4)) * (bf ? 2 : 4);
             if (e.tile == 1 && bwd) {
                 const int nsb = d->cell == FLASHRNN_SLSTM ? 2 : d->cell == FLASHRNN_ELMAN ? 0 : 1, go = d->cell == FLASHRNN_GRU ? G + 1 : G;
