@@ -684,10 +684,11 @@ __global__ __launch_bounds__(MAXW * 64) void fwd_kernel(const KernelParams p) {
                     if constexpr (!MULTI) {
                         write_operand_lds<BF16, PP>(hbuf + (t & 1) * BUF + lds_wr, e0 + 16 * eb, st[eb][0]);
                     } else {
-                        if (t < T) {
-                            const uint32_t cnt = (uint32_t)iter * (uint32_t)T + (uint32_t)t;
-                            publish_tile<BF16, BT, PP>(xr, (cnt & 1u) * xbuf + xgroup, XROW, lm, e_wave, st[0][0], cnt + 1u, p.spread != 0);
-                        }
+                        // (the last step has nobody to hand its h to: its stores are issued all the same, out of range and dropped.
+                        // Under a condition the compiler could no longer count this store among the memory operations behind the
+                        // input prefetch, and the wait for the prefetched inputs below would wait for its acknowledgement as well.)
+                        const uint32_t cnt = (uint32_t)iter * (uint32_t)T + (uint32_t)t;
+                        publish_tile<BF16, BT, PP>(xr, t < T ? (cnt & 1u) * xbuf + xgroup : 0x80000000u, XROW, lm, e_wave, st[0][0], cnt + 1u, p.spread != 0);
                     }
                 }
                 if constexpr (MULTI) FRNN_TRACE_MARK(5);
