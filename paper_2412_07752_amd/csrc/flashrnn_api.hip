@@ -174,11 +174,15 @@ int make_plan(const flashrnn_desc_t* d, int mode, Plan* out) {
             if (smem > kLdsBytes) continue;
             if (e.tile == 1 && kernel_spills(e.fn)) continue;
             const int ng = d->NH * ((d->B + e.BT - 1) / e.BT);
-            const int rounds = (ng + cus - 1) / cus;
-            // (8-row staged tiles, measured at 12 x 64 with 128 and 256 rows: backward 1.45 of a 4-row step, forward 1.6 --
-            // 1.4 when the call saves nothing and writes a third of the bytes --, the sLSTM's forward step, whose point-wise
-            // function is the longest, 2.7)
-            const double rel8 = bwd ? 1.45 : (d->cell == FLASHRNN_SLSTM ? 2.7 : (mode == 2 ? 1.4 : 1.6));
+            // Rounds of workgroups over the CUs.  Small staged workgroups (4 rows, at most 4 waves) share a CU, two and three at a
+            // time, and overlap each other's waits: with more groups than CUs their time grows by 0.62 per CU-load of groups, not by
+            // whole rounds (forward 12 x 64: 1.38 of a single round's time at 1.125 groups per CU, 1.55 at 1.5, 2.6 at 3).
+            const double per_cu = (double)ng / cus;
+            const double rounds = (e.tile == 1 && e.BT == 4 && nw <= 4 && ng > cus) ? 0.7 + 0.62 * per_cu : (double)((ng + cus - 1) / cus);
+            // (8-row staged tiles, measured at 12 x 64 with 96 to 256 rows: backward 1.3 of a 4-row step, forward 1.65 --
+            // 1.25 when the call saves nothing and writes a third of the bytes: 1.48 in one round, 1.12 per round in two --, the
+            // sLSTM's forward step, whose point-wise function is the longest, 2.7)
+            const double rel8 = bwd ? 1.3 : (d->cell == FLASHRNN_SLSTM ? 2.7 : (mode == 2 ? 1.25 : 1.65));
             double rel = e.tile == 1 ? (e.BT == 4 ? 1.0 : rel8) : (e.BT == 4 ? 1.8 : e.BT == 8 ? 3.0 : 6.0);
             // the backward tile kernel splits the contraction over its waves only when the operand reads are
             // many (k-steps x waves); otherwise the second barrier costs more than it saves
