@@ -317,6 +317,14 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
 #pragma unroll
             for (int g = 0; g < G; ++g) acc[g] = OP::mfma(Rf[g][kt], hB[kt], acc[g]);
         FRNN_TRACE_MARK(2);
+        // (short chain: Wx_{t+1}, requested three steps ago, goes to its image here, in the shadow of the last MFMAs, not behind the
+        // point-wise function, where every instruction is on the step's tail; Wx_{t+2} .. Wx_{t+4} stay in flight)
+        if constexpr (!kLongChain) {
+            char* im = in_img + (par ^ 1) * L.in_pitch;
+#pragma unroll
+            for (int k2 = 0; k2 < NCH_IN; ++k2) *(i32x4*)(im + cin_l[k2]) = pre[(PH + 1) & 3][k2];
+        }
+        pin_order();
         // ---- point-wise function; the step's outputs go to their image (they leave for HBM during the next step)
 #pragma unroll
         for (int g = 0; g < G; ++g) compact_tile<BT>(acc[g]);
@@ -348,11 +356,6 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
         write_operand_lds<true, PP>(hbuf + par * BUF + lds_row, e0, st[0]);
 #pragma unroll
         for (int s = 0; s < S; ++s) store_io<false, PP>(oimg + l_st + (uint32_t)s * BT * L.rp_st, 0, st[s]);
-        if constexpr (!kLongChain) {   // park Wx_{t+1} (requested three steps ago); Wx_{t+2} .. Wx_{t+4} stay in flight
-            char* im = in_img + (par ^ 1) * L.in_pitch;
-#pragma unroll
-            for (int k2 = 0; k2 < NCH_IN; ++k2) *(i32x4*)(im + cin_l[k2]) = pre[(PH + 1) & 3][k2];
-        }
 #ifdef FLASHRNN_TRACE
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #endif
