@@ -234,7 +234,13 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
             }
         }
     }
-    char* st_ptr = st_g;   // state slot of the step before the current one (slot 0 is written directly, not through the image)
+    // Short chain (kDefer): the states after step t go to their image at the top of step t+1 (they are still in registers
+    // there, and every LDS write behind the point-wise function is on the step's tail: 12 x 64 forward 0.361 -> 0.327 ms per
+    // 1024 steps), are read back as 16-byte chunks at the top of step t+2 and leave for HBM during that step's chain.  With
+    // a long chain the writes would land between the MFMAs, where the LDS is busy with operand reads (4 x 192: +3 %): there
+    // they stay at the end of step t, and the chunks leave during step t+1.
+    constexpr bool kDefer = !kLongChain;
+    char* st_ptr = st_g;   // state slot t-2 (kDefer) or t-1 of step t (slot 0 is written directly, not through the image)
     char* c_ptr = c_g;     // saved values of the current step
     auto copy_out_store = [&](int j, const i32x4 (&vs)[NCH_ST]) {
         const uint32_t none = j < 1 ? kDrop : 0u;
@@ -269,7 +275,13 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
             const char* im = in_img + par * L.in_pitch + l_in;
 #pragma unroll
             for (int g = 0; g < G; ++g) load_io<true, PP>(im + (uint32_t)g * BT * L.rp_io, 0, wx[g]);
-            copy_out_load(par ^ 1, vs);
+            if constexpr (kDefer) {
+#pragma unroll
+                for (int s = 0; s < S; ++s) store_io<false, PP>(out_img + (par ^ 1) * OUT_PITCH + l_st + (uint32_t)s * BT * L.rp_st, 0, st[s]);   // states after step t-1
+                copy_out_load(par, vs);                                                                                                       // states after step t-2
+            } else {
+                copy_out_load(par ^ 1, vs);   // states after step t-1
+            }
 #pragma unroll
             for (int g = 0; g < G; ++g)     // the bias joins the inputs here, off the step's tail (GRU's candidate bias
 #pragma unroll                      // belongs to the recurrent term that sig(r) multiplies: it stays with y)
@@ -290,7 +302,7 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
         for (int g = 0; g < G; ++g) acc[g] = OP::mfma(Rf[g][0], hB[0], f32x4{0.f, 0.f, 0.f, 0.f});
         pin_order();
         if constexpr (!kLongChain) {
-            copy_out_store(t - 1, vs);
+            copy_out_store(kDefer ? t - 2 : t - 1, vs);
             pin_order();
 #pragma unroll
             for (int kt = 1; kt < (KT < 3 ? KT : 3); ++kt)
@@ -305,7 +317,7 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
 #pragma unroll
             for (int g = 0; g < G; ++g) acc[g] = OP::mfma(Rf[g][2], hB[2], acc[g]);
             pin_order();
-            copy_out_store(t - 1, vs);
+            copy_out_store(kDefer ? t - 2 : t - 1, vs);
             pin_order();
             char* im = in_img + (par ^ 1) * L.in_pitch;
 #pragma unroll
@@ -337,10 +349,9 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
                 else pre_next[k2] = __builtin_amdgcn_raw_buffer_load_b128(rsn, cin_g[k2], 0, 0);
             }
         }
-        char* oimg = out_img + par * OUT_PITCH;
         const rsrc_t rs_c = make_rsrc(c_ptr);
         c_ptr += c_step;
-        st_ptr += st_step;
+        st_ptr += (!kDefer || t >= 2) ? st_step : 0;
 #pragma unroll
         for (int i = 0; i < PP; ++i) {
             float wxi[G], ybi[G], sti[S], cvi[NC];
@@ -354,8 +365,10 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
             store_record<true, CT::RS, NC>(rs_c, voff_c + i * REC, 0, cvi);
         }
         write_operand_lds<true, PP>(hbuf + par * BUF + lds_row, e0, st[0]);
+        if constexpr (!kDefer) {
 #pragma unroll
-        for (int s = 0; s < S; ++s) store_io<false, PP>(oimg + l_st + (uint32_t)s * BT * L.rp_st, 0, st[s]);
+            for (int s = 0; s < S; ++s) store_io<false, PP>(out_img + par * OUT_PITCH + l_st + (uint32_t)s * BT * L.rp_st, 0, st[s]);
+        }
 #ifdef FLASHRNN_TRACE
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #endif
@@ -387,9 +400,18 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
         if (t + 1 <= T) step(ph2{}, t + 1);
         if (t + 2 <= T) step(ph3{}, t + 2);
     }
-    // ---- drain: outputs of step T
+    // ---- drain: the states after step T are in their image -- or (kDefer) those after step T-1, and those after step T still in registers
     if (T > 0) {
         i32x4 vs[NCH_ST];
+        if constexpr (kDefer) {
+#pragma unroll
+            for (int s = 0; s < S; ++s) store_io<false, PP>(out_img + (T & 1) * OUT_PITCH + l_st + (uint32_t)s * BT * L.rp_st, 0, st[s]);
+            st_ptr = st_g + (size_t)(T - 1) * st_step;
+            copy_out_load((T & 1) ^ 1, vs);
+            copy_out_store(T - 1, vs);
+            __syncthreads();
+            st_ptr += st_step;
+        }
         copy_out_load(T & 1, vs);
         copy_out_store(T, vs);
     }
