@@ -241,7 +241,15 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
     // they stay at the end of step t, and the chunks leave during step t+1.
     constexpr bool kDefer = !kLongChain;
     char* st_ptr = st_g;   // state slot t-2 (kDefer) or t-1 of step t (slot 0 is written directly, not through the image)
-    char* c_ptr = c_g;     // saved values of the current step
+    char* c_ptr = c_g;     // saved values of the current step (kDefer: of the step before, whose records leave at the top of this one)
+    // (the saved values too, for heads of up to 64 units -- kDeferRec: 12 x 64 with 64 rows forward 0.388 -> 0.360 ms per 1024
+    // steps; with eight waves the GRU lost 5 % by it and the LSTM gained 3: left at the end of the step there)
+    constexpr bool kDeferRec = kDefer && MAXW <= 4;
+    float cv_keep[PP][CT::NC];   // kDeferRec: the saved values of the step before
+#pragma unroll
+    for (int i = 0; i < PP; ++i)
+#pragma unroll
+        for (int c2 = 0; c2 < CT::NC; ++c2) cv_keep[i][c2] = 0.0f;
     auto copy_out_store = [&](int j, const i32x4 (&vs)[NCH_ST]) {
         const uint32_t none = j < 1 ? kDrop : 0u;
         const rsrc_t rs_st = make_rsrc(st_ptr);
@@ -276,6 +284,12 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
 #pragma unroll
             for (int g = 0; g < G; ++g) load_io<true, PP>(im + (uint32_t)g * BT * L.rp_io, 0, wx[g]);
             if constexpr (kDefer) {
+                if constexpr (kDeferRec) {   // the saved values of step t-1 leave here as well: packing and storing them is off the tail too
+                    const rsrc_t rs_prev = make_rsrc(c_ptr);
+                    c_ptr += t >= 2 ? c_step : 0;
+#pragma unroll
+                    for (int i = 0; i < PP; ++i) store_record<true, CT::RS, NC>(rs_prev, (voff_c + i * REC) | (t < 2 ? kDrop : 0u), 0, cv_keep[i]);
+                }
 #pragma unroll
                 for (int s = 0; s < S; ++s) store_io<false, PP>(out_img + (par ^ 1) * OUT_PITCH + l_st + (uint32_t)s * BT * L.rp_st, 0, st[s]);   // states after step t-1
                 copy_out_load(par, vs);                                                                                                       // states after step t-2
@@ -350,7 +364,7 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
             }
         }
         const rsrc_t rs_c = make_rsrc(c_ptr);
-        c_ptr += c_step;
+        if constexpr (!kDeferRec) c_ptr += c_step;
         st_ptr += (!kDefer || t >= 2) ? st_step : 0;
 #pragma unroll
         for (int i = 0; i < PP; ++i) {
@@ -362,7 +376,12 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
             Cell<CELL, true>::fwd(wxi, ybi, sti, cvi);
 #pragma unroll
             for (int s = 0; s < S; ++s) st[s][i] = sti[s];
-            store_record<true, CT::RS, NC>(rs_c, voff_c + i * REC, 0, cvi);
+            if constexpr (kDeferRec) {
+#pragma unroll
+                for (int c2 = 0; c2 < NC; ++c2) cv_keep[i][c2] = cvi[c2];
+            } else {
+                store_record<true, CT::RS, NC>(rs_c, voff_c + i * REC, 0, cvi);
+            }
         }
         write_operand_lds<true, PP>(hbuf + par * BUF + lds_row, e0, st[0]);
         if constexpr (!kDefer) {
@@ -404,6 +423,11 @@ __device__ __forceinline__ void fwd_tile_body(const KernelParams& p) {
     if (T > 0) {
         i32x4 vs[NCH_ST];
         if constexpr (kDefer) {
+            if constexpr (kDeferRec) {
+                const rsrc_t rs_last = make_rsrc(c_g + (size_t)(T - 1) * c_step);   // the saved values of step T
+#pragma unroll
+                for (int i = 0; i < PP; ++i) store_record<true, CT::RS, NC>(rs_last, voff_c + i * REC, 0, cv_keep[i]);
+            }
 #pragma unroll
             for (int s = 0; s < S; ++s) store_io<false, PP>(out_img + (T & 1) * OUT_PITCH + l_st + (uint32_t)s * BT * L.rp_st, 0, st[s]);
             st_ptr = st_g + (size_t)(T - 1) * st_step;
